@@ -1,0 +1,117 @@
+/* qoq_w4a8.h -- C ABI of the MI355X (gfx950) W4A8 GEMM with progressive group quantization.
+ *
+ * Method: QoQ / QServe, arXiv 2405.04532.  Section 4.1 (progressive group quantization,
+ * Eq. 3-4, protective range), Section 5.2 (W4A8 GEMM: weights stored in consumption order,
+ * UINT4->INT8 dequantization in registers, INT8 matrix cores, FP16 scaling in the epilogue;
+ * Eq. 5-7 for the per-channel variant), Section 6.1 (per-token symmetric INT8 activations).
+ *
+ * Conventions for every call
+ *   - "dev" pointers are DEVICE pointers owned by the caller; the library keeps no reference
+ *     after the call's work has run.  Nothing is copied to or from the host.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Work is only
+ *     enqueued on it; no call synchronizes, except where stated.
+ *   - Weights are [N, K] row-major, N = output channels, K = input channels (the paper's
+ *     n x k code tensors).  Activations are [M, K] row-major, one row per token.
+ *   - Shapes: K % 128 == 0 (group size g = 128 along k), N % 64 == 0, M >= 0.
+ *     Device pointers must be 16-byte aligned.
+ *   - Return value: QOQ_OK or an error code; on error nothing was enqueued and no output
+ *     was touched.  Errors are never reported any other way (no abort, no exception).
+ *   - The library allocates no device memory.  Scratch comes from the caller's `workspace`.
+ */
+#ifndef QOQ_W4A8_H
+#define QOQ_W4A8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QOQ_OK = 0,
+    QOQ_ERR_NULL = 1,       /* a required pointer is NULL */
+    QOQ_ERR_SHAPE = 2,      /* M, N, K or mode outside the supported set */
+    QOQ_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned */
+    QOQ_ERR_WORKSPACE = 4,  /* workspace missing or smaller than qoq_gemm_workspace_bytes */
+    QOQ_ERR_ARCH = 5,       /* current device is not gfx950 */
+    QOQ_ERR_HIP = 6         /* a HIP runtime call failed (launch error) */
+} qoq_status;
+
+typedef enum {
+    QOQ_GROUP128 = 0,       /* Section 4.1: INT8 per channel, then UINT4 per group of 128 */
+    QOQ_PER_CHANNEL = 1     /* Section 5.2.2: UINT4 + zero point + FP16 scale per channel */
+} qoq_mode;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* qoq_status_string(int status);
+
+/* Size in bytes of the packed-weight blob for an [N, K] layer; 0 if the shape is unsupported. */
+size_t qoq_packed_bytes(int64_t N, int64_t K, int mode);
+
+/* Bytes of workspace qoq_w4a8_gemm / qoq_w4a8_gemm_i32 need for this problem (may be 0). */
+size_t qoq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int mode);
+
+/* Offline weight path (Section 4.1 Eq. 3-4, Section 5.2.1): quantize FP16 weights and store
+ * them in the order the GEMM consumes them.
+ *   w_fp16_dev  [N, K] FP16, row-major (read only)
+ *   packed_dev  qoq_packed_bytes(N, K, mode) bytes (written; opaque, self-describing header)
+ * QOQ_GROUP128: level 1 s0[n] = fp16(max_k|W|/119), q0 = round(W/s0) in [-119, 119];
+ *               level 2 per 128 consecutive k: s1 = ceil(range/15) (range widened to hold 0),
+ *               z = round(-min/s1), Q = clamp(round(q0/s1 + z), 0, 15).  Ties round away from 0.
+ * QOQ_PER_CHANNEL: sw[n] = fp16(range/15), z = round(-min/sw), Q = clamp(round(W/sw + z), 0, 15).
+ * Inputs must be finite. */
+int qoq_pack_weights(const void* w_fp16_dev, int64_t N, int64_t K, int mode,
+                     void* packed_dev, void* stream);
+
+/* Same packing from already-quantized tensors (codes produced elsewhere), all dev pointers:
+ *   q_u4   [N, K]      one code 0..15 per byte
+ *   s1_u8  [N, K/128]  level-2 scales (1..16; QOQ_GROUP128 only, else NULL)
+ *   z_u8   [N, K/128]  level-2 zeros 0..15   (QOQ_PER_CHANNEL: [N])
+ *   s_fp16 [N]         s0 (QOQ_GROUP128) or sw (QOQ_PER_CHANNEL)
+ * Every (Q - z) * s1 must lie in [-128, 127] (guaranteed by the protective range). */
+int qoq_pack_quantized(const uint8_t* q_u4, const uint8_t* s1_u8, const uint8_t* z_u8,
+                       const void* s_fp16, int64_t N, int64_t K, int mode,
+                       void* packed_dev, void* stream);
+
+/* Inverse of the packing, for tests and debugging: logical tensors out of a blob, same
+ * shapes as qoq_pack_quantized (s1_u8 may be NULL in per-channel mode). */
+int qoq_unpack_weights(const void* packed_dev, int64_t N, int64_t K, int mode,
+                       uint8_t* q_u4, uint8_t* s1_u8, uint8_t* z_u8, void* s_fp16, void* stream);
+
+/* Per-token symmetric INT8 activation quantization (Section 6.1; Eq. 1 symmetric form):
+ *   x_fp16_dev [M, K] FP16 in;  qx [M, K] INT8 out, sx_fp16 [M] out with
+ *   sx = fp16(max_k|x|/127) (1.0 for an all-zero row), qx = round(x/sx) in [-127, 127].
+ *   rowsum [M] INT32 = sum_k qx (nullable; the per-channel GEMM needs it, Eq. 6).
+ *   tx [M] FP32 = sum_k x, the t_X of Eq. 7 (nullable). */
+int qoq_quant_act_per_token(const void* x_fp16_dev, int64_t M, int64_t K,
+                            int8_t* qx, void* sx_fp16, int32_t* rowsum, float* tx, void* stream);
+
+/* W4A8 GEMM (Section 5.2): out[m, n] = fp16( acc[m, n] * sx[m] * s[n] ) with
+ *   QOQ_GROUP128:    acc = sum_k qx[m,k] * ((Q[n,k] - z[n,g]) * s1[n,g]),  s = s0
+ *   QOQ_PER_CHANNEL: acc = sum_k qx[m,k] * Q[n,k] - z[n] * rowsum[m],      s = sw  (Eq. 6)
+ * accumulated exactly in INT32; the scaling is done in FP32 and rounded once to FP16.
+ *   qx [M, K] INT8, sx_fp16 [M], rowsum [M] INT32 (per-channel only, else may be NULL),
+ *   packed = blob of qoq_pack_weights for the same N, K, mode, out_fp16 [M, N] row-major.
+ *   workspace: >= qoq_gemm_workspace_bytes(M, N, K, mode) bytes, 16-byte aligned (may be NULL
+ *   if that size is 0).  Its contents are scratch before and after the call; two calls that
+ *   share a workspace must be ordered on one stream. */
+int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum,
+                  const void* packed, int64_t M, int64_t N, int64_t K, int mode,
+                  void* out_fp16, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Debug twin of qoq_w4a8_gemm: same main loop, returns the raw INT32 accumulators acc[M, N]
+ * (per-channel: already zero-corrected) instead of scaling them. */
+int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packed,
+                      int64_t M, int64_t N, int64_t K, int mode,
+                      int32_t* acc, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Test/tuning hook: force the GEMM launch configuration instead of the built-in heuristic.
+ * tile_m in {0 (auto), 16, 32, 64, 128}; split_k >= 0 (0 = auto).  Process-wide; returns
+ * QOQ_ERR_SHAPE for values outside the set. */
+int qoq_set_gemm_config(int tile_m, int split_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QOQ_W4A8_H */

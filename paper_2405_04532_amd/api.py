@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libqoq_w4a8.so (same names as include/qoq_w4a8.h).
+
+Argument marshalling only: torch owns device memory and streams, every step of the path
+runs in the library's HIP kernels.  There is no fallback: if the library is not built or
+a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqoq_w4a8.so")
+
+QOQ_GROUP128 = 0
+QOQ_PER_CHANNEL = 1
+GROUP = 128
+
+_lib = None
+
+_SIGNATURES = {
+    "qoq_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "qoq_packed_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
+    "qoq_gemm_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
+    "qoq_pack_weights": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                        ctypes.c_void_p, ctypes.c_void_p]),
+    "qoq_pack_quantized": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.c_void_p]),
+    "qoq_unpack_weights": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p]),
+    "qoq_quant_act_per_token": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "qoq_w4a8_gemm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "qoq_w4a8_gemm_i32": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "qoq_set_gemm_config": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+}
+
+EXPORTS = tuple(_SIGNATURES)
+
+
+class QoqError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(message)
+        self.status = status
+
+
+def lib():
+    """Load the built library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2405_04532_amd.build` first")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def status_string(status):
+    return lib().qoq_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise QoqError(status, status_string(status))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(device):
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+    return t
+
+
+def packed_bytes(N, K, mode=QOQ_GROUP128):
+    return int(lib().qoq_packed_bytes(N, K, mode))
+
+
+def gemm_workspace_bytes(M, N, K, mode=QOQ_GROUP128):
+    return int(lib().qoq_gemm_workspace_bytes(M, N, K, mode))
+
+
+def set_gemm_config(tile_m=0, split_k=0):
+    _check(lib().qoq_set_gemm_config(tile_m, split_k))
+
+
+def pack_weights(w, mode=QOQ_GROUP128, out=None):
+    """FP16 weights [N, K] on the GPU -> packed blob (uint8 tensor)."""
+    _dev(w, torch.float16, "w")
+    N, K = w.shape
+    size = packed_bytes(N, K, mode)
+    if size == 0:
+        _check(2)
+    blob = out if out is not None else torch.empty(size, dtype=torch.uint8, device=w.device)
+    _check(lib().qoq_pack_weights(_ptr(w), N, K, mode, _ptr(blob), _stream(w.device)))
+    return blob
+
+
+def pack_quantized(q, s1, z, s, mode=QOQ_GROUP128):
+    """Already-quantized tensors (uint8 codes [N,K], uint8 s1/z, FP16 scales) -> packed blob."""
+    _dev(q, torch.uint8, "q")
+    N, K = q.shape
+    size = packed_bytes(N, K, mode)
+    if size == 0:
+        _check(2)
+    blob = torch.zeros(size, dtype=torch.uint8, device=q.device)
+    _check(lib().qoq_pack_quantized(_ptr(q), _ptr(s1), _ptr(z), _ptr(s), N, K, mode, _ptr(blob), _stream(q.device)))
+    return blob
+
+
+def unpack_weights(blob, N, K, mode=QOQ_GROUP128):
+    """Packed blob -> (codes uint8 [N,K], s1 uint8 [N,K/128] or None, z uint8, scales FP16 [N])."""
+    dev = blob.device
+    q = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    s = torch.empty(N, dtype=torch.float16, device=dev)
+    if mode == QOQ_GROUP128:
+        s1 = torch.empty((N, K // GROUP), dtype=torch.uint8, device=dev)
+        z = torch.empty((N, K // GROUP), dtype=torch.uint8, device=dev)
+    else:
+        s1 = None
+        z = torch.empty(N, dtype=torch.uint8, device=dev)
+    _check(lib().qoq_unpack_weights(_ptr(blob), N, K, mode, _ptr(q), _ptr(s1), _ptr(z), _ptr(s), _stream(dev)))
+    return q, s1, z, s
+
+
+def quant_act_per_token(x, want_rowsum=True, want_tx=False):
+    """FP16 activations [M, K] -> (qx int8 [M,K], sx FP16 [M], rowsum int32 [M] | None, tx FP32 [M] | None)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    qx = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    sx = torch.empty(M, dtype=torch.float16, device=x.device)
+    rowsum = torch.empty(M, dtype=torch.int32, device=x.device) if want_rowsum else None
+    tx = torch.empty(M, dtype=torch.float32, device=x.device) if want_tx else None
+    _check(lib().qoq_quant_act_per_token(_ptr(x), M, K, _ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(tx), _stream(x.device)))
+    return qx, sx, rowsum, tx
+
+
+def _workspace(M, N, K, mode, device, workspace):
+    need = gemm_workspace_bytes(M, N, K, mode)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, (workspace.numel() * workspace.element_size() if workspace is not None else 0)
+
+
+def w4a8_gemm(qx, sx, packed, N, mode=QOQ_GROUP128, rowsum=None, out=None, workspace=None):
+    """out[M, N] FP16 = W4A8 GEMM of INT8 activations with a packed weight blob."""
+    _dev(qx, torch.int8, "qx")
+    M, K = qx.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=qx.device)
+    workspace, ws_bytes = _workspace(M, N, K, mode, qx.device, workspace)
+    _check(lib().qoq_w4a8_gemm(_ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(packed), M, N, K, mode, _ptr(out),
+                               _ptr(workspace), ws_bytes, _stream(qx.device)))
+    return out
+
+
+def w4a8_gemm_i32(qx, packed, N, mode=QOQ_GROUP128, rowsum=None, out=None, workspace=None):
+    """Raw INT32 accumulators [M, N] of the same GEMM (debug entry)."""
+    _dev(qx, torch.int8, "qx")
+    M, K = qx.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=qx.device)
+    workspace, ws_bytes = _workspace(M, N, K, mode, qx.device, workspace)
+    _check(lib().qoq_w4a8_gemm_i32(_ptr(qx), _ptr(rowsum), _ptr(packed), M, N, K, mode, _ptr(out),
+                                   _ptr(workspace), ws_bytes, _stream(qx.device)))
+    return out

@@ -1,0 +1,164 @@
+// C-ABI layer: argument validation, error codes and dispatch.  No kernel code here.
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include <atomic>
+
+#include "../../include/qoq_w4a8.h"
+#include "qoq_internal.h"
+
+namespace {
+
+std::atomic<int> g_forced_tile_m{0};
+std::atomic<int> g_forced_split_k{0};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// 1 = gfx950, 0 = something else, cached per device (the query is slow).
+int arch_ok()
+{
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int c = cache[dev].load();
+    if (c == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        c = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 2;
+        cache[dev].store(c);
+    }
+    return c == 1;
+}
+
+int check_shape(int64_t N, int64_t K, int mode) { return qoq::shape_ok(N, K, mode) ? QOQ_OK : QOQ_ERR_SHAPE; }
+
+int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const void* packed, int64_t M, int64_t N,
+                int64_t K, int mode, void* out16, int32_t* out32, void* ws, size_t ws_bytes, void* stream)
+{
+    if (check_shape(N, K, mode) != QOQ_OK || M < 0 || M > (1 << 24)) return QOQ_ERR_SHAPE;
+    if (M * N >= ((int64_t)1 << 40)) return QOQ_ERR_SHAPE;
+    if (M == 0) return QOQ_OK;  // empty batch: nothing to do
+    if (!qx || !packed || (!out16 && !out32) || (out16 && !sx)) return QOQ_ERR_NULL;
+    if (mode == QOQ_PER_CHANNEL && !rowsum) return QOQ_ERR_NULL;
+    if (!aligned16(qx) || !aligned16(packed) || !aligned16(out16) || !aligned16(out32) || !aligned16(ws))
+        return QOQ_ERR_ALIGN;
+    int tile_m, split_k;
+    qoq::pick_gemm_config(M, N, K, g_forced_tile_m.load(), g_forced_split_k.load(), tile_m, split_k);
+    if (split_k > 1) {
+        const size_t need = (size_t)M * (size_t)N * sizeof(int32_t);
+        if (!ws || ws_bytes < need) return QOQ_ERR_WORKSPACE;
+    }
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    qoq::GemmArgs a;
+    a.qx = qx; a.sx = sx; a.rowsum = rowsum; a.blob = static_cast<const uint8_t*>(packed);
+    a.M = M; a.N = N; a.K = K; a.mode = mode;
+    a.out_fp16 = out16; a.out_i32 = out32; a.workspace = static_cast<int32_t*>(ws);
+    a.tile_m = tile_m; a.split_k = split_k;
+    return qoq::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* qoq_status_string(int status)
+{
+    switch (status) {
+        case QOQ_OK: return "QOQ_OK";
+        case QOQ_ERR_NULL: return "QOQ_ERR_NULL: a required pointer is NULL";
+        case QOQ_ERR_SHAPE: return "QOQ_ERR_SHAPE: unsupported M/N/K/mode (need K % 128 == 0, N % 64 == 0)";
+        case QOQ_ERR_ALIGN: return "QOQ_ERR_ALIGN: pointer not 16-byte aligned";
+        case QOQ_ERR_WORKSPACE: return "QOQ_ERR_WORKSPACE: workspace missing or too small";
+        case QOQ_ERR_ARCH: return "QOQ_ERR_ARCH: device is not gfx950";
+        case QOQ_ERR_HIP: return "QOQ_ERR_HIP: HIP runtime error";
+        default: return "QOQ_ERR_UNKNOWN";
+    }
+}
+
+size_t qoq_packed_bytes(int64_t N, int64_t K, int mode)
+{
+    if (!qoq::shape_ok(N, K, mode)) return 0;
+    return qoq::make_layout(N, K, mode).total;
+}
+
+size_t qoq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int mode)
+{
+    if (!qoq::shape_ok(N, K, mode) || M <= 0) return 0;
+    int tile_m, split_k;
+    qoq::pick_gemm_config(M, N, K, g_forced_tile_m.load(), g_forced_split_k.load(), tile_m, split_k);
+    return split_k > 1 ? (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+}
+
+int qoq_set_gemm_config(int tile_m, int split_k)
+{
+    if (!(tile_m == 0 || tile_m == 16 || tile_m == 32 || tile_m == 64 || tile_m == 128) || split_k < 0)
+        return QOQ_ERR_SHAPE;
+    g_forced_tile_m.store(tile_m);
+    g_forced_split_k.store(split_k);
+    return QOQ_OK;
+}
+
+int qoq_pack_weights(const void* w_fp16_dev, int64_t N, int64_t K, int mode, void* packed_dev, void* stream)
+{
+    if (check_shape(N, K, mode) != QOQ_OK) return QOQ_ERR_SHAPE;
+    if (!w_fp16_dev || !packed_dev) return QOQ_ERR_NULL;
+    if (!aligned16(w_fp16_dev) || !aligned16(packed_dev)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    const qoq::BlobLayout L = qoq::make_layout(N, K, mode);
+    return qoq::launch_pack_weights(w_fp16_dev, L, static_cast<uint8_t*>(packed_dev),
+                                    static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_pack_quantized(const uint8_t* q_u4, const uint8_t* s1_u8, const uint8_t* z_u8, const void* s_fp16, int64_t N,
+                       int64_t K, int mode, void* packed_dev, void* stream)
+{
+    if (check_shape(N, K, mode) != QOQ_OK) return QOQ_ERR_SHAPE;
+    if (!q_u4 || !z_u8 || !s_fp16 || !packed_dev || (mode == QOQ_GROUP128 && !s1_u8)) return QOQ_ERR_NULL;
+    if (!aligned16(packed_dev)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    const qoq::BlobLayout L = qoq::make_layout(N, K, mode);
+    return qoq::launch_pack_quantized(q_u4, s1_u8, z_u8, s_fp16, L, static_cast<uint8_t*>(packed_dev),
+                                      static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_unpack_weights(const void* packed_dev, int64_t N, int64_t K, int mode, uint8_t* q_u4, uint8_t* s1_u8,
+                       uint8_t* z_u8, void* s_fp16, void* stream)
+{
+    if (check_shape(N, K, mode) != QOQ_OK) return QOQ_ERR_SHAPE;
+    if (!packed_dev || !q_u4 || !z_u8 || !s_fp16 || (mode == QOQ_GROUP128 && !s1_u8)) return QOQ_ERR_NULL;
+    if (!aligned16(packed_dev)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    const qoq::BlobLayout L = qoq::make_layout(N, K, mode);
+    return qoq::launch_unpack(static_cast<const uint8_t*>(packed_dev), L, q_u4, s1_u8, z_u8, s_fp16,
+                              static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_quant_act_per_token(const void* x_fp16_dev, int64_t M, int64_t K, int8_t* qx, void* sx_fp16, int32_t* rowsum,
+                            float* tx, void* stream)
+{
+    if (M < 0 || M > (1 << 24) || K <= 0 || (K % qoq::kGroup) != 0 || K > (1 << 24)) return QOQ_ERR_SHAPE;
+    if (M == 0) return QOQ_OK;  // empty batch: nothing to do
+    if (!x_fp16_dev || !qx || !sx_fp16) return QOQ_ERR_NULL;
+    if (!aligned16(x_fp16_dev) || !aligned16(qx)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_act_quant(x_fp16_dev, M, K, qx, sx_fp16, rowsum, tx, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum, const void* packed, int64_t M,
+                  int64_t N, int64_t K, int mode, void* out_fp16, void* workspace, size_t workspace_bytes,
+                  void* stream)
+{
+    if (!out_fp16 && M != 0) return QOQ_ERR_NULL;
+    return gemm_common(qx, sx_fp16, rowsum, packed, M, N, K, mode, out_fp16, nullptr, workspace, workspace_bytes,
+                       stream);
+}
+
+int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packed, int64_t M, int64_t N, int64_t K,
+                      int mode, int32_t* acc, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!acc && M != 0) return QOQ_ERR_NULL;
+    return gemm_common(qx, nullptr, rowsum, packed, M, N, K, mode, nullptr, acc, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+// Internal launch interfaces between the C-ABI layer and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qoq_layout.h"
+
+namespace qoq {
+
+// qoq_pack.hip
+hipError_t launch_pack_weights(const void* w_fp16, const BlobLayout& L, uint8_t* blob, hipStream_t s);
+hipError_t launch_pack_quantized(const uint8_t* q, const uint8_t* s1, const uint8_t* z, const void* s_fp16,
+                                 const BlobLayout& L, uint8_t* blob, hipStream_t s);
+hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* q, uint8_t* s1, uint8_t* z,
+                         void* s_fp16, hipStream_t s);
+
+// qoq_act.hip
+hipError_t launch_act_quant(const void* x_fp16, int64_t M, int64_t K, int8_t* qx, void* sx, int32_t* rowsum,
+                            float* tx, hipStream_t s);
+
+// qoq_gemm.hip
+struct GemmArgs {
+    const int8_t* qx;
+    const void* sx;          // FP16 [M] (null for the INT32 entry)
+    const int32_t* rowsum;   // INT32 [M], per-channel mode
+    const uint8_t* blob;
+    int64_t M, N, K;
+    int mode;
+    void* out_fp16;          // [M, N] FP16, or null
+    int32_t* out_i32;        // [M, N] INT32, or null
+    int32_t* workspace;      // [M, N] INT32 partial sums when split_k > 1
+    int tile_m;              // 16, 32, 64, 128
+    int split_k;             // >= 1
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+// Launch configuration the library picks for a problem (also sizes the workspace).
+void pick_gemm_config(int64_t M, int64_t N, int64_t K, int forced_tile_m, int forced_split_k,
+                      int& tile_m, int& split_k);
+
+}  // namespace qoq

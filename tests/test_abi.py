@@ -1,0 +1,116 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-only entry
+points and argument validation behave as documented (no GPU compute calls)."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "qoq_w4a8.h")
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2405_04532_amd import api as a
+    if not os.path.exists(a.LIB_PATH):
+        from paper_2405_04532_amd import build
+        build.build()
+    return a
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qoq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_exports_match_header(api):
+    names = _declared()
+    assert len(names) >= 10
+    handle = api.lib()
+    for n in names:
+        assert hasattr(handle, n), n
+    assert set(names) == set(api.EXPORTS)
+
+
+def test_header_compiles_as_c():
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", HEADER])
+
+
+def test_packed_bytes_and_status(api):
+    assert api.packed_bytes(256, 256) >= 256 * 256 // 2 + 256 * 2 * 2 + 256 * 2
+    assert api.packed_bytes(256, 256) % 256 == 0
+    # algorithmic size plus at most the 0.5-byte-per-group metadata padding and section alignment
+    n, k = 4096, 4096
+    algo = n * k // 2 + n * (k // 128) * 3 // 2 + 2 * n
+    assert algo <= api.packed_bytes(n, k) <= algo + n * (k // 128) // 2 + 2048
+    assert api.packed_bytes(256, 100) == 0 and api.packed_bytes(100, 256) == 0 and api.packed_bytes(256, 256, 7) == 0
+    assert api.packed_bytes(256, 256, api.QOQ_PER_CHANNEL) >= 256 * 128 + 256 * 3
+    assert api.status_string(0) == "QOQ_OK"
+    assert "SHAPE" in api.status_string(2) and "UNKNOWN" in api.status_string(99)
+
+
+def test_argument_validation_without_gpu(api):
+    L = api.lib()
+    buf = (ctypes.c_uint8 * 64)()
+    p = ctypes.addressof(buf)
+    p = (p + 15) & ~15
+    assert L.qoq_pack_weights(p, 256, 100, 0, p, None) == 2       # K % 128
+    assert L.qoq_pack_weights(p, 100, 256, 0, p, None) == 2       # N % 64
+    assert L.qoq_pack_weights(None, 256, 256, 0, p, None) == 1
+    assert L.qoq_pack_weights(p + 4, 256, 256, 0, p, None) == 3
+    assert L.qoq_quant_act_per_token(p, 4, 100, p, p, None, None, None) == 2
+    assert L.qoq_quant_act_per_token(None, 4, 128, p, p, None, None, None) == 1
+    assert L.qoq_quant_act_per_token(None, 0, 128, None, None, None, None, None) == 0   # empty batch
+    assert L.qoq_w4a8_gemm(p, p, None, p, 4, 256, 256, 3, p, None, 0, None) == 2
+    assert L.qoq_w4a8_gemm(p, p, None, p, 4, 256, 256, 1, p, None, 0, None) == 1        # per-channel needs rowsum
+    assert L.qoq_w4a8_gemm(p, p, None, p, 0, 256, 256, 0, p, None, 0, None) == 0        # M = 0
+    assert L.qoq_w4a8_gemm(p, p, None, p, 4, 256, 256, 0, None, None, 0, None) == 1
+    assert L.qoq_w4a8_gemm_i32(p, None, p, 4, 256, 256, 0, p + 8, None, 0, None) == 3
+    assert L.qoq_set_gemm_config(48, 0) == 2 and L.qoq_set_gemm_config(0, 0) == 0
+    # split-k problems must come with a workspace
+    assert api.gemm_workspace_bytes(16, 256, 4096) == 16 * 256 * 4
+    assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, None, 0, None) == 4
+    assert api.gemm_workspace_bytes(4096, 4096, 4096) == 0
+
+
+def test_layout_is_a_bijection(tmp_path):
+    """Host logic of the packed layout: (n, k) -> (byte, nibble) is one-to-one and onto."""
+    src = tmp_path / "t.cpp"
+    src.write_text(r'''
+#include <cstdio>
+#include <set>
+#include <utility>
+#include "qoq_layout.h"
+int main() {
+  const long N = 128, K = 384, G = K / 128;
+  std::set<std::pair<size_t,int>> seen;
+  for (long n = 0; n < N; ++n) {
+    long nf; int i; qoq::phys_row(n, nf, i);
+    if (qoq::logical_row(nf, i) != n || i < 0 || i > 15 || nf < 0 || nf >= N / 16) return 1;
+    for (long k = 0; k < K; ++k) {
+      int sh; size_t off = qoq::code_dword_offset(nf, i, k / 128, G, (int)(k % 128), sh);
+      if (off % 4 || off >= (size_t)N * K / 2 || sh % 4 || sh > 28) return 2;
+      if (!seen.insert({off, sh}).second) return 3;
+    }
+  }
+  if (seen.size() != (size_t)N * K) return 4;
+  // one lane's 16 bytes hold 32 codes of ONE row and ONE group: k_local = kb*16+t and 64+kb*16+t
+  for (int kb = 0; kb < 4; ++kb) for (int t = 0; t < 16; ++t) for (int s = 0; s < 2; ++s) {
+    int sh; size_t off = qoq::code_dword_offset(3, 5, 1, G, s * 64 + kb * 16 + t, sh);
+    size_t lane_base = ((size_t)(3 * G + 1) * 64 + (size_t)(kb * 16 + 5)) * 16;
+    if (off < lane_base || off >= lane_base + 16 || (int)((off - lane_base) / 8) != s) return 5;
+  }
+  qoq::BlobLayout L = qoq::make_layout(4096, 4096, 0);
+  if (L.codes_off % 256 || L.meta_off % 256 || L.scale_off % 256 || L.total % 256) return 6;
+  if (L.meta_off < L.codes_off + (size_t)4096 * 4096 / 2) return 7;
+  printf("ok\n");
+  return 0;
+}
+''')
+    exe = tmp_path / "t"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "paper_2405_04532_amd", "csrc"),
+                           str(src), "-o", str(exe)])
+    assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "ok"

@@ -1,0 +1,240 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle, element by
+element, on the same seeded inputs.  Integer results (codes, scales' bit patterns, INT8
+activations, INT32 accumulators) must be bit-exact; the FP16 output must satisfy
+|gpu - ref64| <= 1e-3*|ref64| + 2^-24 against the oracle's FP64 epilogue."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gemm as ogemm
+from oracle import qoq_quant as qq
+from paper_2405_04532_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2405_04532_amd import api as a
+    a.lib()
+    a.set_gemm_config(0, 0)
+    yield a
+    a.set_gemm_config(0, 0)
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def check_fp16(out_gpu, ref64):
+    got = _np(out_gpu).astype(np.float64)
+    tol = 1e-3 * np.abs(ref64) + 2.0 ** -24
+    bad = np.abs(got - ref64) > tol
+    assert not bad.any(), f"{int(bad.sum())} outputs outside tolerance, worst {np.abs(got - ref64).max()}"
+
+
+def rand_inputs(M, N, K, seed, zero_row=True):
+    w = wl.make_weights(N, K, seed, DEV, outlier_count=max(1, N // 100))
+    x = wl.make_activations(M, K, seed, DEV, outlier_count=max(1, K // 100)) if M else \
+        torch.empty((0, K), dtype=torch.float16, device=DEV)
+    if zero_row and N >= 128:
+        w[5] = 0                      # all-zero channel
+        w[7, :128] = 0.03125          # constant group
+    if zero_row and M >= 4:
+        x[2] = 0                      # all-zero token
+    return w, x
+
+
+# ---------------------------------------------------------------------------- weight path
+@pytest.mark.parametrize("N,K", [(256, 256), (64, 128), (320, 1152)])
+def test_pack_group_matches_oracle(api, N, K):
+    w, _ = rand_inputs(0, N, K, seed=N + K)
+    blob = api.pack_weights(w, api.QOQ_GROUP128)
+    q, s1, z, s0 = api.unpack_weights(blob, N, K, api.QOQ_GROUP128)
+    ref = qq.progressive_quant(_np(w))
+    assert (_np(s0).view(np.uint16) == ref["s0"].view(np.uint16)).all()
+    assert (_np(s1).astype(np.int64) == ref["s1"]).all()
+    assert (_np(z).astype(np.int64) == ref["z"]).all()
+    assert (_np(q).astype(np.int64) == ref["Q"]).all()
+
+
+@pytest.mark.parametrize("N,K", [(256, 256), (192, 640)])
+def test_pack_per_channel_matches_oracle(api, N, K):
+    w, _ = rand_inputs(0, N, K, seed=N + K + 1)
+    w[3] = w[3].abs()
+    blob = api.pack_weights(w, api.QOQ_PER_CHANNEL)
+    q, _, z, sw = api.unpack_weights(blob, N, K, api.QOQ_PER_CHANNEL)
+    code, zr, swr = qq.per_channel_quant(_np(w))
+    assert (_np(sw).view(np.uint16) == swr.view(np.uint16)).all()
+    assert (_np(z).astype(np.int64) == zr).all()
+    assert (_np(q).astype(np.int64) == code).all()
+
+
+def test_pack_quantized_roundtrip(api):
+    rng = np.random.default_rng(3)
+    N, K = 128, 384
+    q0 = rng.integers(-119, 120, size=(N, K))
+    code, s1, z = qq.level2_quant(q0)
+    s0 = (rng.random(N) * 0.01 + 0.001).astype(np.float16)
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a.astype(dt))).to(DEV)
+    blob = api.pack_quantized(t(code, np.uint8), t(s1, np.uint8), t(z, np.uint8), t(s0, np.float16))
+    q, s1g, zg, s0g = api.unpack_weights(blob, N, K)
+    assert (_np(q) == code).all() and (_np(s1g) == s1).all() and (_np(zg) == z).all()
+    assert (_np(s0g).view(np.uint16) == s0.view(np.uint16)).all()
+
+
+# ---------------------------------------------------------------------------- activations
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008)])
+def test_act_quant_matches_oracle(api, M, K):
+    _, x = rand_inputs(M, 64, K, seed=M * 7 + K)
+    qx, sx, rowsum, tx = api.quant_act_per_token(x, want_rowsum=True, want_tx=True)
+    rqx, rsx, rrow, rtx = qq.act_quant(_np(x))
+    assert (_np(sx).view(np.uint16) == rsx.view(np.uint16)).all()
+    assert (_np(qx).astype(np.int64) == rqx).all()
+    assert (_np(rowsum).astype(np.int64) == rrow).all()
+    assert np.allclose(_np(tx), rtx, rtol=1e-4, atol=1e-2)
+
+
+def test_act_quant_ties_round_away(api):
+    """Rows made of exact half-integer multiples of the scale: every tie rounds away from 0."""
+    vals = np.concatenate([np.arange(-127, 128) + 0.5, [127.0, -127.0]])[:256] * 2.0 ** -6
+    vals[vals > 127 * 2.0 ** -6] = 127 * 2.0 ** -6
+    x = torch.from_numpy(vals.astype(np.float16)[None, :]).to(DEV)
+    qx, sx, _, _ = api.quant_act_per_token(x)
+    rqx, rsx, _, _ = qq.act_quant(_np(x))
+    assert (_np(sx).view(np.uint16) == rsx.view(np.uint16)).all() and (_np(qx) == rqx).all()
+
+
+# ---------------------------------------------------------------------------- GEMM
+def run_group_case(api, M, N, K, seed, tile_m=0, split_k=0):
+    w, x = rand_inputs(M, N, K, seed)
+    ref = ogemm.forward_group(_np(w), _np(x))
+    blob = api.pack_weights(w, api.QOQ_GROUP128)
+    qx, sx, _, _ = api.quant_act_per_token(x)
+    api.set_gemm_config(tile_m, split_k)
+    try:
+        acc = api.w4a8_gemm_i32(qx, blob, N)
+        out = api.w4a8_gemm(qx, sx, blob, N)
+        torch.cuda.synchronize()
+    finally:
+        api.set_gemm_config(0, 0)
+    assert (_np(qx).astype(np.int64) == ref["qx"]).all()
+    assert (_np(acc).astype(np.int64) == ref["acc"]).all(), f"INT32 mismatch M={M} N={N} K={K} tile={tile_m} split={split_k}"
+    check_fp16(out, ref["out64"])
+
+
+def test_config0_tiny(api):
+    """M=16, K=256, N=256, seed 0 with 2 outlier output channels and 4 outlier input channels."""
+    w, x = wl.config0(DEV)
+    ref = ogemm.forward_group(_np(w), _np(x))
+    blob = api.pack_weights(w)
+    qx, sx, _, _ = api.quant_act_per_token(x)
+    acc = api.w4a8_gemm_i32(qx, blob, 256)
+    out = api.w4a8_gemm(qx, sx, blob, 256)
+    assert (_np(acc).astype(np.int64) == ref["acc"]).all()
+    check_fp16(out, ref["out64"])
+    # stricter: at most one FP16 ulp from the oracle's own FP16 rounding
+    a = _np(out).view(np.int16).astype(np.int64)
+    b = ref["out"].view(np.int16).astype(np.int64)
+    assert np.abs(a - b).max() <= 1
+
+
+@pytest.mark.parametrize("M", [1, 8, 17, 63, 64, 100, 130, 257])
+def test_group_ragged_m(api, M):
+    run_group_case(api, M, 320, 640, seed=100 + M)
+
+
+@pytest.mark.parametrize("tile_m,split_k", [(16, 1), (32, 1), (64, 1), (128, 1), (16, 3), (64, 5), (128, 2), (32, 9)])
+def test_group_forced_variants(api, tile_m, split_k):
+    run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
+
+
+def test_group_several_tiles_all_axes(api):
+    run_group_case(api, 300, 1088, 2048, seed=11)
+
+
+def _pack_logical(api, code, s1, z, s0):
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a.astype(dt))).to(DEV)
+    return api.pack_quantized(t(code, np.uint8), t(s1, np.uint8), t(z, np.uint8), t(s0, np.float16))
+
+
+def test_one_hot_operands_pin_fragment_maps(api):
+    """One-hot activations select single weights: checks the (n, k) <-> lane/byte maps of the
+    packed layout and the MFMA operand order independently of any averaging."""
+    N, K, M = 128, 256, 48
+    rng = np.random.default_rng(5)
+    q0 = rng.integers(-119, 120, size=(N, K))
+    code, s1, z = qq.level2_quant(q0)
+    w_hat = qq.level2_dequant(code, s1, z)
+    blob = _pack_logical(api, code, s1, z, np.ones(N, np.float16))
+    qx = np.zeros((M, K), dtype=np.int8)
+    ks = rng.permutation(K)[:M]
+    qx[np.arange(M), ks] = 1
+    acc = api.w4a8_gemm_i32(torch.from_numpy(qx).to(DEV), blob, N)
+    assert (_np(acc).astype(np.int64) == w_hat[:, ks].T).all()
+
+
+def test_extreme_magnitudes_fit_int32(api):
+    """All activations 127 against the largest representable weights, K = 28672."""
+    N, K, M = 64, 28672, 16
+    code = np.full((N, K), 15)
+    code[1::2] = 0
+    s1 = np.full((N, K // 128), 16)
+    z = np.full((N, K // 128), 8)          # w_hat = (15-8)*16 = 112 or (0-8)*16 = -128
+    blob = _pack_logical(api, code, s1, z, np.ones(N, np.float16))
+    qx = torch.full((M, K), 127, dtype=torch.int8, device=DEV)
+    qx[1::2] = -127
+    acc = _np(api.w4a8_gemm_i32(qx, blob, N)).astype(np.int64)
+    ref = ogemm.gemm_i64(_np(qx), qq.level2_dequant(code, s1, z))
+    assert np.abs(ref).max() == 127 * 128 * K and (acc == ref).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 256, 256), (70, 192, 640), (200, 448, 1152)])
+def test_per_channel_gemm(api, M, N, K):
+    w, x = rand_inputs(M, N, K, seed=M + N)
+    ref = ogemm.forward_per_channel(_np(w), _np(x))
+    blob = api.pack_weights(w, api.QOQ_PER_CHANNEL)
+    qx, sx, rowsum, _ = api.quant_act_per_token(x)
+    for tile_m, split_k in [(0, 0), (32, 3), (128, 1)]:
+        api.set_gemm_config(tile_m, split_k)
+        try:
+            acc = api.w4a8_gemm_i32(qx, blob, N, api.QOQ_PER_CHANNEL, rowsum=rowsum)
+            out = api.w4a8_gemm(qx, sx, blob, N, api.QOQ_PER_CHANNEL, rowsum=rowsum)
+        finally:
+            api.set_gemm_config(0, 0)
+        assert (_np(acc).astype(np.int64) == ref["acc"]).all()
+        check_fp16(out, ref["out64"])
+
+
+def test_repeated_launches_are_identical(api):
+    """Double-buffer hazards would show as run-to-run differences."""
+    w, x = rand_inputs(96, 512, 2048, seed=21)
+    blob = api.pack_weights(w)
+    qx, sx, _, _ = api.quant_act_per_token(x)
+    first = api.w4a8_gemm_i32(qx, blob, 512).clone()
+    for _ in range(5):
+        assert torch.equal(api.w4a8_gemm_i32(qx, blob, 512), first)
+
+
+def test_empty_batch(api):
+    w, _ = rand_inputs(0, 64, 128, seed=1, zero_row=False)
+    blob = api.pack_weights(w)
+    x = torch.empty((0, 128), dtype=torch.float16, device=DEV)
+    qx, sx, _, _ = api.quant_act_per_token(x)
+    out = api.w4a8_gemm(qx, sx, blob, 64)
+    assert out.shape == (0, 64)
+
+
+def test_runtime_errors_leave_outputs_untouched(api):
+    w, x = rand_inputs(16, 256, 4096, seed=2)
+    blob = api.pack_weights(w)
+    qx, sx, _, _ = api.quant_act_per_token(x)
+    out = torch.full((16, 256), 7.0, dtype=torch.float16, device=DEV)
+    tiny = torch.empty(16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(api.QoqError) as e:
+        api.w4a8_gemm(qx, sx, blob, 256, out=out, workspace=tiny)
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
