@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8 GEMM hot path on one MI355X.
+
+Default workload (`llama2_7b_decode_m64`): the four Llama-2-7B-shaped linear layers (fused
+QKV, O-proj, fused gate+up, down) at M = 64 tokens, group size 128, seeded synthetic FP16
+weights/activations with 1% outlier channels.  One step = one pass over the four layers;
+each layer runs per-token activation quantization, then the W4A8 GEMM (weights are packed
+once, offline, before the timed region).  Several independently packed copies of the layer
+set are rotated so the weights of a step come from HBM, not from the 256 MB Infinity Cache,
+as they do when a whole model's layers stream through.
+
+Prints ONE JSON line: effective TOPS (2*M*K*N summed over the layers / step time), the HBM
+roofline of the GEMM launch, and the CPU oracle timed on the host cores as a baseline.
+`--sweep FILE` additionally writes per-layer, per-M timings of every configuration family.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5033.0     # MI355X dense INT8 matrix, published (5.0 POP/s)
+
+
+def algorithmic_bytes(M, N, K, mode=0):
+    """Bytes the GEMM must move: packed codes, level-2 metadata (1.5 B per group), FP16
+    channel scales, INT8 activations with their FP16 scales, FP16 output."""
+    meta = 1.5 * N * (K // 128) if mode == 0 else N
+    return K * N / 2 + meta + 2 * N + M * K + 2 * M + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--m", type=int, default=64, help="tokens per step (default workload: 64)")
+    ap.add_argument("--copies", type=int, default=8, help="independently packed layer sets rotated per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", type=str, default=None, help="also write a per-layer/per-M table to this file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(see DESIGN.md for how the path would shard)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2405_04532_amd import api, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    api.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    M = args.m
+    layers = list(wl.LLAMA2_7B.items())          # name -> (K, N)
+
+    # ---- setup (untimed): weights packed offline, activations resident in HBM
+    blobs = {name: [] for name, _ in layers}
+    for name, (K, N) in layers:
+        w = wl.layer_weights("llama2_7b", name, 1, dev)
+        first = api.pack_weights(w)
+        blobs[name].append(first)
+        for _ in range(args.copies - 1):
+            blobs[name].append(first.clone())
+        del w
+    xs = {name: wl.layer_activations("llama2_7b", name, M, 1, dev) for name, _ in layers}
+    bufs = {}
+    for name, (K, N) in layers:
+        bufs[name] = dict(
+            qx=torch.empty((M, K), dtype=torch.int8, device=dev),
+            sx=torch.empty(M, dtype=torch.float16, device=dev),
+            out=torch.empty((M, N), dtype=torch.float16, device=dev),
+            ws=api.new_workspace(api.gemm_workspace_bytes(M, N, K), dev))
+    L = api.lib()
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    P = lambda t: t.data_ptr()
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(api.status_string(rc))
+
+    def gemm_only(step):
+        for name, (K, N) in layers:
+            b = bufs[name]
+            check(L.qoq_w4a8_gemm(P(b["qx"]), P(b["sx"]), None, P(blobs[name][step % args.copies]), M, N, K, 0,
+                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), sp))
+
+    def full_step(step):
+        for name, (K, N) in layers:
+            b = bufs[name]
+            check(L.qoq_quant_act_per_token(P(xs[name]), M, K, P(b["qx"]), P(b["sx"]), None, None, sp))
+            check(L.qoq_w4a8_gemm(P(b["qx"]), P(b["sx"]), None, P(blobs[name][step % args.copies]), M, N, K, 0,
+                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), sp))
+
+    def timed(fn, steps, warmup):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(steps):
+            fn(warmup + i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps      # ms per step
+
+    ms_step = timed(full_step, args.steps, args.warmup)
+    ms_gemm = timed(gemm_only, args.steps, args.warmup)   # the four GEMM launches alone
+
+    ops = sum(2.0 * M * K * N for _, (K, N) in layers)
+    byts = sum(algorithmic_bytes(M, N, K) for _, (K, N) in layers)
+    tops = ops / (ms_step * 1e-3) / 1e12
+    gemm_gbs = byts / (ms_gemm * 1e-3) / 1e9
+    gemm_tops = ops / (ms_gemm * 1e-3) / 1e12
+
+    result = {
+        "metric": "W4A8 GEMM effective TOPS (Llama-2-7B-shaped layers, M=%d, g128)" % M,
+        "value": round(tops, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "llama2_7b_decode_m%d" % M, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
+                   "M": M, "group": 128, "mode": "group128", "weight_copies_rotated": args.copies,
+                   "step": "4 x (qoq_quant_act_per_token + qoq_w4a8_gemm)"},
+        "roofline": {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "qoq_w4a8_gemm launch (average over the four layers)",
+                     "avg_launch_us": round(ms_gemm * 1e3 / len(layers), 3),
+                     "algorithmic_bytes_per_launch": round(byts / len(layers)),
+                     "gemm_only_tops": round(gemm_tops, 3),
+                     "int8_mfma_frac": round(gemm_tops / INT8_PEAK_TOPS, 4)},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(M, xs, wl)
+
+    if args.sweep:
+        sweep(args.sweep, api, wl, dev)
+
+    print(json.dumps(result))
+
+
+def cpu_baseline(M, xs, wl):
+    """The CPU oracle as it stands on a bounded sample of the same workload: the O-proj and
+    QKV layers at the same M (activation quantization + INT8 GEMM in int64 + FP64 epilogue);
+    weights are quantized by the oracle beforehand, untimed, like the offline packing."""
+    import numpy as np
+
+    from oracle import gemm as ogemm
+    from oracle import qoq_quant as qq
+
+    sample = ["o", "qkv"]
+    prepared = []
+    for name in sample:
+        K, N = wl.LLAMA2_7B[name]
+        w = wl.layer_weights("llama2_7b", name, 1, "cuda:0").cpu().numpy()
+        wq = qq.progressive_quant(w)
+        prepared.append((name, K, N, np.ascontiguousarray(wq["w_hat"].astype(np.int8)), wq["s0"],
+                         xs[name].cpu().numpy()))
+        del w, wq
+    ogemm.gemm_i64(np.zeros((1, 128), np.int8), np.zeros((1, 128), np.int8))   # load the library
+    t0 = time.perf_counter()
+    ops = 0.0
+    for name, K, N, w_hat, s0, x in prepared:
+        qx, sx, _, _ = qq.act_quant(x)
+        acc = ogemm.gemm_i64(qx, w_hat)
+        qq.output_fp16(acc, sx, s0)
+        ops += 2.0 * M * K * N
+    dt = time.perf_counter() - t0
+    return {"value": round(ops / dt / 1e12, 6), "unit": "TOPS", "cores": ogemm.num_threads(), "kind": "oracle",
+            "sample": "layers %s at M=%d, one pass (%.2f s)" % ("+".join(sample), M, dt)}
+
+
+def sweep(path, api, wl, dev):
+    """Per-layer timings over M for the three layer families (GEMM launch only, rotated copies)."""
+    import torch
+    rows = []
+    fams = [("llama2_7b", wl.LLAMA2_7B, 0, (1, 8, 32, 64, 128, 256, 512, 1024, 2048, 4096)),
+            ("llama3_70b", wl.LLAMA3_70B, 0, (512, 2048)),
+            ("llama3_8b", wl.LLAMA3_8B, 1, (64, 1024))]
+    stream = torch.cuda.current_stream()
+    for fam, shapes, mode, ms in fams:
+        for name, (K, N) in shapes.items():
+            w = wl.layer_weights(fam, name, 2, dev)
+            blob0 = api.pack_weights(w, mode)
+            del w
+            copies = max(1, min(8, int(600e6 // blob0.numel())))
+            blobs = [blob0] + [blob0.clone() for _ in range(copies - 1)]
+            for M in ms:
+                x = wl.layer_activations(fam, name, M, 2, dev)
+                qx, sx, rowsum, _ = api.quant_act_per_token(x)
+                out = torch.empty((M, N), dtype=torch.float16, device=dev)
+                ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, mode), dev)
+                reps = 20 if M >= 1024 else 50
+                for i in range(5):
+                    api.w4a8_gemm(qx, sx, blobs[i % copies], N, mode, rowsum=rowsum, out=out, workspace=ws)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for i in range(reps):
+                    api.w4a8_gemm(qx, sx, blobs[i % copies], N, mode, rowsum=rowsum, out=out, workspace=ws)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                ops = 2.0 * M * K * N
+                byts = algorithmic_bytes(M, N, K, mode)
+                rows.append({"family": fam, "layer": name, "mode": mode, "M": M, "K": K, "N": N, "us": round(us, 2),
+                             "tops": round(ops / us / 1e6, 2), "mfma_frac": round(ops / us / 1e6 / INT8_PEAK_TOPS, 4),
+                             "gbs": round(byts / us / 1e3, 1), "hbm_frac": round(byts / us / 1e3 / HBM_PEAK_GBS, 4)})
+                del x, qx, sx, out, ws
+            del blobs, blob0
+            torch.cuda.empty_cache()
+    os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
+    with open(path, "w") as f:
+        for r in rows:
+            f.write(json.dumps(r) + "\n")
+
+
+if __name__ == "__main__":
+    main()

@@ -49,8 +49,15 @@ const char* qoq_status_string(int status);
 /* Size in bytes of the packed-weight blob for an [N, K] layer; 0 if the shape is unsupported. */
 size_t qoq_packed_bytes(int64_t N, int64_t K, int mode);
 
-/* Bytes of workspace qoq_w4a8_gemm / qoq_w4a8_gemm_i32 need for this problem (may be 0). */
+/* Bytes of workspace qoq_w4a8_gemm / qoq_w4a8_gemm_i32 need for this problem (may be 0;
+ * always a multiple of 16).  Used for split-k: per-tile arrival counters and partial tiles. */
 size_t qoq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int mode);
+
+/* Zero-fill a workspace (dev pointer, 16-byte aligned, size a multiple of 16) on `stream`.
+ * A workspace must be zero-filled ONCE after allocation, before its first GEMM call: the
+ * GEMM relies on its arrival counters being zero on entry and leaves them zero on exit, so
+ * later calls need no further preparation (and no memset appears on the hot path). */
+int qoq_gemm_workspace_prepare(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Offline weight path (Section 4.1 Eq. 3-4, Section 5.2.1): quantize FP16 weights and store
  * them in the order the GEMM consumes them.
@@ -94,8 +101,9 @@ int qoq_quant_act_per_token(const void* x_fp16_dev, int64_t M, int64_t K,
  *   qx [M, K] INT8, sx_fp16 [M], rowsum [M] INT32 (per-channel only, else may be NULL),
  *   packed = blob of qoq_pack_weights for the same N, K, mode, out_fp16 [M, N] row-major.
  *   workspace: >= qoq_gemm_workspace_bytes(M, N, K, mode) bytes, 16-byte aligned (may be NULL
- *   if that size is 0).  Its contents are scratch before and after the call; two calls that
- *   share a workspace must be ordered on one stream. */
+ *   if that size is 0), zero-filled once with qoq_gemm_workspace_prepare.  One workspace may
+ *   serve any sequence of calls of any shapes it is large enough for, as long as they are
+ *   ordered on one stream; calls that overlap in time need separate workspaces. */
 int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum,
                   const void* packed, int64_t M, int64_t N, int64_t K, int mode,
                   void* out_fp16, void* workspace, size_t workspace_bytes, void* stream);
@@ -107,8 +115,10 @@ int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packe
                       int32_t* acc, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Test/tuning hook: force the GEMM launch configuration instead of the built-in heuristic.
- * tile_m in {0 (auto), 16, 32, 64, 128}; split_k >= 0 (0 = auto).  Process-wide; returns
- * QOQ_ERR_SHAPE for values outside the set. */
+ * tile_m in {0 (auto), 16, 32, 64 (streaming kernel), 128 (tiled kernel)}.  split_k >= 0
+ * (0 = auto): for the tiled kernel the number of k-slices per output tile, for the streaming
+ * kernel the number of workgroups the stream of work units is dealt to.  Process-wide; returns
+ * QOQ_ERR_SHAPE for values outside the set.  Workspace sizes depend on it. */
 int qoq_set_gemm_config(int tile_m, int split_k);
 
 #ifdef __cplusplus

@@ -22,6 +22,7 @@ _SIGNATURES = {
     "qoq_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "qoq_packed_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
     "qoq_gemm_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
+    "qoq_gemm_workspace_prepare": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_pack_weights": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                         ctypes.c_void_p, ctypes.c_void_p]),
     "qoq_pack_quantized": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -151,10 +152,18 @@ def quant_act_per_token(x, want_rowsum=True, want_tx=False):
     return qx, sx, rowsum, tx
 
 
+def new_workspace(nbytes, device):
+    """Allocate a GEMM workspace and zero-fill it with the library's own kernel."""
+    nbytes = (int(nbytes) + 15) // 16 * 16
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    _check(lib().qoq_gemm_workspace_prepare(_ptr(ws), ws.numel(), _stream(device)))
+    return ws
+
+
 def _workspace(M, N, K, mode, device, workspace):
     need = gemm_workspace_bytes(M, N, K, mode)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        workspace = new_workspace(need, device)
     return workspace, (workspace.numel() * workspace.element_size() if workspace is not None else 0)
 
 

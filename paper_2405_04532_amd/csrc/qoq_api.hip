@@ -12,6 +12,8 @@ namespace {
 std::atomic<int> g_forced_tile_m{0};
 std::atomic<int> g_forced_split_k{0};
 
+qoq::GemmTuning forced() { return {g_forced_tile_m.load(), g_forced_split_k.load()}; }
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // 1 = gfx950, 0 = something else, cached per device (the query is slow).
@@ -43,16 +45,15 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     if (!aligned16(qx) || !aligned16(packed) || !aligned16(out16) || !aligned16(out32) || !aligned16(ws))
         return QOQ_ERR_ALIGN;
     int tile_m, split_k;
-    qoq::pick_gemm_config(M, N, K, g_forced_tile_m.load(), g_forced_split_k.load(), tile_m, split_k);
-    if (split_k > 1) {
-        const size_t need = (size_t)M * (size_t)N * sizeof(int32_t);
-        if (!ws || ws_bytes < need) return QOQ_ERR_WORKSPACE;
-    }
+    qoq::pick_gemm_config(M, N, K, forced(), tile_m, split_k);
+    if ((uint64_t)M * (uint64_t)K >= ((uint64_t)1 << 32)) return QOQ_ERR_SHAPE;  // 32-bit activation offsets
+    const size_t need = qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
+    if (need && (!ws || ws_bytes < need)) return QOQ_ERR_WORKSPACE;
     if (!arch_ok()) return QOQ_ERR_ARCH;
     qoq::GemmArgs a;
     a.qx = qx; a.sx = sx; a.rowsum = rowsum; a.blob = static_cast<const uint8_t*>(packed);
     a.M = M; a.N = N; a.K = K; a.mode = mode;
-    a.out_fp16 = out16; a.out_i32 = out32; a.workspace = static_cast<int32_t*>(ws);
+    a.out_fp16 = out16; a.out_i32 = out32; a.workspace = ws;
     a.tile_m = tile_m; a.split_k = split_k;
     return qoq::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
@@ -85,8 +86,18 @@ size_t qoq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int mode)
 {
     if (!qoq::shape_ok(N, K, mode) || M <= 0) return 0;
     int tile_m, split_k;
-    qoq::pick_gemm_config(M, N, K, g_forced_tile_m.load(), g_forced_split_k.load(), tile_m, split_k);
-    return split_k > 1 ? (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+    qoq::pick_gemm_config(M, N, K, forced(), tile_m, split_k);
+    return qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
+}
+
+int qoq_gemm_workspace_prepare(void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (workspace_bytes == 0) return QOQ_OK;
+    if (!workspace) return QOQ_ERR_NULL;
+    if (!aligned16(workspace) || (workspace_bytes & 15u)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_zero(workspace, workspace_bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK
+                                                                                                        : QOQ_ERR_HIP;
 }
 
 int qoq_set_gemm_config(int tile_m, int split_k)

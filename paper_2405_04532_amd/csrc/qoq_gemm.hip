@@ -12,10 +12,28 @@
 //     range keeps every byte in [1, 255]), and one XOR turns the +128 bias into two's
 //     complement.  The per-channel variant feeds the codes unchanged and folds the zero
 //     point into the epilogue through the token's row sum (Eq. 6).
-//   * activations: INT8 tile staged through LDS in operand-fragment order (conflict-free
-//     128-bit reads), double buffered, one barrier per group of 128 k.
-//   * small M: grid-level split-k with exact INT32 atomics into the workspace, then a
-//     scaling pass (Section 5.2.4 mentions split-k for small m).
+//   * two kernels.  "stream" (M <= 64, memory bound): a multi-stage pipeline of direct
+//     global->LDS copies (the asynchronous-copy, multi-stage software pipeline of Section 5.2.4 in
+//     its gfx950 form) over a balanced, stream-k style partition of the work.
+//       - Work unit = one quantization group of one 64-channel block (4 KiB of packed weights).
+//         The N/64 * K/128 units are dealt out in equal contiguous runs to about one workgroup
+//         per CU, whatever the layer shape; a run may start and end in the middle of a block.
+//       - HBM latency under load is about 1.5 us here, so some 50 KiB per CU must be in
+//         flight.  Each of eight consumer waves (fragment f, group parity e) copies the units
+//         it will itself consume into a private 8-deep LDS ring: no barrier guards the weights.
+//         Activations come from L2 and need far less lead, but a wave's outstanding loads retire
+//         in order, so a wave issuing both would stall its deep weight prefetch on every
+//         activation wait.  A ninth wave therefore copies the activation slabs, level-2 metadata
+//         and channel scales three iterations ahead; one barrier per iteration (two groups)
+//         publishes them.  Copies are issued from inline assembly and waited for with explicit
+//         s_waitcnt vmcnt(n): the compiler's own bookkeeping would wait for ALL outstanding
+//         copies before every LDS read.
+//       - A block finished inside one run is scaled and stored at once.  Blocks shared by
+//         several runs meet in the workspace: partial INT32 tiles are written through to
+//         memory, a per-block counter elects the last workgroup to arrive, which adds all
+//         partials (integer sums are exact and order independent) and runs the epilogue.
+//     "tiled" (larger M): 128 x 256 tile, activations staged through LDS in operand-fragment
+//     order, double buffered, one barrier per group; plain split-k with the same counter scheme.
 //   * epilogue (Section 5.2.2): FP32 acc * (sx[m] * s[n]), one rounding to FP16.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
@@ -27,6 +45,14 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Streaming (non-temporal) 128-bit load: weights are read exactly once per GEMM.
+__device__ inline uint4 load_stream(const uint4* ptr)
+{
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ptr));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
@@ -42,10 +68,13 @@ struct GemmDev {
     const int32_t* rowsum;
     __half* out16;
     int32_t* out32;
-    int M, N, K, G, gps;  // gps = groups per k-split
+    int* counters;  // split-k: one per output tile, zero on entry and on exit
+    int4* parts;    // split-k: [tile][split][value][thread]
+    int M, N, K, G, gps, S;  // gps = groups per k-split, S = number of k-splits (tiled kernel)
+    int upw;                 // stream kernel: work units per workgroup
 };
 
-enum { OUT_FP16 = 0, OUT_I32 = 1, OUT_ATOMIC = 2 };
+enum { OUT_FP16 = 0, OUT_I32 = 1 };
 
 __device__ inline uint32_t pk_mad_u16(uint32_t a, uint32_t s, uint32_t b)
 {
@@ -71,8 +100,489 @@ __device__ inline v4i dequant(uint32_t x0, uint32_t x1, uint32_t S, uint32_t B)
     return r;
 }
 
+__device__ inline v4i as_v4i(uint4 t) { return (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w}; }
+
+// Split-k across workgroups.  Every workgroup of a tile stores its CNT int4 values per thread;
+// the last one to arrive (per-tile counter) adds the others' and returns true.
+//
+// Visibility between workgroups (which may sit on different XCDs, each with its own L2) is
+// obtained without device-wide fences: a release/acquire fence pair writes back and
+// invalidates a whole L2 and was measured to cost tens of microseconds per GEMM here.  The
+// partial tiles are instead written and read with relaxed device-scope atomic accesses, which
+// go through to memory past the non-coherent caches; a workgroup waits for its own stores to
+// complete (s_waitcnt) before it bumps the tile's counter with a device-scope atomic, and the
+// last arriver reads the partials only after that atomic has returned.
+__device__ inline void store_coherent(int4* dst, int4 v)
+{
+    int* d = reinterpret_cast<int*>(dst);
+    __hip_atomic_store(d + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(d + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(d + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(d + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline int4 load_coherent(const int4* src)
+{
+    int* s = const_cast<int*>(reinterpret_cast<const int*>(src));
+    int4 v;
+    v.x = __hip_atomic_load(s + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.y = __hip_atomic_load(s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.z = __hip_atomic_load(s + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.w = __hip_atomic_load(s + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+
+// `tid` in [0, 256) indexes the 256 value-holding threads of the tile; threads with
+// active == false only take part in the barriers.
+template <int CNT>
+__device__ inline bool splitk_combine(int4 (&v)[CNT], const GemmDev& p, int tile, int split, int tid, bool active)
+{
+    __shared__ int s_last;
+    if (active) {
+        int4* mine = p.parts + ((size_t)tile * p.S + split) * CNT * kThreads + tid;
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) store_coherent(mine + (size_t)i * kThreads, v[i]);
+    }
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_waitcnt(0);  // every store of this thread has completed at memory
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __syncthreads();                // ... and of every thread of the workgroup
+    if (active && tid == 0)
+        s_last = __hip_atomic_fetch_add(p.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.S - 1;
+    __syncthreads();
+    if (!s_last) return false;
+    if (active) {
+        for (int s = 0; s < p.S; ++s) {
+            if (s == split) continue;
+            const int4* other = p.parts + ((size_t)tile * p.S + s) * CNT * kThreads + tid;
+#pragma unroll
+            for (int i = 0; i < CNT; ++i) {
+                const int4 o = load_coherent(other + (size_t)i * kThreads);
+                v[i].x += o.x; v[i].y += o.y; v[i].z += o.z; v[i].w += o.w;
+            }
+        }
+        if (tid == 0) __hip_atomic_store(p.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return true;
+}
+
+// Epilogue for ROWS consecutive output channels n0.. of token m held in v[0..ROWS).
+template <bool GROUP, int OUT, int ROWS>
+__device__ inline void store_row(const GemmDev& p, int m, int n0, int (&v)[ROWS])
+{
+    static_assert(ROWS == 4 || ROWS == 16, "row segment");
+    if constexpr (!GROUP) {
+        const int rs = p.rowsum[m];
+        uint32_t zw[ROWS / 4];
+        if constexpr (ROWS == 4) {
+            zw[0] = *reinterpret_cast<const uint32_t*>(p.zeros + n0);
+        } else {
+            const uint4 zz = *reinterpret_cast<const uint4*>(p.zeros + n0);
+            zw[0] = zz.x; zw[1] = zz.y; zw[2] = zz.z; zw[3] = zz.w;
+        }
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) v[j] -= (int)((zw[j >> 2] >> (8 * (j & 3))) & 0xFFu) * rs;
+    }
+    if constexpr (OUT == OUT_I32) {
+        int4* dst = reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n0);
+#pragma unroll
+        for (int j = 0; j < ROWS / 4; ++j) dst[j] = make_int4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
+    } else {
+        const float sxm = __half2float(p.sx[m]);
+        const uint32_t* sp = reinterpret_cast<const uint32_t*>(p.scales + n0);
+        uint32_t h[ROWS / 2];
+#pragma unroll
+        for (int j = 0; j < ROWS / 2; ++j) {
+            const uint32_t sw = sp[j];
+            const float s_a = __half2float(__ushort_as_half((unsigned short)(sw & 0xFFFFu)));
+            const float s_b = __half2float(__ushort_as_half((unsigned short)(sw >> 16)));
+            const __half a = __float2half_rn((float)v[2 * j] * (sxm * s_a));
+            const __half b = __float2half_rn((float)v[2 * j + 1] * (sxm * s_b));
+            h[j] = (uint32_t)__half_as_ushort(a) | ((uint32_t)__half_as_ushort(b) << 16);
+        }
+        if constexpr (ROWS == 4) {
+            *reinterpret_cast<uint2*>(p.out16 + (size_t)m * p.N + n0) = make_uint2(h[0], h[1]);
+        } else {
+            uint4* dst = reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n0);
+            dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
+            dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// "stream" kernel: 16*MF <= 64 tokens; nine waves; grid = (workgroups, m-tiles).
+// Consumer wave c = 2*f + e handles fragment f of the current 64-channel block and, in each
+// iteration, the group of parity e of a pair of consecutive groups.
+// ------------------------------------------------------------------------------------------
+
+// Direct global -> LDS copy, 16 (or 4) bytes per lane; lane l lands at lds_addr + 16*l (4*l).
+// `base` is wave-uniform, `voff` the lane's byte offset.  Opaque to the compiler on purpose.
+// M0 (the copy's LDS base) is a reserved register that nothing else in these kernels uses, so
+// it is not listed as a clobber.
+__device__ __forceinline__ const void* to_sgpr(const void* ptr)   // value is wave-uniform; pin it to scalar registers
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(to_sgpr(base)) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(to_sgpr(base)) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+// Write-through store / cache-bypassing load of 16 bytes (device-coherent without fences).
+__device__ __forceinline__ void store_sc1(int4* ptr, v4i v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(ptr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void load_sc1_nowait(v4i& v, const int4* ptr)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(ptr) : "memory");
+}
+__device__ __forceinline__ void wait_loads(v4i& a, v4i& b, v4i& c, v4i& d)
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) :: "memory");
+}
+
+constexpr int kStreamThreads = 640;  // eight consumer waves + two producer waves
+
+// Walk over a workgroup's run of work units (unit u = block * G + g), two units per iteration.
+// A pair never straddles a block boundary or the end of the run.  Kept to a handful of scalar
+// instructions per step: nine waves execute it every iteration and the scalar unit is shared.
+struct Walk {
+    int block, g;   // first unit of the next iteration
+    int left;       // units left in the current block segment (0 = run exhausted)
+    int rem;        // units of the run after this segment
+};
+__device__ __forceinline__ void walk_init(Walk& w, int u0, int u1, int G)
+{
+    w.block = __builtin_amdgcn_readfirstlane(u0 / G);
+    w.g = u0 - w.block * G;
+    w.left = min(G - w.g, u1 - u0);
+    w.rem = (u1 - u0) - w.left;
+}
+// advance by the iteration's n = min(2, left) units; returns true if that finished the segment
+__device__ __forceinline__ bool walk_step(Walk& w, int n, int G)
+{
+    w.g += n;
+    w.left -= n;
+    if (w.left > 0) return false;
+    if (w.rem > 0) {
+        w.block += 1;
+        w.g = 0;
+        w.left = min(G, w.rem);
+        w.rem -= w.left;
+    }
+    return true;
+}
+
+template <bool GROUP, int OUT>
+__device__ __forceinline__ void finish4(const GemmDev& p, int m, int n0, v4i v, const float (&sn)[4],
+                                        const int (&zn)[4], float sxm, int rs)
+{
+    int t[4] = {v.x, v.y, v.z, v.w};
+    if constexpr (!GROUP) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) t[j] -= zn[j] * rs;
+    }
+    if constexpr (OUT == OUT_I32) {
+        *reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n0) = make_int4(t[0], t[1], t[2], t[3]);
+    } else {
+        uint32_t h[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const __half a = __float2half_rn((float)t[2 * j] * (sxm * sn[2 * j]));
+            const __half b = __float2half_rn((float)t[2 * j + 1] * (sxm * sn[2 * j + 1]));
+            h[j] = (uint32_t)__half_as_ushort(a) | ((uint32_t)__half_as_ushort(b) << 16);
+        }
+        *reinterpret_cast<uint2*>(p.out16 + (size_t)m * p.N + n0) = make_uint2(h[0], h[1]);
+    }
+}
+
 template <int MF, bool GROUP, int OUT>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev p)
+__global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
+{
+    // Weights: every consumer wave owns a deep private ring of 1 KiB units.  Activations, metadata and
+    // scales: shallow rings, one slot per iteration (= two consecutive groups of a block), filled by
+    // the two producer waves (producer k serves the k-th group of the pair).
+    constexpr int kWRing = MF == 4 ? 10 : 12;
+    constexpr int kARing = 3;
+    constexpr int kABlocks = 2 * MF;                                  // 1 KiB blocks (m-fragment, k-step) per group
+    constexpr int kProducerDma0 = kABlocks + (GROUP ? 1 : 0) + 1;     // producer 0 also copies the scales
+    constexpr int kProducerDma1 = kABlocks + (GROUP ? 1 : 0);
+    static_assert(kWRing - 2 < 64 && (kARing - 2) * kProducerDma0 < 64, "vmcnt range");
+    __shared__ uint4 wring[8][kWRing][64];            // private ring of weight units per consumer wave
+    __shared__ uint4 aring[kARing][2][kABlocks * 64]; // activation slabs of the iteration's two groups
+    __shared__ uint4 mring[kARing][2][16];            // level-2 metadata: 4 fragments x 16 rows x uint16
+    __shared__ uint4 sring[kARing][16];               // block's FP16 scales (128 B) and zeros (64 B)
+    __shared__ int4 red[kNFrag * MF * 64];
+    __shared__ float sx_lds[16 * MF];
+    __shared__ int rs_lds[16 * MF];
+    __shared__ int s_flag[2];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool producer = wave >= 8;
+    const int pk = wave & 1;                               // producer: which group of the pair
+    const int f = (wave & 7) >> 1, e = wave & 1;           // consumer: fragment, group parity
+    const int wg = blockIdx.x;
+    const int m0 = blockIdx.y * (16 * MF);
+    const int G = p.G;
+    const int blocks = p.N / 64;
+    const int total = blocks * G;
+    const int u0 = min(total, wg * p.upw), u1 = min(total, u0 + p.upw);
+    if (u0 >= u1) return;                                  // whole workgroup: nothing to do
+    const int q = lane >> 4, ml = lane & 15;
+    const int nf_total = p.N / 16;
+
+    Walk cw;                                               // what is being consumed
+    walk_init(cw, u0, u1, G);
+    Walk iw = cw;                                          // what this wave copies next (runs ahead)
+    const int first_g = cw.g;
+
+    v4i acc[MF];
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf) acc[mf] = (v4i){0, 0, 0, 0};
+
+    // ---- copy roles -----------------------------------------------------------------------
+    // producer: lane 4r+c copies 16-byte chunk c ^ h(r) of row r of a 16-row activation block: a quad
+    // reads one 64-byte row segment; h spreads the rows over the LDS banks for the fragment reads
+    uint32_t a_voff[kABlocks];
+    {
+        const int r = lane >> 2, c = lane & 3;
+        const int h = ((r >> 1) ^ (r >> 2)) & 3;
+#pragma unroll
+        for (int b = 0; b < kABlocks; ++b) {
+            const int row = min(m0 + (b >> 1) * 16 + r, p.M - 1);  // rows past M repeat the last one; never stored
+            a_voff[b] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((b & 1) * 64 + (c ^ h) * 16);
+        }
+    }
+    const uint32_t m_voff = (uint32_t)(lane & 31) * 4u;                      // 128 B of metadata; upper lanes re-read
+    // scales: lanes 0..31 fetch the block's 64 FP16 scales, lanes 32..47 its 64 zero bytes
+    const uint32_t zero_delta = (uint32_t)(reinterpret_cast<const char*>(p.zeros) - reinterpret_cast<const char*>(p.scales));
+    const uint32_t s_voff = (lane < 32 || GROUP) ? (uint32_t)(lane & 31) * 4u : zero_delta + (uint32_t)((lane - 32) & 15) * 4u;
+    const uint32_t s_blk_stride = (lane < 32 || GROUP) ? 128u : 64u;         // bytes per block in either array
+    const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0] + (uint32_t)(wave & 7) * (kWRing * 1024);
+    const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)pk * (kABlocks * 1024);
+    const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * 256;
+    const uint32_t sring_addr = (uint32_t)(uintptr_t)&sring[0][0];
+    constexpr uint32_t kASlot = 2 * kABlocks * 1024;
+    const char* abase = reinterpret_cast<const char*>(p.qx);
+    const char* sbase = reinterpret_cast<const char*>(p.scales);
+    const uint32_t w_voff = (uint32_t)lane * 16u;
+    // per-block base pointers, refreshed only when the walk enters a new block
+    const size_t w_block_stride = (size_t)kNFrag * G * 1024;
+    const char* w_row = reinterpret_cast<const char*>(p.codes) + ((size_t)(iw.block * kNFrag + f) * G) * 1024;
+    const char* m_row = reinterpret_cast<const char*>(p.meta) + (size_t)iw.block * kNFrag * 32;
+    const size_t m_g_stride = (size_t)nf_total * 32;
+    int i_block = iw.block;
+
+    // Copies for the iteration at the issue walk.  Past the end of the run the last iteration is
+    // simply copied again, so that every iteration issues the same number of copies.
+    int islot = 0;
+    auto issue = [&]() {
+        const int n = min(2, max(iw.left, 1));
+        if (producer) {
+            const int g = iw.g + (pk < n ? pk : 0);
+#pragma unroll
+            for (int b = 0; b < kABlocks; ++b)
+                dma16(abase + (size_t)g * kGroup, a_voff[b], aring_addr + islot * kASlot + b * 1024);
+            if (GROUP) dma4(m_row + (size_t)g * m_g_stride, m_voff, mring_addr + islot * 512);
+            if (pk == 0) dma4(sbase, s_voff + (uint32_t)i_block * s_blk_stride, sring_addr + islot * 256);
+            islot = islot + 1 == kARing ? 0 : islot + 1;
+        } else {
+            dma16(w_row + (size_t)(iw.g + (e < n ? e : 0)) * 1024, w_voff, wring_addr + islot * 1024);
+            islot = islot + 1 == kWRing ? 0 : islot + 1;
+        }
+        if (iw.left > 0 && walk_step(iw, n, G) && iw.left > 0) {
+            i_block = iw.block;
+            w_row += w_block_stride;
+            m_row += kNFrag * 32;
+        }
+    };
+
+    const int hsw = ((ml >> 1) ^ (ml >> 2)) & 3;
+    const int a_src = 4 * ml + (q ^ hsw);   // slot of (row ml, chunk q) inside a 1 KiB activation block
+    int wslot = 0, aslot = 0;               // ring slots of the iteration being consumed
+    auto compute = [&]() {
+        const uint4 wq = wring[wave & 7][wslot][lane];
+        uint32_t S = 0, B = 0;
+        if (GROUP) {
+            const uint32_t mt = reinterpret_cast<const uint16_t*>(&mring[aslot][e][0])[f * 16 + ml];
+            S = __builtin_amdgcn_perm(mt, mt, 0x0c000c00u);  // s1 in both 16-bit lanes
+            B = __builtin_amdgcn_perm(mt, mt, 0x01010101u);  // bias in all four bytes
+        }
+        const uint4* slab = aring[aslot][e];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i a_op[MF];
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(slab[(mf * 2 + ks) * 64 + a_src]);
+            const v4i w_op = dequant<GROUP>(ks ? wq.z : wq.x, ks ? wq.w : wq.y, S, B);
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf)
+                acc[mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w_op, a_op[mf], acc[mf], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop --------------------------------------------------------------------------
+    // Each iteration consumes one slot of every ring while later ones are being copied.  A wave first
+    // waits until at most the copies of the (ring - 2) younger iterations it issued are outstanding,
+    // so its own copies for this iteration have landed; the barrier then publishes every wave's
+    // copies and proves that the slots refilled next are no longer being read.
+    const int tid = f * 64 + lane;                          // owner lanes: index inside a partial tile
+    const bool owner = !producer && e == 0;
+    int4* my_parts = p.parts + (size_t)(blockIdx.y * gridDim.x + wg) * 2 * (MF * kThreads);
+    int npart = 0, part_block[2] = {0, 0};
+    int seg_first_g = first_g, seg_index = 0;
+
+    if (producer) {
+#pragma unroll
+        for (int k = 0; k < kARing - 1; ++k) issue();
+        // per-token epilogue constants go through LDS so that the consumer waves never issue a
+        // register load whose compiler-placed wait would drain their copy queue
+        if (pk == 1 && lane < 16 * MF) {
+            const int m = min(m0 + lane, p.M - 1);
+            sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
+            rs_lds[lane] = GROUP ? 0 : p.rowsum[m];
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kWRing - 1; ++k) issue();
+    }
+    while (cw.left > 0) {
+        const int n = min(2, cw.left);
+        if (!producer) wait_vmcnt<kWRing - 2>();
+        else if (pk == 0) wait_vmcnt<(kARing - 2) * kProducerDma0>();
+        else wait_vmcnt<(kARing - 2) * kProducerDma1>();
+        __syncthreads();
+        issue();
+        if (!producer && e < n) compute();
+        const int aslot_now = aslot;
+        wslot = wslot + 1 == kWRing ? 0 : wslot + 1;
+        aslot = aslot + 1 == kARing ? 0 : aslot + 1;
+        const int block_now = cw.block;
+        const bool wrapped = cw.g + n >= G;
+        if (!walk_step(cw, n, G)) continue;
+
+        // ---- end of this run's share of block_now: parity-1 waves hand over, owners finish -----
+        if (!producer && e == 1) {
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                red[(f * MF + mf) * 64 + lane] = make_int4(acc[mf].x, acc[mf].y, acc[mf].z, acc[mf].w);
+                acc[mf] = (v4i){0, 0, 0, 0};
+            }
+        }
+        __syncthreads();
+        const bool complete = seg_first_g == 0 && wrapped;
+        if (owner) {
+            float sn[4] = {0.f, 0.f, 0.f, 0.f};
+            int zn[4] = {0, 0, 0, 0};
+            if (complete) {
+                const char* sc = reinterpret_cast<const char*>(&sring[aslot_now][0]);
+                const uint2 sw = *reinterpret_cast<const uint2*>(sc + (16 * q + 4 * f) * 2);
+                sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
+                sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
+                sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
+                sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
+                if (!GROUP) {
+                    const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 128 + 16 * q + 4 * f);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
+                }
+            }
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                const int4 o = red[(f * MF + mf) * 64 + lane];
+                v4i v = acc[mf];
+                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                acc[mf] = (v4i){0, 0, 0, 0};
+                if (complete) {
+                    const int m = m0 + mf * 16 + ml;
+                    if (m < p.M)
+                        finish4<GROUP, OUT>(p, m, block_now * 64 + 16 * q + 4 * f, v, sn, zn, sx_lds[mf * 16 + ml],
+                                            rs_lds[mf * 16 + ml]);
+                } else {
+                    store_sc1(my_parts + (size_t)(seg_index ? 1 : 0) * (MF * kThreads) + mf * kThreads + tid, v);
+                }
+            }
+        }
+        if (!complete) { part_block[npart] = block_now; ++npart; }
+        seg_first_g = 0;
+        ++seg_index;
+    }
+    wait_vmcnt<0>();   // tail copies still target the rings; partial tiles have reached memory
+    if (npart == 0) return;
+
+    // ---- blocks shared with other workgroups ---------------------------------------------------
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 0; k < npart; ++k) {
+            const int b = part_block[k];
+            const int w_first = (b * G) / p.upw, w_last = (b * G + G - 1) / p.upw;
+            int* ctr = p.counters + blockIdx.y * blocks + b;
+            const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_flag[k] = old == w_last - w_first;
+            if (s_flag[k]) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __syncthreads();
+    for (int k = 0; k < npart; ++k) {
+        if (!s_flag[k]) continue;
+        // last to arrive: add every contributor's partial tile, element by element, and finish it
+        const int b = part_block[k];
+        const int w_first = (b * G) / p.upw, w_last = (b * G + G - 1) / p.upw;
+        for (int el = threadIdx.x; el < MF * kThreads; el += kStreamThreads) {
+            v4i sum = (v4i){0, 0, 0, 0};
+            for (int w = w_first; w <= w_last; w += 4) {
+                v4i t[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int ww = min(w + x, w_last);
+                    const int which = (ww * p.upw) / G == b ? 0 : 1;   // first or second partial of that workgroup
+                    load_sc1_nowait(t[x], p.parts + ((size_t)(blockIdx.y * gridDim.x + ww) * 2 + which) * (MF * kThreads) + el);
+                }
+                wait_loads(t[0], t[1], t[2], t[3]);
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if (w + x <= w_last) sum += t[x];
+            }
+            const int mf = el / kThreads, ft = (el % kThreads) >> 6, ln = el & 63;
+            const int m = m0 + mf * 16 + (ln & 15);
+            const int n0 = b * 64 + 16 * (ln >> 4) + 4 * ft;
+            if (m >= p.M) continue;
+            float sn[4];
+            int zn[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sn[j] = OUT == OUT_FP16 ? __half2float(p.scales[n0 + j]) : 0.f;
+            if (!GROUP) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) zn[j] = p.zeros[n0 + j];
+            }
+            finish4<GROUP, OUT>(p, m, n0, sum, sn, zn, OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f,
+                                GROUP ? 0 : p.rowsum[m]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// "tiled" kernel: 16*MF tokens x 256 channels per workgroup, activations through LDS.
+// grid = (ceil(N/256), m-tiles, splits).
+// ------------------------------------------------------------------------------------------
+template <int MF, bool GROUP, int OUT>
+__global__ __launch_bounds__(kThreads) void tiled_kernel(GemmDev p)
 {
     constexpr int kPasses = (MF * 128 + kThreads - 1) / kThreads;  // 16-byte chunks of the A tile per thread
     __shared__ uint4 a_lds[2][MF * 2 * 64];
@@ -90,7 +600,6 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev p)
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf) acc[f][mf] = (v4i){0, 0, 0, 0};
 
-    // this thread's slots of the activation tile
     int a_row[kPasses], a_chunk[kPasses];
     bool a_valid[kPasses];
 #pragma unroll
@@ -116,15 +625,12 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev p)
             if (r < 16 * MF) a_lds[stage][((r >> 4) * 2 + (c >> 2)) * 64 + (c & 3) * 16 + (r & 15)] = regs[ps];
         }
     };
-
-    // this lane's stream of weight words: fragment f of block sb, group g
-    const size_t unit_stride = 64;  // uint4 per unit
     auto load_w = [&](int g, uint4* wq, uint32_t* mt) {
 #pragma unroll
         for (int f = 0; f < kNFrag; ++f) {
-            const size_t unit = (size_t)(sb * kNFrag + f) * p.G + g;
-            wq[f] = p.codes[unit * unit_stride + lane];
-            if (GROUP) mt[f] = p.meta[unit * 16 + (lane & 15)];
+            const size_t nf = (size_t)sb * kNFrag + f;
+            wq[f] = p.codes[(nf * p.G + g) * 64 + lane];
+            if (GROUP) mt[f] = p.meta[((size_t)g * (p.N / 16) + nf) * 16 + (lane & 15)];
         }
     };
 
@@ -149,18 +655,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev p)
             if (GROUP) {
 #pragma unroll
                 for (int f = 0; f < kNFrag; ++f) {
-                    S[f] = (mt[f] & 0xFFu) * 0x00010001u;
-                    B[f] = (mt[f] >> 8) * 0x01010101u;
+                    S[f] = __builtin_amdgcn_perm(mt[f], mt[f], 0x0c000c00u);
+                    B[f] = __builtin_amdgcn_perm(mt[f], mt[f], 0x01010101u);
                 }
             }
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 v4i a_op[MF];
 #pragma unroll
-                for (int mf = 0; mf < MF; ++mf) {
-                    const uint4 t = a_lds[stage][(mf * 2 + s) * 64 + lane];
-                    a_op[mf] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-                }
+                for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(a_lds[stage][(mf * 2 + s) * 64 + lane]);
 #pragma unroll
                 for (int f = 0; f < kNFrag; ++f) {
                     const uint32_t x0 = s == 0 ? wq[f].x : wq[f].z;
@@ -181,156 +684,116 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev p)
         stage ^= 1;
     }
 
+    if (p.S > 1) {
+        int4 v[kNFrag * MF];
+#pragma unroll
+        for (int f = 0; f < kNFrag; ++f)
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf)
+                v[f * MF + mf] = make_int4(acc[f][mf].x, acc[f][mf].y, acc[f][mf].z, acc[f][mf].w);
+        if (!splitk_combine<kNFrag * MF>(v, p, blockIdx.y * gridDim.x + blockIdx.x, blockIdx.z, threadIdx.x, true)) return;
+#pragma unroll
+        for (int f = 0; f < kNFrag; ++f)
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf)
+                acc[f][mf] = (v4i){v[f * MF + mf].x, v[f * MF + mf].y, v[f * MF + mf].z, v[f * MF + mf].w};
+    }
     if (!active) return;
-    // lane (q, ml) owns, for every m-fragment, token m0 + mf*16 + ml and the 16 consecutive
-    // output channels n_base .. n_base+15 (value j = 4*f + r is acc[f][mf][r])
+    // lane (q, ml): token m0 + mf*16 + ml, channels n_base .. n_base+15 (value 4*f + r is acc[f][mf][r])
     const int q = lane >> 4, ml = lane & 15;
     const int n_base = sb * 64 + 16 * q;
-
-    if (OUT == OUT_ATOMIC) {
-#pragma unroll
-        for (int mf = 0; mf < MF; ++mf) {
-            const int m = m0 + mf * 16 + ml;
-            if (m >= p.M) continue;
-            int32_t* dst = p.out32 + (size_t)m * p.N + n_base;
-#pragma unroll
-            for (int f = 0; f < kNFrag; ++f)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) atomicAdd(dst + 4 * f + r, acc[f][mf][r]);
-        }
-        return;
-    }
-
-    int zero[16];
-    if (!GROUP) {
-        const uint4 zz = *reinterpret_cast<const uint4*>(p.zeros + n_base);
-        const uint32_t zw[4] = {zz.x, zz.y, zz.z, zz.w};
-#pragma unroll
-        for (int j = 0; j < 16; ++j) zero[j] = (int)((zw[j >> 2] >> (8 * (j & 3))) & 0xFFu);
-    }
-    float sn[16];
-    if (OUT == OUT_FP16) {
-        const uint4 s_lo = *reinterpret_cast<const uint4*>(p.scales + n_base);
-        const uint4 s_hi = *reinterpret_cast<const uint4*>(p.scales + n_base + 8);
-        const uint32_t sw[8] = {s_lo.x, s_lo.y, s_lo.z, s_lo.w, s_hi.x, s_hi.y, s_hi.z, s_hi.w};
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            sn[j] = __half2float(__ushort_as_half((unsigned short)((sw[j >> 1] >> (16 * (j & 1))) & 0xFFFFu)));
-    }
 #pragma unroll
     for (int mf = 0; mf < MF; ++mf) {
         const int m = m0 + mf * 16 + ml;
         if (m >= p.M) continue;
-        int v[16];
+        int vals[16];
 #pragma unroll
         for (int f = 0; f < kNFrag; ++f)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[4 * f + r] = acc[f][mf][r];
-        if (!GROUP) {
-            const int rs = p.rowsum[m];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] -= zero[j] * rs;
-        }
-        if (OUT == OUT_I32) {
-            int4* dst = reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n_base);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) dst[j] = make_int4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
-        } else {
-            const float sxm = __half2float(p.sx[m]);
-            uint32_t h[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const __half a = __float2half_rn((float)v[2 * j] * (sxm * sn[2 * j]));
-                const __half b = __float2half_rn((float)v[2 * j + 1] * (sxm * sn[2 * j + 1]));
-                h[j] = (uint32_t)__half_as_ushort(a) | ((uint32_t)__half_as_ushort(b) << 16);
-            }
-            uint4* dst = reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n_base);
-            dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
-            dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
-        }
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void zero_i32_kernel(int4* dst, size_t n4)
-{
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads)
-        dst[i] = make_int4(0, 0, 0, 0);
-}
-
-// Split-k second pass: 8 consecutive channels of one token per thread.
-template <bool GROUP, bool TO_FP16>
-__global__ __launch_bounds__(kThreads) void finalize_kernel(const int32_t* __restrict__ ws, GemmDev p)
-{
-    const size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    const size_t per_row = (size_t)p.N / 8;
-    if (idx >= (size_t)p.M * per_row) return;
-    const int m = (int)(idx / per_row);
-    const int n0 = (int)(idx % per_row) * 8;
-    const int4 a = *reinterpret_cast<const int4*>(ws + (size_t)m * p.N + n0);
-    const int4 b = *reinterpret_cast<const int4*>(ws + (size_t)m * p.N + n0 + 4);
-    int v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    if (!GROUP) {
-        const int rs = p.rowsum[m];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] -= (int)p.zeros[n0 + j] * rs;
-    }
-    if (TO_FP16) {
-        const float sxm = __half2float(p.sx[m]);
-        uint32_t h[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const __half x = __float2half_rn((float)v[2 * j] * (sxm * __half2float(p.scales[n0 + 2 * j])));
-            const __half y = __float2half_rn((float)v[2 * j + 1] * (sxm * __half2float(p.scales[n0 + 2 * j + 1])));
-            h[j] = (uint32_t)__half_as_ushort(x) | ((uint32_t)__half_as_ushort(y) << 16);
-        }
-        *reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n0) = make_uint4(h[0], h[1], h[2], h[3]);
-    } else {
-        int4* dst = reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n0);
-        dst[0] = make_int4(v[0], v[1], v[2], v[3]);
-        dst[1] = make_int4(v[4], v[5], v[6], v[7]);
+            for (int r = 0; r < 4; ++r) vals[4 * f + r] = acc[f][mf][r];
+        store_row<GROUP, OUT, 16>(p, m, n_base, vals);
     }
 }
 
 template <int MF, bool GROUP>
-void launch_variant(const GemmDev& p, int out_mode, dim3 grid, hipStream_t s)
+void launch_stream(const GemmDev& p, bool fp16, dim3 grid, hipStream_t s)
 {
-    if (out_mode == OUT_FP16) gemm_kernel<MF, GROUP, OUT_FP16><<<grid, kThreads, 0, s>>>(p);
-    else if (out_mode == OUT_I32) gemm_kernel<MF, GROUP, OUT_I32><<<grid, kThreads, 0, s>>>(p);
-    else gemm_kernel<MF, GROUP, OUT_ATOMIC><<<grid, kThreads, 0, s>>>(p);
+    if (fp16) stream_kernel<MF, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+    else stream_kernel<MF, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
 }
 
 template <bool GROUP>
-void launch_tile(const GemmDev& p, int tile_m, int out_mode, dim3 grid, hipStream_t s)
+void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
-    switch (tile_m) {
-        case 16: launch_variant<1, GROUP>(p, out_mode, grid, s); break;
-        case 32: launch_variant<2, GROUP>(p, out_mode, grid, s); break;
-        case 64: launch_variant<4, GROUP>(p, out_mode, grid, s); break;
-        default: launch_variant<8, GROUP>(p, out_mode, grid, s); break;
+    if (tile_m <= 64) {
+        const dim3 grid((unsigned)nwg, (unsigned)((p.M + tile_m - 1) / tile_m));
+        if (tile_m == 16) launch_stream<1, GROUP>(p, fp16, grid, s);
+        else if (tile_m == 32) launch_stream<2, GROUP>(p, fp16, grid, s);
+        else launch_stream<4, GROUP>(p, fp16, grid, s);
+    } else {
+        const dim3 grid((unsigned)((p.N + 255) / 256), (unsigned)((p.M + 127) / 128), (unsigned)p.S);
+        if (fp16) tiled_kernel<8, GROUP, OUT_FP16><<<grid, kThreads, 0, s>>>(p);
+        else tiled_kernel<8, GROUP, OUT_I32><<<grid, kThreads, 0, s>>>(p);
     }
+}
+
+int64_t tiles_of(int64_t M, int64_t N, int tile_m)
+{
+    return tile_m <= 64 ? (N / 64) * ((M + tile_m - 1) / tile_m) : ((N + 255) / 256) * ((M + 127) / 128);
 }
 
 }  // namespace
 
-void pick_gemm_config(int64_t M, int64_t N, int64_t K, int forced_tile_m, int forced_split_k, int& tile_m,
-                      int& split_k)
+// split_k: tiled kernel = number of k-slices per tile; stream kernel = number of workgroups the
+// unit stream is dealt to (per m-tile).
+void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
-    tile_m = forced_tile_m ? forced_tile_m : (M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128);
-    const int64_t blocks = ((N + 255) / 256) * ((M + tile_m - 1) / tile_m);
-    int64_t split = forced_split_k;
+    tile_m = forced.tile_m ? forced.tile_m : (M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128);
+    if (tile_m <= 64) {
+        const int64_t units = (N / 64) * G;
+        // one workgroup per CU; when the number of 64-channel blocks already fills most of the
+        // chip, one workgroup per block avoids the cross-workgroup reduction altogether
+        const int64_t blocks = N / 64;
+        int64_t nwg = forced.split_k > 0 ? forced.split_k : (blocks >= 160 && blocks <= 256 ? blocks : 256);
+        const int64_t max_wg = (units + 1) / 2;   // at least one full iteration (two units) each
+        if (nwg > max_wg) nwg = max_wg;
+        if (nwg < 1) nwg = 1;
+        const int64_t upw = (units + nwg - 1) / nwg;
+        split_k = (int)((units + upw - 1) / upw);
+        return;
+    }
+    const int64_t tiles = tiles_of(M, N, tile_m);
+    int64_t split = forced.split_k;
     if (split <= 0) {
         split = 1;
-        if (blocks < 256) {
-            split = (512 + blocks - 1) / blocks;
-            const int64_t max_split = G / 2 > 0 ? G / 2 : 1;  // keep at least two groups per slice
+        if (tiles < 256) {
+            split = (256 + tiles - 1) / tiles;
+            const int64_t max_split = G / 4 > 0 ? G / 4 : 1;
             if (split > max_split) split = max_split;
+            if (split > 8) split = 8;
         }
     }
     if (split > G) split = G;
     if (split < 1) split = 1;
     const int64_t gps = (G + split - 1) / split;
     split_k = (int)((G + gps - 1) / gps);
+}
+
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
+{
+    if (tile_m <= 64) {
+        const int64_t m_tiles = (M + tile_m - 1) / tile_m;
+        const int64_t units = (N / 64) * (K / kGroup);
+        const int64_t upw = (units + split_k - 1) / split_k;
+        if (upw * 1 >= units && split_k <= 1) return 0;
+        const size_t counters = align256((size_t)(m_tiles * (N / 64)) * sizeof(int));
+        return counters + (size_t)m_tiles * (size_t)split_k * 2 * (size_t)(tile_m * 64) * sizeof(int32_t);
+    }
+    if (split_k <= 1) return 0;
+    const int64_t tiles = tiles_of(M, N, tile_m);
+    const size_t counters = align256((size_t)tiles * sizeof(int));
+    return counters + (size_t)tiles * (size_t)split_k * (size_t)(128 * 256) * sizeof(int32_t);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
@@ -348,32 +811,42 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     p.out16 = static_cast<__half*>(a.out_fp16);
     p.out32 = a.out_i32;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K; p.G = (int)L.G;
-    p.gps = (int)((L.G + a.split_k - 1) / a.split_k);
-    const dim3 grid((unsigned)((a.N + 255) / 256), (unsigned)((a.M + a.tile_m - 1) / a.tile_m), (unsigned)a.split_k);
-    const bool group = a.mode == 0;
-    if (a.split_k == 1) {
-        const int out_mode = a.out_fp16 ? OUT_FP16 : OUT_I32;
-        if (group) launch_tile<true>(p, a.tile_m, out_mode, grid, s);
-        else launch_tile<false>(p, a.tile_m, out_mode, grid, s);
-        return hipGetLastError();
-    }
-    // split-k: exact INT32 partial sums meet in the workspace, then one scaling pass
-    const size_t n4 = (size_t)a.M * (size_t)a.N / 4;
-    zero_i32_kernel<<<dim3((unsigned)((n4 + kThreads - 1) / kThreads > 2048 ? 2048 : (n4 + kThreads - 1) / kThreads)),
-                      kThreads, 0, s>>>(reinterpret_cast<int4*>(a.workspace), n4);
-    GemmDev pa = p;
-    pa.out32 = a.workspace;
-    if (group) launch_tile<true>(pa, a.tile_m, OUT_ATOMIC, grid, s);
-    else launch_tile<false>(pa, a.tile_m, OUT_ATOMIC, grid, s);
-    const size_t items = (size_t)a.M * (size_t)a.N / 8;
-    const dim3 fgrid((unsigned)((items + kThreads - 1) / kThreads));
-    if (group) {
-        if (a.out_fp16) finalize_kernel<true, true><<<fgrid, kThreads, 0, s>>>(a.workspace, p);
-        else finalize_kernel<true, false><<<fgrid, kThreads, 0, s>>>(a.workspace, p);
+    p.counters = reinterpret_cast<int*>(a.workspace);
+    int nwg = 0;
+    size_t counters;
+    if (a.tile_m <= 64) {
+        const int64_t units = (a.N / 64) * L.G;
+        p.upw = (int)((units + a.split_k - 1) / a.split_k);
+        nwg = a.split_k;
+        p.S = 1; p.gps = (int)L.G;
+        counters = align256((size_t)(((a.M + a.tile_m - 1) / a.tile_m) * (a.N / 64)) * sizeof(int));
     } else {
-        if (a.out_fp16) finalize_kernel<false, true><<<fgrid, kThreads, 0, s>>>(a.workspace, p);
-        else finalize_kernel<false, false><<<fgrid, kThreads, 0, s>>>(a.workspace, p);
+        p.upw = 0;
+        p.S = a.split_k;
+        p.gps = (int)((L.G + a.split_k - 1) / a.split_k);
+        counters = align256((size_t)tiles_of(a.M, a.N, a.tile_m) * sizeof(int));
     }
+    p.parts = reinterpret_cast<int4*>(reinterpret_cast<uint8_t*>(a.workspace) + counters);
+    if (a.mode == 0) launch_any<true>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);
+    else launch_any<false>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);
+    return hipGetLastError();
+}
+
+namespace {
+__global__ __launch_bounds__(256) void zero_kernel(int4* dst, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+        dst[i] = make_int4(0, 0, 0, 0);
+}
+}  // namespace
+
+
+hipError_t launch_zero(void* dst, size_t bytes, hipStream_t s)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    const size_t blocks = (n16 + 255) / 256;
+    zero_kernel<<<dim3((unsigned)(blocks > 4096 ? 4096 : blocks)), 256, 0, s>>>(static_cast<int4*>(dst), n16);
     return hipGetLastError();
 }
 

@@ -28,14 +28,18 @@ struct GemmArgs {
     int mode;
     void* out_fp16;          // [M, N] FP16, or null
     int32_t* out_i32;        // [M, N] INT32, or null
-    int32_t* workspace;      // [M, N] INT32 partial sums when split_k > 1
-    int tile_m;              // 16, 32, 64, 128
-    int split_k;             // >= 1
+    void* workspace;         // split-k counters and partial tiles when split_k > 1
+    int tile_m;              // 16, 32, 64 (stream kernel) or 128 (tiled kernel)
+    int split_k;             // tiled kernel: k-slices per tile; stream kernel: workgroups sharing the unit stream
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 
+// Workspace a (tile_m, split_k) launch needs: per-tile counters, then the partial tiles.
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k);
+hipError_t launch_zero(void* dst, size_t bytes, hipStream_t s);
+
 // Launch configuration the library picks for a problem (also sizes the workspace).
-void pick_gemm_config(int64_t M, int64_t N, int64_t K, int forced_tile_m, int forced_split_k,
-                      int& tile_m, int& split_k);
+struct GemmTuning { int tile_m, split_k; };  // 0 = let the heuristic decide
+void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k);
 
 }  // namespace qoq

@@ -21,7 +21,9 @@
 //   so that after the MFMA (lane group q = lane/16 holds rows 4q..4q+3 of each fragment) one
 //   lane owns 16 consecutive logical n of a 64-channel block: 32-byte FP16 row segments.
 //
-// meta (group mode): per unit 16 x uint16, entry i = s1 | (bias << 8) with
+// meta (group mode): 16 x uint16 per (group, fragment), group-major: entry ((g * N/16 + nf) * 16 + i),
+//   so the metadata of neighbouring fragments for one group is contiguous;
+//   entry = s1 | (bias << 8) with
 //   bias = (128 - z * s1) & 0xFF, the byte constant of the subtraction-after-multiplication
 //   dequantizer (Section 5.2.3): code * s1 + bias == w_hat + 128 in every byte, no carries.
 // scales: FP16 [N] in logical order (s0, or sw in per-channel mode).
@@ -100,9 +102,9 @@ QOQ_HD size_t code_dword_offset(int64_t nf, int i, int64_t g, int64_t G, int k_l
     return ((size_t)(nf * G + g) * 64 + (size_t)(kb * 16 + i)) * 16 + (size_t)(2 * s + (t >> 3)) * 4;
 }
 
-QOQ_HD size_t meta_offset(int64_t nf, int i, int64_t g, int64_t G)
+QOQ_HD size_t meta_offset(int64_t nf, int i, int64_t g, int64_t nf_total)
 {
-    return ((size_t)(nf * G + g) * 16 + (size_t)i) * 2;
+    return ((size_t)(g * nf_total + nf) * 16 + (size_t)i) * 2;
 }
 
 }  // namespace qoq

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void pack_group_kernel(const __half* __re
         const int cb = nb <= 0 ? 0 : min(15, nb / (2 * s1));
         store_group_codes(codes, nf, i, g, L.G, lane, ca, cb);
         if (lane == 0)
-            meta[meta_offset(nf, i, g, L.G) / 2] = (uint16_t)(s1 | (((128 - z * s1) & 0xFF) << 8));
+            meta[meta_offset(nf, i, g, L.N / 16) / 2] = (uint16_t)(s1 | (((128 - z * s1) & 0xFF) << 8));
     }
 }
 
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void pack_quantized_kernel(const uint8_t*
     if (j == 0) {
         if (L.mode == 0) {
             const int sc = s1[n * L.G + g], zz = z[n * L.G + g];
-            reinterpret_cast<uint16_t*>(blob + L.meta_off)[meta_offset(nf, i, g, L.G) / 2] =
+            reinterpret_cast<uint16_t*>(blob + L.meta_off)[meta_offset(nf, i, g, L.N / 16) / 2] =
                 (uint16_t)(sc | (((128 - zz * sc) & 0xFF) << 8));
         }
         if (g == 0) {
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint8_t* __restr
     q[idx] = (uint8_t)((v >> sh) & 15);
     if (k_local == 0) {
         if (L.mode == 0) {
-            const uint16_t m = reinterpret_cast<const uint16_t*>(blob + L.meta_off)[meta_offset(nf, i, g, L.G) / 2];
+            const uint16_t m = reinterpret_cast<const uint16_t*>(blob + L.meta_off)[meta_offset(nf, i, g, L.N / 16) / 2];
             const int sc = m & 0xFF;
             int b = m >> 8;
             if (b > 128) b -= 256;  // bias = 128 - z*s1 lies in [-112, 128]

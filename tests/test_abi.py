@@ -69,11 +69,16 @@ def test_argument_validation_without_gpu(api):
     assert L.qoq_w4a8_gemm(p, p, None, p, 0, 256, 256, 0, p, None, 0, None) == 0        # M = 0
     assert L.qoq_w4a8_gemm(p, p, None, p, 4, 256, 256, 0, None, None, 0, None) == 1
     assert L.qoq_w4a8_gemm_i32(p, None, p, 4, 256, 256, 0, p + 8, None, 0, None) == 3
-    assert L.qoq_set_gemm_config(48, 0) == 2 and L.qoq_set_gemm_config(0, 0) == 0
+    assert L.qoq_set_gemm_config(48, 0) == 2 and L.qoq_set_gemm_config(0, -1) == 2 and L.qoq_set_gemm_config(0, 0) == 0
     # split-k problems must come with a workspace
-    assert api.gemm_workspace_bytes(16, 256, 4096) == 16 * 256 * 4
+    need = api.gemm_workspace_bytes(16, 256, 4096)
+    assert need >= 2 * 16 * 256 * 4 and need % 16 == 0          # counters + at least two partial tiles
     assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, None, 0, None) == 4
+    assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, p, need - 16, None) == 4
     assert api.gemm_workspace_bytes(4096, 4096, 4096) == 0
+    assert L.qoq_gemm_workspace_prepare(None, 64, None) == 1
+    assert L.qoq_gemm_workspace_prepare(p, 24, None) == 3
+    assert L.qoq_gemm_workspace_prepare(None, 0, None) == 0
 
 
 def test_layout_is_a_bijection(tmp_path):

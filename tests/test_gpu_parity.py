@@ -146,7 +146,8 @@ def test_group_ragged_m(api, M):
     run_group_case(api, M, 320, 640, seed=100 + M)
 
 
-@pytest.mark.parametrize("tile_m,split_k", [(16, 1), (32, 1), (64, 1), (128, 1), (16, 3), (64, 5), (128, 2), (32, 9)])
+@pytest.mark.parametrize("tile_m,split_k", [(16, 1), (32, 1), (64, 1), (128, 1), (16, 3), (64, 5), (128, 2), (32, 9),
+                                            (64, 2), (128, 9)])
 def test_group_forced_variants(api, tile_m, split_k):
     run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
 
@@ -232,6 +233,7 @@ def test_runtime_errors_leave_outputs_untouched(api):
     blob = api.pack_weights(w)
     qx, sx, _, _ = api.quant_act_per_token(x)
     out = torch.full((16, 256), 7.0, dtype=torch.float16, device=DEV)
+    assert api.gemm_workspace_bytes(16, 256, 4096) > 16
     tiny = torch.empty(16, dtype=torch.uint8, device=DEV)
     with pytest.raises(api.QoqError) as e:
         api.w4a8_gemm(qx, sx, blob, 256, out=out, workspace=tiny)
