@@ -86,28 +86,42 @@ def main():
         if rc != 0:
             raise RuntimeError(api.status_string(rc))
 
-    def gemm_only(step):
+    def gemm_only(step, s=None):
+        s = sp if s is None else s
         for name, (K, N) in layers:
             b = bufs[name]
             check(L.qoq_w4a8_gemm(P(b["qx"]), P(b["sx"]), None, P(blobs[name][step % args.copies]), M, N, K, 0,
-                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), sp))
+                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), s))
 
-    def full_step(step):
+    def full_step(step, s=None):
+        s = sp if s is None else s
         for name, (K, N) in layers:
             b = bufs[name]
-            check(L.qoq_quant_act_per_token(P(xs[name]), M, K, P(b["qx"]), P(b["sx"]), None, None, sp))
+            check(L.qoq_quant_act_per_token(P(xs[name]), M, K, P(b["qx"]), P(b["sx"]), None, None, s))
             check(L.qoq_w4a8_gemm(P(b["qx"]), P(b["sx"]), None, P(blobs[name][step % args.copies]), M, N, K, 0,
-                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), sp))
+                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), s))
 
     def timed(fn, steps, warmup):
+        """Warm up eagerly, then time `steps` steps.  The launches of `copies` consecutive steps are
+        captured once into a HIP graph (launch-bound inner loops belong in graphs) and the graph is
+        replayed steps / copies times between two events on the capture stream's parent."""
         for i in range(warmup):
             fn(i)
         torch.cuda.synchronize()
+        per_graph = args.copies
+        assert steps % per_graph == 0, "--steps must be a multiple of --copies"
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cs = torch.cuda.current_stream().cuda_stream
+            for i in range(per_graph):
+                fn(i, cs)
+        graph.replay()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for i in range(steps):
-            fn(warmup + i)
-        e1.record(stream)
+        e0.record()
+        for _ in range(steps // per_graph):
+            graph.replay()
+        e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps      # ms per step
 
@@ -127,7 +141,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "llama2_7b_decode_m%d" % M, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
                    "M": M, "group": 128, "mode": "group128", "weight_copies_rotated": args.copies,
-                   "step": "4 x (qoq_quant_act_per_token + qoq_w4a8_gemm)"},
+                   "step": "4 x (qoq_quant_act_per_token + qoq_w4a8_gemm), launches replayed from a HIP graph"},
         "roofline": {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "qoq_w4a8_gemm launch (average over the four layers)",

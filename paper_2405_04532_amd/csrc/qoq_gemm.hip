@@ -578,140 +578,191 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
 }
 
 // ------------------------------------------------------------------------------------------
-// "tiled" kernel: 16*MF tokens x 256 channels per workgroup, activations through LDS.
-// grid = (ceil(N/256), m-tiles, splits).
+// "mma" kernel (compute bound, M > 64): 256 tokens x 256 channels per workgroup.
+// Four waves in a 2 x 2 grid own 128 x 128 outputs each: 256 accumulator registers per lane, so
+// exactly one wave per SIMD (a fifth, copy-only wave would halve every wave's register budget).
+// v_mfma_i32_32x32x32_i8: at 32 cycles per MFMA the vector ALU has room for about five
+// instructions per MFMA, and one dequantized weight operand (15 instructions) is reused by the
+// four token fragments of the wave.
+// One stage = one quantization group (k = 128): 32 KiB of activations + 16 KiB of packed weights
+// + metadata, copied global->LDS (each wave a quarter) into a ring of three stages.
+// grid = (m-tiles * n-tiles).
 // ------------------------------------------------------------------------------------------
-template <int MF, bool GROUP, int OUT>
-__global__ __launch_bounds__(kThreads) void tiled_kernel(GemmDev p)
+typedef int v16i __attribute__((ext_vector_type(16)));
+constexpr int kMmaThreads = 256;
+constexpr int kMmaStages = 3;
+constexpr int kMmaStageBytes = 32768 + 16384 + 1024;   // activations, weight units, metadata (256 B per wave)
+
+template <bool GROUP, int OUT>
+__global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 {
-    constexpr int kPasses = (MF * 128 + kThreads - 1) / kThreads;  // 16-byte chunks of the A tile per thread
-    __shared__ uint4 a_lds[2][MF * 2 * 64];
+    __shared__ __attribute__((aligned(16))) char ring[kMmaStages][kMmaStageBytes];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int sb = blockIdx.x * kWaves + wave;  // 64-channel block of this wave
-    const bool active = sb < p.N / 64;
-    const int m0 = blockIdx.y * (16 * MF);
-    const int g_begin = blockIdx.z * p.gps;
-    const int g_end = min(p.G, g_begin + p.gps);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int G = p.G;
+    const int n_tiles = (p.N + 255) / 256;
+    const int tile = blockIdx.x;
+    const int tm = tile / n_tiles, tn = tile - tm * n_tiles;
+    const int m_base = tm * 256;
+    const int nf_base = tn * 16;                         // first 16-row fragment (unit row) of the tile
+    const int nf_total = p.N / 16;
 
-    v4i acc[kNFrag][MF];
+    // ---- copy role: wave w copies token fragments 4w..4w+3 (both k-steps), weight units 4w..4w+3 and
+    // their metadata.  Activation block = (16-token fragment, 64-wide k-step): lane 4r+c copies 16-byte
+    // chunk c ^ h(r) of token r, so a quad reads one 64-byte row segment and fragment reads are
+    // conflict free.
+    constexpr int kDma = 8 + 4 + (GROUP ? 1 : 0);
+    static_assert((kMmaStages - 2) * kDma < 64, "vmcnt range");
+    uint32_t a_voff[4];
+    {
+        const int r = lane >> 2, c = lane & 3;
+        const int h = ((r >> 1) ^ (r >> 2)) & 3;
 #pragma unroll
-    for (int f = 0; f < kNFrag; ++f)
-#pragma unroll
-        for (int mf = 0; mf < MF; ++mf) acc[f][mf] = (v4i){0, 0, 0, 0};
-
-    int a_row[kPasses], a_chunk[kPasses];
-    bool a_valid[kPasses];
-#pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps) {
-        const int idx = ps * kThreads + threadIdx.x;
-        a_row[ps] = idx >> 3;
-        a_chunk[ps] = idx & 7;
-        a_valid[ps] = a_row[ps] < 16 * MF && m0 + a_row[ps] < p.M;
+        for (int t = 0; t < 4; ++t) {
+            const int row = min(m_base + (wave * 4 + t) * 16 + r, p.M - 1);   // rows past M repeat the last one
+            a_voff[t] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((c ^ h) * 16);
+        }
     }
-    auto load_a = [&](int g, uint4* regs) {
+    const uint32_t w_voff = (uint32_t)lane * 16u;
+    const uint32_t m_voff = (uint32_t)(lane & 31) * 4u;
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)&ring[0][0];
+    const char* abase = reinterpret_cast<const char*>(p.qx);
+    const char* wrow[4];
 #pragma unroll
-        for (int ps = 0; ps < kPasses; ++ps) {
-            regs[ps] = make_uint4(0, 0, 0, 0);
-            if (a_valid[ps])
-                regs[ps] = *reinterpret_cast<const uint4*>(p.qx + (size_t)(m0 + a_row[ps]) * p.K + (size_t)g * kGroup +
-                                                           a_chunk[ps] * 16);
-        }
-    };
-    auto store_a = [&](int stage, const uint4* regs) {
+    for (int u = 0; u < 4; ++u)   // units past N repeat the last one; their results are never stored
+        wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * 4 + u, nf_total - 1) * G * 1024;
+    const char* mrow = reinterpret_cast<const char*>(p.meta) + (size_t)min(nf_base + wave * 4, nf_total - 4) * 32;
+    const size_t m_g_stride = (size_t)nf_total * 32;
+    auto issue = [&](int g, int slot) {
+        const uint32_t base = ring_addr + (uint32_t)slot * kMmaStageBytes;
+        const char* arow = abase + (size_t)g * kGroup;
 #pragma unroll
-        for (int ps = 0; ps < kPasses; ++ps) {
-            const int r = a_row[ps], c = a_chunk[ps];
-            if (r < 16 * MF) a_lds[stage][((r >> 4) * 2 + (c >> 2)) * 64 + (c & 3) * 16 + (r & 15)] = regs[ps];
+        for (int t = 0; t < 4; ++t) {
+            dma16(arow, a_voff[t], base + (uint32_t)((wave * 4 + t) * 2) * 1024);
+            dma16(arow + 64, a_voff[t], base + (uint32_t)((wave * 4 + t) * 2 + 1) * 1024);
         }
-    };
-    auto load_w = [&](int g, uint4* wq, uint32_t* mt) {
 #pragma unroll
-        for (int f = 0; f < kNFrag; ++f) {
-            const size_t nf = (size_t)sb * kNFrag + f;
-            wq[f] = p.codes[(nf * p.G + g) * 64 + lane];
-            if (GROUP) mt[f] = p.meta[((size_t)g * (p.N / 16) + nf) * 16 + (lane & 15)];
-        }
+        for (int u = 0; u < 4; ++u)
+            dma16(wrow[u] + (size_t)g * 1024, w_voff, base + 32768 + (uint32_t)(wave * 4 + u) * 1024);
+        if (GROUP) dma4(mrow + (size_t)g * m_g_stride, m_voff, base + 49152 + (uint32_t)wave * 256);
     };
 
-    uint4 a_regs[kPasses], wq[kNFrag], wq_next[kNFrag];
-    uint32_t mt[kNFrag], mt_next[kNFrag];
-    if (g_begin < g_end) {
-        load_a(g_begin, a_regs);
-        if (active) load_w(g_begin, wq, mt);
-        store_a(0, a_regs);
+    // ---- compute waves --------------------------------------------------------------------------
+    issue(0, 0);
+    issue(min(1, G - 1), 1);
+    const int wm = wave >> 1, wn = wave & 1;             // 128-token half, 128-channel half
+    const int r32 = lane & 31, kb2 = lane >> 5;
+    v16i acc[4][4];                                      // [channel fragment][token fragment]
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    // LDS byte offsets (inside a stage) of this lane's operands
+    //   activations, token fragment tf, k32-step j: token t = wm*128 + tf*32 + r32 -> block (t/16, s), slot (t%16, chunk)
+    //   chunk c = 2j + kb2 of the group: s = c/4, position 4*row + ((c%4) ^ h(row))
+    const int arow = r32 & 15;
+    const int ah = ((arow >> 1) ^ (arow >> 2)) & 3;
+    uint32_t a_off[4][4];                                // [tf][j]
+#pragma unroll
+    for (int tf = 0; tf < 4; ++tf)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t16 = wm * 8 + tf * 2 + (r32 >> 4);
+            const int cch = 2 * j + kb2;
+            a_off[tf][j] = (uint32_t)((t16 * 2 + (cch >> 2)) * 1024 + (4 * arow + ((cch & 3) ^ ah)) * 16);
+        }
+    //   weights, channel fragment cf (32 rows = units 2cf, 2cf+1), k32-steps jp and jp+2 in one 16-byte read:
+    //   unit = wn*8 + 2cf + r32/16, lane slot ((2jp + kb2) % 4) * 16 + r32 % 16
+    uint32_t w_off[4][2];
+#pragma unroll
+    for (int cf = 0; cf < 4; ++cf)
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp)
+            w_off[cf][jp] = (uint32_t)(32768 + (wn * 8 + 2 * cf + (r32 >> 4)) * 1024 + (((2 * jp + kb2) & 3) * 16 + (r32 & 15)) * 16);
+    uint32_t mt_off[4];
+#pragma unroll
+    for (int cf = 0; cf < 4; ++cf) {
+        const int u = wn * 8 + 2 * cf + (r32 >> 4);      // unit in the tile; its metadata sits in the copying wave's 256 B
+        mt_off[cf] = (uint32_t)(49152 + (u >> 2) * 256 + ((u & 3) * 16 + (r32 & 15)) * 2);
     }
-    __syncthreads();
 
-    int stage = 0;
-    for (int g = g_begin; g < g_end; ++g) {
-        const bool more = g + 1 < g_end;
-        if (more) {
-            load_a(g + 1, a_regs);
-            if (active) load_w(g + 1, wq_next, mt_next);
-        }
-        if (active) {
-            uint32_t S[kNFrag], B[kNFrag];
-            if (GROUP) {
-#pragma unroll
-                for (int f = 0; f < kNFrag; ++f) {
-                    S[f] = __builtin_amdgcn_perm(mt[f], mt[f], 0x0c000c00u);
-                    B[f] = __builtin_amdgcn_perm(mt[f], mt[f], 0x01010101u);
-                }
-            }
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                v4i a_op[MF];
-#pragma unroll
-                for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(a_lds[stage][(mf * 2 + s) * 64 + lane]);
-#pragma unroll
-                for (int f = 0; f < kNFrag; ++f) {
-                    const uint32_t x0 = s == 0 ? wq[f].x : wq[f].z;
-                    const uint32_t x1 = s == 0 ? wq[f].y : wq[f].w;
-                    const v4i w_op = dequant<GROUP>(x0, x1, GROUP ? S[f] : 0u, GROUP ? B[f] : 0u);
-#pragma unroll
-                    for (int mf = 0; mf < MF; ++mf)
-                        acc[f][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w_op, a_op[mf], acc[f][mf], 0, 0, 0);
-                }
-            }
-        }
-        if (more) {
-            store_a(stage ^ 1, a_regs);
-#pragma unroll
-            for (int f = 0; f < kNFrag; ++f) { wq[f] = wq_next[f]; mt[f] = mt_next[f]; }
-        }
+    // Stage g is consumed while g+1 is in flight and g+2 is issued.  A wave first waits until only the
+    // copies of the one younger stage it issued are outstanding; the barrier publishes everybody's share
+    // of stage g and proves that stage g-1, whose slot is refilled next, is no longer being read.
+    int slot = 0, islot = 2;
+    for (int g = 0; g < G; ++g) {
+        wait_vmcnt<(kMmaStages - 2) * kDma>();
         __syncthreads();
-        stage ^= 1;
+        issue(min(g + 2, G - 1), islot);
+        islot = islot + 1 == kMmaStages ? 0 : islot + 1;
+        const char* st = ring[slot];
+        slot = slot + 1 == kMmaStages ? 0 : slot + 1;
+        uint32_t S[4], B[4];
+        if (GROUP) {
+#pragma unroll
+            for (int cf = 0; cf < 4; ++cf) {
+                const uint32_t mt = *reinterpret_cast<const uint16_t*>(st + mt_off[cf]);
+                S[cf] = __builtin_amdgcn_perm(mt, mt, 0x0c000c00u);
+                B[cf] = __builtin_amdgcn_perm(mt, mt, 0x01010101u);
+            }
+        }
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp) {
+            uint4 raw[4];
+#pragma unroll
+            for (int cf = 0; cf < 4; ++cf) raw[cf] = *reinterpret_cast<const uint4*>(st + w_off[cf][jp]);
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int j = jp + 2 * hh;
+                v4i a_op[4];
+#pragma unroll
+                for (int tf = 0; tf < 4; ++tf) a_op[tf] = as_v4i(*reinterpret_cast<const uint4*>(st + a_off[tf][j]));
+#pragma unroll
+                for (int cf = 0; cf < 4; ++cf) {
+                    const v4i w_op = dequant<GROUP>(hh ? raw[cf].z : raw[cf].x, hh ? raw[cf].w : raw[cf].y,
+                                                    GROUP ? S[cf] : 0u, GROUP ? B[cf] : 0u);
+#pragma unroll
+                    for (int tf = 0; tf < 4; ++tf)
+                        acc[cf][tf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w_op, a_op[tf], acc[cf][tf], 0, 0, 0);
+                }
+            }
+        }
     }
 
-    if (p.S > 1) {
-        int4 v[kNFrag * MF];
+    wait_vmcnt<0>();   // the repeated tail copies still target the ring
+    // ---- epilogue: lane (token r32, half hb = kb2) of fragment (cf, tf) holds rows 8*(v/4) + 4*hb + v%4 ----
+    const int hb = kb2;
 #pragma unroll
-        for (int f = 0; f < kNFrag; ++f)
+    for (int cf = 0; cf < 4; ++cf) {
 #pragma unroll
-            for (int mf = 0; mf < MF; ++mf)
-                v[f * MF + mf] = make_int4(acc[f][mf].x, acc[f][mf].y, acc[f][mf].z, acc[f][mf].w);
-        if (!splitk_combine<kNFrag * MF>(v, p, blockIdx.y * gridDim.x + blockIdx.x, blockIdx.z, threadIdx.x, true)) return;
+        for (int v4 = 0; v4 < 4; ++v4) {
+            // four consecutive physical rows 8*v4 + 4*hb + (0..3) of the 32-row fragment
+            const int row = 8 * v4 + 4 * hb;
+            const int nf = nf_base + wn * 8 + 2 * cf + (row >> 4);
+            if (nf >= nf_total) continue;
+            const int i = row & 15;
+            const int n0 = (nf >> 2) * 64 + 16 * (i >> 2) + 4 * (nf & 3);
+            float sn[4];
+            int zn[4] = {0, 0, 0, 0};
 #pragma unroll
-        for (int f = 0; f < kNFrag; ++f)
+            for (int x = 0; x < 4; ++x) sn[x] = OUT == OUT_FP16 ? __half2float(p.scales[n0 + x]) : 0.f;
+            if (!GROUP) {
 #pragma unroll
-            for (int mf = 0; mf < MF; ++mf)
-                acc[f][mf] = (v4i){v[f * MF + mf].x, v[f * MF + mf].y, v[f * MF + mf].z, v[f * MF + mf].w};
-    }
-    if (!active) return;
-    // lane (q, ml): token m0 + mf*16 + ml, channels n_base .. n_base+15 (value 4*f + r is acc[f][mf][r])
-    const int q = lane >> 4, ml = lane & 15;
-    const int n_base = sb * 64 + 16 * q;
+                for (int x = 0; x < 4; ++x) zn[x] = p.zeros[n0 + x];
+            }
 #pragma unroll
-    for (int mf = 0; mf < MF; ++mf) {
-        const int m = m0 + mf * 16 + ml;
-        if (m >= p.M) continue;
-        int vals[16];
-#pragma unroll
-        for (int f = 0; f < kNFrag; ++f)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) vals[4 * f + r] = acc[f][mf][r];
-        store_row<GROUP, OUT, 16>(p, m, n_base, vals);
+            for (int tf = 0; tf < 4; ++tf) {
+                const int m = m_base + wm * 128 + tf * 32 + r32;
+                if (m >= p.M) continue;
+                const v4i val = {acc[cf][tf][4 * v4], acc[cf][tf][4 * v4 + 1], acc[cf][tf][4 * v4 + 2], acc[cf][tf][4 * v4 + 3]};
+                finish4<GROUP, OUT>(p, m, n0, val, sn, zn, OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f,
+                                    GROUP ? 0 : p.rowsum[m]);
+            }
+        }
     }
 }
 
@@ -731,15 +782,15 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
         else if (tile_m == 32) launch_stream<2, GROUP>(p, fp16, grid, s);
         else launch_stream<4, GROUP>(p, fp16, grid, s);
     } else {
-        const dim3 grid((unsigned)((p.N + 255) / 256), (unsigned)((p.M + 127) / 128), (unsigned)p.S);
-        if (fp16) tiled_kernel<8, GROUP, OUT_FP16><<<grid, kThreads, 0, s>>>(p);
-        else tiled_kernel<8, GROUP, OUT_I32><<<grid, kThreads, 0, s>>>(p);
+        const dim3 grid((unsigned)(((p.N + 255) / 256) * ((p.M + 255) / 256)));
+        if (fp16) mma_kernel<GROUP, OUT_FP16><<<grid, kMmaThreads, 0, s>>>(p);
+        else mma_kernel<GROUP, OUT_I32><<<grid, kMmaThreads, 0, s>>>(p);
     }
 }
 
 int64_t tiles_of(int64_t M, int64_t N, int tile_m)
 {
-    return tile_m <= 64 ? (N / 64) * ((M + tile_m - 1) / tile_m) : ((N + 255) / 256) * ((M + 127) / 128);
+    return tile_m <= 64 ? (N / 64) * ((M + tile_m - 1) / tile_m) : ((N + 255) / 256) * ((M + 255) / 256);
 }
 
 }  // namespace
@@ -763,21 +814,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
         split_k = (int)((units + upw - 1) / upw);
         return;
     }
-    const int64_t tiles = tiles_of(M, N, tile_m);
-    int64_t split = forced.split_k;
-    if (split <= 0) {
-        split = 1;
-        if (tiles < 256) {
-            split = (256 + tiles - 1) / tiles;
-            const int64_t max_split = G / 4 > 0 ? G / 4 : 1;
-            if (split > max_split) split = max_split;
-            if (split > 8) split = 8;
-        }
-    }
-    if (split > G) split = G;
-    if (split < 1) split = 1;
-    const int64_t gps = (G + split - 1) / split;
-    split_k = (int)((G + gps - 1) / gps);
+    split_k = 1;   // the compute-bound kernel does not split k
 }
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
@@ -790,10 +827,7 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int spl
         const size_t counters = align256((size_t)(m_tiles * (N / 64)) * sizeof(int));
         return counters + (size_t)m_tiles * (size_t)split_k * 2 * (size_t)(tile_m * 64) * sizeof(int32_t);
     }
-    if (split_k <= 1) return 0;
-    const int64_t tiles = tiles_of(M, N, tile_m);
-    const size_t counters = align256((size_t)tiles * sizeof(int));
-    return counters + (size_t)tiles * (size_t)split_k * (size_t)(128 * 256) * sizeof(int32_t);
+    return 0;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
@@ -822,9 +856,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         counters = align256((size_t)(((a.M + a.tile_m - 1) / a.tile_m) * (a.N / 64)) * sizeof(int));
     } else {
         p.upw = 0;
-        p.S = a.split_k;
-        p.gps = (int)((L.G + a.split_k - 1) / a.split_k);
-        counters = align256((size_t)tiles_of(a.M, a.N, a.tile_m) * sizeof(int));
+        p.S = 1;
+        p.gps = (int)L.G;
+        counters = 0;
     }
     p.parts = reinterpret_cast<int4*>(reinterpret_cast<uint8_t*>(a.workspace) + counters);
     if (a.mode == 0) launch_any<true>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);
