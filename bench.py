@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5033.0     # MI355X dense INT8 matrix, published (5.0 POP/s)
+CALIB_BYTES = 256 << 20     # size of the calibration copy
+# HBM bytes per GEMM launch of the default workload, from the two counter runs summarised in
+# profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy); None for any other workload.
+TRAFFIC_BYTES_PER_LAUNCH_DEFAULT = 39.84e6
 
 
 def algorithmic_bytes(M, N, K, mode=0):
@@ -70,6 +74,14 @@ def main():
             blobs[name].append(first.clone())
         del w
     xs = {name: wl.layer_activations("llama2_7b", name, M, 1, dev) for name, _ in layers}
+    # A plain streaming kernel of known size (256 MiB read, 256 MiB written), launched three times during
+    # set-up: under `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` its reading gives the factor that converts the
+    # counters of the GEMM launches of the same run into bytes.
+    calib_src = torch.zeros(CALIB_BYTES // 4, dtype=torch.int32, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    for _ in range(3):
+        torch.mul(calib_src, 1, out=calib_dst)
+    del calib_src, calib_dst
     bufs = {}
     for name, (K, N) in layers:
         bufs[name] = dict(
@@ -143,7 +155,8 @@ def main():
                    "M": M, "group": 128, "mode": "group128", "weight_copies_rotated": args.copies,
                    "step": "4 x (qoq_quant_act_per_token + qoq_w4a8_gemm), launches replayed from a HIP graph"},
         "roofline": {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH_DEFAULT if (M == 64 and args.copies == 8) else None,
                      "kernel": "qoq_w4a8_gemm launch (average over the four layers)",
                      "avg_launch_us": round(ms_gemm * 1e3 / len(layers), 3),
                      "algorithmic_bytes_per_launch": round(byts / len(layers)),
