@@ -580,27 +580,37 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
 // ------------------------------------------------------------------------------------------
 // "mma" kernel (compute bound, M > 64): 256 tokens x 256 channels per workgroup.
 // Four waves in a 2 x 2 grid own 128 x 128 outputs each: 256 accumulator registers per lane, so
-// exactly one wave per SIMD (a fifth, copy-only wave would halve every wave's register budget).
-// v_mfma_i32_32x32x32_i8: at 32 cycles per MFMA the vector ALU has room for about five
-// instructions per MFMA, and one dequantized weight operand (15 instructions) is reused by the
-// four token fragments of the wave.
-// One stage = one quantization group (k = 128): 32 KiB of activations + 16 KiB of packed weights
-// + metadata, copied global->LDS (each wave a quarter) into a ring of three stages.
-// grid = (m-tiles * n-tiles).
+// exactly one wave per SIMD, and nothing but that wave's own instruction stream can keep the matrix
+// pipe busy.  The main loop is therefore software pipelined by hand into "chunks" of one
+// v_mfma_i32_32x32x32_i8 (32 cycles) plus what fits in its shadow: a quarter of the dequantization
+// of the NEXT weight operand (one operand = 4 dwords, reused by the four token fragments of the
+// wave: 3.5 vector instructions per MFMA), at most one LDS read and at most one copy.  A scheduling
+// barrier after every chunk keeps the compiler from regrouping them.
+//
+// Copies are global->LDS DMA in half-group steps (k = 64): activations in a ring of six 16 KiB
+// slabs, packed weights (whole groups: the 16-byte lane word covers both halves) and metadata in
+// rings of three.  During half-stage h, six blocks in, a wave waits for its own copies of half-stage
+// h+1 and all waves meet: that publishes h+1 and proves h-1 is no longer read, so its slab is
+// refilled with h+5 (weights of group g+2 go out with the even half-stages).  The last two blocks
+// of h overlap the first LDS reads and the first dequantization of h+1, so the matrix pipe does not
+// drain at the barrier.  grid = (m-tiles * n-tiles).
 // ------------------------------------------------------------------------------------------
 typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kMmaThreads = 256;
-constexpr int kMmaStages = 3;
-constexpr int kMmaStageBytes = 32768 + 16384 + 1024;   // activations, weight units, metadata (256 B per wave)
+constexpr int kASlots = 6, kASlotBytes = 16384;     // activations: 256 tokens x 64 k per half-stage
+constexpr int kWSlots = 3, kWSlotBytes = 16384;     // weights: 16 units (256 channels x 128 k)
+constexpr int kMSlotBytes = 1024;                   // metadata: 256 B per copying wave
 
 template <bool GROUP, int OUT>
 __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 {
-    __shared__ __attribute__((aligned(16))) char ring[kMmaStages][kMmaStageBytes];
+    __shared__ __attribute__((aligned(16))) char aring[kASlots * kASlotBytes];
+    __shared__ __attribute__((aligned(16))) char wring[kWSlots * kWSlotBytes];
+    __shared__ __attribute__((aligned(16))) char mring[kWSlots * kMSlotBytes];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int G = p.G;
+    const int G = p.G, H = 2 * p.G;
     const int n_tiles = (p.N + 255) / 256;
     const int tile = blockIdx.x;
     const int tm = tile / n_tiles, tn = tile - tm * n_tiles;
@@ -608,12 +618,10 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     const int nf_base = tn * 16;                         // first 16-row fragment (unit row) of the tile
     const int nf_total = p.N / 16;
 
-    // ---- copy role: wave w copies token fragments 4w..4w+3 (both k-steps), weight units 4w..4w+3 and
-    // their metadata.  Activation block = (16-token fragment, 64-wide k-step): lane 4r+c copies 16-byte
-    // chunk c ^ h(r) of token r, so a quad reads one 64-byte row segment and fragment reads are
-    // conflict free.
-    constexpr int kDma = 8 + 4 + (GROUP ? 1 : 0);
-    static_assert((kMmaStages - 2) * kDma < 64, "vmcnt range");
+    // ---- copy role: wave w copies token fragments 4w..4w+3, weight units 4w..4w+3 and their metadata.
+    // Activation block = (16-token fragment, 64-wide half-stage): lane 4r+c copies 16-byte chunk
+    // c ^ h(r) of token r, so a quad reads one 64-byte row segment and fragment reads are conflict free.
+    constexpr int kOdd = 4, kEven = 8 + (GROUP ? 1 : 0);   // copies a wave issues after an odd / even half-stage's barrier
     uint32_t a_voff[4];
     {
         const int r = lane >> 2, c = lane & 3;
@@ -626,7 +634,9 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     }
     const uint32_t w_voff = (uint32_t)lane * 16u;
     const uint32_t m_voff = (uint32_t)(lane & 31) * 4u;
-    const uint32_t ring_addr = (uint32_t)(uintptr_t)&ring[0][0];
+    const uint32_t a_dst = (uint32_t)(uintptr_t)&aring[0] + (uint32_t)wave * 4096u;
+    const uint32_t w_dst = (uint32_t)(uintptr_t)&wring[0] + (uint32_t)wave * 4096u;
+    const uint32_t m_dst = (uint32_t)(uintptr_t)&mring[0] + (uint32_t)wave * 256u;
     const char* abase = reinterpret_cast<const char*>(p.qx);
     const char* wrow[4];
 #pragma unroll
@@ -634,23 +644,28 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * 4 + u, nf_total - 1) * G * 1024;
     const char* mrow = reinterpret_cast<const char*>(p.meta) + (size_t)min(nf_base + wave * 4, nf_total - 4) * 32;
     const size_t m_g_stride = (size_t)nf_total * 32;
-    auto issue = [&](int g, int slot) {
-        const uint32_t base = ring_addr + (uint32_t)slot * kMmaStageBytes;
-        const char* arow = abase + (size_t)g * kGroup;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            dma16(arow, a_voff[t], base + (uint32_t)((wave * 4 + t) * 2) * 1024);
-            dma16(arow + 64, a_voff[t], base + (uint32_t)((wave * 4 + t) * 2 + 1) * 1024);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            dma16(wrow[u] + (size_t)g * 1024, w_voff, base + 32768 + (uint32_t)(wave * 4 + u) * 1024);
-        if (GROUP) dma4(mrow + (size_t)g * m_g_stride, m_voff, base + 49152 + (uint32_t)wave * 256);
-    };
+    int ca = 0, cw = 0;   // next half-stage / group to copy; past the end the last one is copied again into a free slab
+    auto copy_a = [&](int t, int slot) { dma16(abase + (size_t)ca * 64, a_voff[t], a_dst + (uint32_t)(slot * kASlotBytes + t * 1024)); };
+    auto copy_w = [&](int u, int slot) { dma16(wrow[u] + (size_t)cw * 1024, w_voff, w_dst + (uint32_t)(slot * kWSlotBytes + u * 1024)); };
+    auto copy_m = [&](int slot) { if (GROUP) dma4(mrow + (size_t)cw * m_g_stride, m_voff, m_dst + (uint32_t)(slot * kMSlotBytes)); };
+    auto adv_a = [&]() { ca = min(ca + 1, H - 1); };
+    auto adv_w = [&]() { cw = min(cw + 1, G - 1); };
 
-    // ---- compute waves --------------------------------------------------------------------------
-    issue(0, 0);
-    issue(min(1, G - 1), 1);
+    // prologue: half-stages 0..4, groups 0..1, in the order of the steady state (odd, even, odd, even, odd)
+#pragma unroll
+    for (int hh = 0; hh < 5; ++hh) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) copy_a(t, hh);
+        adv_a();
+        if (hh & 1) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) copy_w(u, hh >> 1);
+            copy_m(hh >> 1);
+            adv_w();
+        }
+    }
+
+    // ---- compute role ---------------------------------------------------------------------------
     const int wm = wave >> 1, wn = wave & 1;             // 128-token half, 128-channel half
     const int r32 = lane & 31, kb2 = lane >> 5;
     v16i acc[4][4];                                      // [channel fragment][token fragment]
@@ -661,76 +676,146 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
-    // LDS byte offsets (inside a stage) of this lane's operands
-    //   activations, token fragment tf, k32-step j: token t = wm*128 + tf*32 + r32 -> block (t/16, s), slot (t%16, chunk)
-    //   chunk c = 2j + kb2 of the group: s = c/4, position 4*row + ((c%4) ^ h(row))
+    // LDS byte offsets of this lane's operands inside a slab.
+    //   activations, token fragment tf (+ tf * 2048), k32-step jj of the half-stage: token wm*128 + tf*32 + r32
+    //   -> block token/16, row token%16, 16-byte chunk (2jj + kb2) ^ h(row)
     const int arow = r32 & 15;
     const int ah = ((arow >> 1) ^ (arow >> 2)) & 3;
-    uint32_t a_off[4][4];                                // [tf][j]
+    uint32_t a_rd[2], w_rd[2];
 #pragma unroll
-    for (int tf = 0; tf < 4; ++tf)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int t16 = wm * 8 + tf * 2 + (r32 >> 4);
-            const int cch = 2 * j + kb2;
-            a_off[tf][j] = (uint32_t)((t16 * 2 + (cch >> 2)) * 1024 + (4 * arow + ((cch & 3) ^ ah)) * 16);
-        }
-    //   weights, channel fragment cf (32 rows = units 2cf, 2cf+1), k32-steps jp and jp+2 in one 16-byte read:
-    //   unit = wn*8 + 2cf + r32/16, lane slot ((2jp + kb2) % 4) * 16 + r32 % 16
-    uint32_t w_off[4][2];
-#pragma unroll
-    for (int cf = 0; cf < 4; ++cf)
-#pragma unroll
-        for (int jp = 0; jp < 2; ++jp)
-            w_off[cf][jp] = (uint32_t)(32768 + (wn * 8 + 2 * cf + (r32 >> 4)) * 1024 + (((2 * jp + kb2) & 3) * 16 + (r32 & 15)) * 16);
-    uint32_t mt_off[4];
-#pragma unroll
-    for (int cf = 0; cf < 4; ++cf) {
-        const int u = wn * 8 + 2 * cf + (r32 >> 4);      // unit in the tile; its metadata sits in the copying wave's 256 B
-        mt_off[cf] = (uint32_t)(49152 + (u >> 2) * 256 + ((u & 3) * 16 + (r32 & 15)) * 2);
+    for (int jj = 0; jj < 2; ++jj) {
+        a_rd[jj] = (uint32_t)((wm * 8 + (r32 >> 4)) * 1024 + (4 * arow + (((2 * jj + kb2) & 3) ^ ah)) * 16);
+        //   weights, channel fragment cf (+ cf * 2048; 32 rows = units 2cf, 2cf+1), half s (+ s * 8):
+        //   unit wn*8 + 2cf + r32/16, lane word ((2jj + kb2) % 4) * 16 + r32 % 16
+        w_rd[jj] = (uint32_t)((wn * 8 + (r32 >> 4)) * 1024 + ((((2 * jj + kb2) & 3) * 16) + (r32 & 15)) * 16);
     }
+    //   metadata of fragment cf: + (cf / 2) * 256 + (cf % 2) * 64
+    const uint32_t m_rd = (uint32_t)(wn * 512 + ((r32 >> 4) * 16 + (r32 & 15)) * 2);
 
-    // Stage g is consumed while g+1 is in flight and g+2 is issued.  A wave first waits until only the
-    // copies of the one younger stage it issued are outstanding; the barrier publishes everybody's share
-    // of stage g and proves that stage g-1, whose slot is refilled next, is no longer being read.
-    int slot = 0, islot = 2;
+    auto lds_a = [&](uint32_t slab, int jj, int tf) {
+        return as_v4i(*reinterpret_cast<const uint4*>(aring + slab + a_rd[jj] + tf * 2048));
+    };
+    auto lds_w = [&](uint32_t slab, int blk) {           // lane word (both halves) of block blk = (jj, cf)
+        return *reinterpret_cast<const uint4*>(wring + slab + w_rd[blk >> 2] + (blk & 3) * 2048);
+    };
+    auto lds_m = [&](uint32_t slab, int cf) {
+        return (uint32_t)*reinterpret_cast<const uint16_t*>(mring + slab + m_rd + (cf >> 1) * 256 + (cf & 1) * 64);
+    };
+    const uint32_t nib_mask = 0x0F0F0F0Fu, sign = 0x80808080u;
+    auto src_dword = [&](uint4 r, int half, int d) { return half == 0 ? (d < 2 ? r.x : r.y) : (d < 2 ? r.z : r.w); };
+    auto deq1 = [&](uint4 r, int half, int d, uint32_t S, uint32_t B) {   // dword d of the operand of k-half `half`
+        const uint32_t x = src_dword(r, half, d);
+        uint32_t v = (d & 1) ? (x >> 4) & nib_mask : x & nib_mask;
+        if (GROUP) v = pk_mad_u16(v, S, B) ^ sign;
+        return (int)v;
+    };
+    // The same dequantization cut into four phases of 3-4 instructions, one phase per chunk, with the
+    // multiply-add of one dword and the sign flip of the previous one interleaved so that no result is
+    // consumed by the very next instruction.  t[] carries the dwords in progress, o[] receives the operand.
+    auto deq_phase = [&](int ph, uint4 r, int half, uint32_t S, uint32_t B, uint32_t (&t)[4], v4i& o) {
+        if (ph == 0) {
+            t[0] = src_dword(r, half, 0) & nib_mask;
+            t[1] = (src_dword(r, half, 1) >> 4) & nib_mask;
+            if (GROUP) t[0] = pk_mad_u16(t[0], S, B);
+        } else if (ph == 1) {
+            if (GROUP) t[1] = pk_mad_u16(t[1], S, B);
+            o.x = (int)(GROUP ? t[0] ^ sign : t[0]);
+            t[2] = src_dword(r, half, 2) & nib_mask;
+            t[3] = (src_dword(r, half, 3) >> 4) & nib_mask;
+        } else if (ph == 2) {
+            if (GROUP) t[2] = pk_mad_u16(t[2], S, B);
+            o.y = (int)(GROUP ? t[1] ^ sign : t[1]);
+            if (GROUP) t[3] = pk_mad_u16(t[3], S, B);
+        } else {
+            o.z = (int)(GROUP ? t[2] ^ sign : t[2]);
+            o.w = (int)(GROUP ? t[3] ^ sign : t[3]);
+        }
+    };
+
+    // first barrier: half-stage 0 and group 0 have landed everywhere
+    wait_vmcnt<2 * kOdd + kEven>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    uint32_t S[4] = {0, 0, 0, 0}, B[4] = {0, 0, 0, 0}, mt[4] = {0, 0, 0, 0};
+    if (GROUP) {
+#pragma unroll
+        for (int cf = 0; cf < 4; ++cf) {
+            mt[cf] = lds_m(0, cf);
+            S[cf] = __builtin_amdgcn_perm(mt[cf], mt[cf], 0x0c000c00u);
+            B[cf] = __builtin_amdgcn_perm(mt[cf], mt[cf], 0x01010101u);
+        }
+    }
+    // Register-level pipeline.  rq[blk]: lane words of the eight blocks of a group, read four blocks ahead
+    // (blocks 4..7 during blocks 0..3 of the first half, blocks 0..3 of the next group after the barrier of the
+    // second half).  a0: activations of k32-step 0 of a half-stage (read in blocks 4, 5 of the half-stage
+    // before), a1[s]: k32-step 1 (read in blocks 6, 7 of the half-stage before, hence two sets).
+    uint4 rq[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rq[i] = i < 4 ? lds_w(0, i) : make_uint4(0, 0, 0, 0);
+    v4i a0[4], a1[2][4];
+#pragma unroll
+    for (int tf = 0; tf < 4; ++tf) { a0[tf] = lds_a(0, 0, tf); a1[0][tf] = lds_a(0, 1, tf); a1[1][tf] = (v4i){0, 0, 0, 0}; }
+    v4i w_cur = {deq1(rq[0], 0, 0, S[0], B[0]), deq1(rq[0], 0, 1, S[0], B[0]), deq1(rq[0], 0, 2, S[0], B[0]), deq1(rq[0], 0, 3, S[0], B[0])};
+    v4i w_nxt = {0, 0, 0, 0};
+    uint32_t dq[4] = {0, 0, 0, 0};
+    deq_phase(0, rq[1], 0, S[1], B[1], dq, w_nxt);        // block 1 is one phase ahead, as in the steady state
+
+    int gs = 0;                                          // g % 3
     for (int g = 0; g < G; ++g) {
-        wait_vmcnt<(kMmaStages - 2) * kDma>();
-        __syncthreads();
-        issue(min(g + 2, G - 1), islot);
-        islot = islot + 1 == kMmaStages ? 0 : islot + 1;
-        const char* st = ring[slot];
-        slot = slot + 1 == kMmaStages ? 0 : slot + 1;
-        uint32_t S[4], B[4];
-        if (GROUP) {
+        const int gp1 = gs == 2 ? 0 : gs + 1, gm1 = gs == 0 ? 2 : gs - 1;
 #pragma unroll
-            for (int cf = 0; cf < 4; ++cf) {
-                const uint32_t mt = *reinterpret_cast<const uint16_t*>(st + mt_off[cf]);
-                S[cf] = __builtin_amdgcn_perm(mt, mt, 0x0c000c00u);
-                B[cf] = __builtin_amdgcn_perm(mt, mt, 0x01010101u);
-            }
-        }
+        for (int s = 0; s < 2; ++s) {                    // half-stage h = 2g + s
+            const uint32_t a_nxt = (uint32_t)((s == 0 ? 2 * gs + 1 : 2 * gp1) * kASlotBytes);
+            const uint32_t w_this = (uint32_t)(gs * kWSlotBytes), w_next = (uint32_t)(gp1 * kWSlotBytes);
+            const uint32_t m_nxt = (uint32_t)(gp1 * kMSlotBytes);
+            const int a_islot = s == 0 ? 2 * gm1 + 1 : 2 * gs;   // slab of half-stage h-1 = (h+5) % 6
+            const int w_islot = gm1;                             // slab of group g-1 = (g+2) % 3
 #pragma unroll
-        for (int jp = 0; jp < 2; ++jp) {
-            uint4 raw[4];
-#pragma unroll
-            for (int cf = 0; cf < 4; ++cf) raw[cf] = *reinterpret_cast<const uint4*>(st + w_off[cf][jp]);
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                const int j = jp + 2 * hh;
-                v4i a_op[4];
-#pragma unroll
-                for (int tf = 0; tf < 4; ++tf) a_op[tf] = as_v4i(*reinterpret_cast<const uint4*>(st + a_off[tf][j]));
-#pragma unroll
-                for (int cf = 0; cf < 4; ++cf) {
-                    const v4i w_op = dequant<GROUP>(hh ? raw[cf].z : raw[cf].x, hh ? raw[cf].w : raw[cf].y,
-                                                    GROUP ? S[cf] : 0u, GROUP ? B[cf] : 0u);
-#pragma unroll
-                    for (int tf = 0; tf < 4; ++tf)
-                        acc[cf][tf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w_op, a_op[tf], acc[cf][tf], 0, 0, 0);
+            for (int c = 0; c < 32; ++c) {               // chunk = (block b = (jj, cf), token fragment tf)
+                const int b = c >> 2, tf = c & 3, jj = b >> 2, cf = b & 3;
+                if (c == 16) {
+                    if (s == 0) wait_vmcnt<2 * kOdd + kEven>(); else wait_vmcnt<kOdd + kEven>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
                 }
+                if (tf == 0 && c != 0) w_cur = w_nxt;    // (for c == 0 the hand-over happened at the end of the previous half-stage)
+                acc[cf][tf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w_cur, jj == 0 ? a0[tf] : a1[s][tf], acc[cf][tf], 0, 0, 0);
+                {   // one phase of a later operand: chunks (b,0..2) finish block b+1, chunk (b,3) starts block b+2
+                    const int ph = (tf + 1) & 3;
+                    const int tb = ph == 0 ? b + 2 : b + 1;      // target block; 8, 9 = blocks 0, 1 of the next half-stage
+                    const int half = tb >= 8 ? 1 - s : s;
+                    deq_phase(ph, rq[tb & 7], half, S[tb & 3], B[tb & 3], dq, w_nxt);
+                }
+                if (tf == 0) {                           // lane words four blocks ahead
+                    if (s == 0 && b < 4) rq[b + 4] = lds_w(w_this, b + 4);
+                    if (s == 1 && b >= 4) rq[b - 4] = lds_w(w_next, b - 4);
+                }
+                if (b >= 4 && (tf & 1)) {                // activations of the next half-stage, two fragments per block
+                    const int q = (b & 1) * 2 + (tf >> 1);
+                    if (b < 6) a0[q] = lds_a(a_nxt, 0, q);
+                    else a1[1 - s][q] = lds_a(a_nxt, 1, q);
+                }
+                if (GROUP && s == 1) {                   // level-2 constants of the next group, each after the last use of the old one
+                    if (b == 4) mt[tf] = lds_m(m_nxt, tf);
+                    const int pc = c == 20 ? 0 : c == 22 ? 1 : c == 24 ? 2 : c == 28 ? 3 : -1;
+                    if (pc >= 0) {
+                        S[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x0c000c00u);
+                        B[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x01010101u);
+                    }
+                }
+                if (c >= 16) {                           // refill the slabs the barrier has just freed
+                    const int k = c - 16;
+                    if (k < 4) copy_a(k, a_islot);
+                    else if (k < 8 && s == 0) copy_w(k - 4, w_islot);
+                    else if (k == 8 && s == 0) copy_m(w_islot);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            w_cur = w_nxt;
+            adv_a();
+            if (s == 0) adv_w();
         }
+        gs = gp1;
     }
 
     wait_vmcnt<0>();   // the repeated tail copies still target the ring
