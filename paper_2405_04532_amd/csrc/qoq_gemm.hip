@@ -607,13 +607,29 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     __shared__ __attribute__((aligned(16))) char aring[kASlots * kASlotBytes];
     __shared__ __attribute__((aligned(16))) char wring[kWSlots * kWSlotBytes];
     __shared__ __attribute__((aligned(16))) char mring[kWSlots * kMSlotBytes];
+    __shared__ __attribute__((aligned(16))) char ering[2304];   // sx[256] fp16 | s[256] fp16 | rowsum[256] | zeros[256]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int G = p.G, H = 2 * p.G;
-    const int n_tiles = (p.N + 255) / 256;
-    const int tile = blockIdx.x;
-    const int tm = tile / n_tiles, tn = tile - tm * n_tiles;
+    // Workgroup -> tile.  Consecutive workgroup ids land on consecutive XCDs (8, each with its own L2), so
+    // workgroup i is the (i / 8)-th of XCD i % 8.  Each XCD gets a contiguous run of a tile order that walks
+    // panels of four token tiles column by column: the 32 tiles an XCD works on at a time form a 4 x 8 block
+    // sharing 4 activation slabs and 8 weight slabs through that XCD's L2.
+    const int n_tiles = (p.N + 255) / 256, m_tiles = (p.M + 255) / 256;
+    int tm, tn;
+    {
+        const int T = n_tiles * m_tiles, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int q = T >> 3, r = T & 7;
+        const int L = xcd * q + min(xcd, r) + slot;      // slot < q + (xcd < r) because blockIdx.x < T
+        constexpr int kPanel = 4;
+        const int per_panel = kPanel * n_tiles;
+        const int panel = L / per_panel;
+        const int rows = min(kPanel, m_tiles - panel * kPanel);
+        const int rem = L - panel * per_panel;
+        tn = rem / rows;
+        tm = panel * kPanel + (rem - tn * rows);
+    }
     const int m_base = tm * 256;
     const int nf_base = tn * 16;                         // first 16-row fragment (unit row) of the tile
     const int nf_total = p.N / 16;
@@ -650,6 +666,31 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     auto copy_m = [&](int slot) { if (GROUP) dma4(mrow + (size_t)cw * m_g_stride, m_voff, m_dst + (uint32_t)(slot * kMSlotBytes)); };
     auto adv_a = [&]() { ca = min(ca + 1, H - 1); };
     auto adv_w = [&]() { cw = min(cw + 1, G - 1); };
+
+    // Epilogue constants of the tile (token scales, channel scales; per-channel mode: token sums, zero points)
+    // are copied into LDS first of all, so they are the oldest entries of each wave's copy queue and cost no
+    // separate wait.  Indices past M / N repeat the last valid dword (never stored from).
+    {
+        const uint32_t e_dst = (uint32_t)(uintptr_t)&ering[0];
+        if (OUT == OUT_FP16) {
+            if (wave < 2) {
+                const int last = (p.M - m_base - 1) >> 1;                 // dword holding the last token of the tile
+                dma4(reinterpret_cast<const char*>(p.sx) + (size_t)m_base * 2, (uint32_t)min(wave * 64 + lane, last) * 4u,
+                     e_dst + (uint32_t)wave * 256u);
+            } else {
+                const int last = ((p.N - tn * 256) >> 1) - 1;
+                dma4(reinterpret_cast<const char*>(p.scales) + (size_t)tn * 512, (uint32_t)min((wave - 2) * 64 + lane, last) * 4u,
+                     e_dst + 512u + (uint32_t)(wave - 2) * 256u);
+            }
+        }
+        if (!GROUP) {
+            dma4(reinterpret_cast<const char*>(p.rowsum) + (size_t)m_base * 4, (uint32_t)min(wave * 64 + lane, p.M - m_base - 1) * 4u,
+                 e_dst + 1024u + (uint32_t)wave * 256u);
+            if (wave == 0)
+                dma4(reinterpret_cast<const char*>(p.zeros) + (size_t)tn * 256, (uint32_t)min(lane, ((p.N - tn * 256) >> 2) - 1) * 4u,
+                     e_dst + 2048u);
+        }
+    }
 
     // prologue: half-stages 0..4, groups 0..1, in the order of the steady state (odd, even, odd, even, odd)
 #pragma unroll
@@ -775,7 +816,9 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                 const int b = c >> 2, tf = c & 3, jj = b >> 2, cf = b & 3;
                 if (c == 16) {
                     if (s == 0) wait_vmcnt<2 * kOdd + kEven>(); else wait_vmcnt<kOdd + kEven>();
+#ifndef QOQ_EXP_NOBAR
                     __builtin_amdgcn_s_barrier();
+#endif
                     asm volatile("" ::: "memory");
                 }
                 if (tf == 0 && c != 0) w_cur = w_nxt;    // (for c == 0 the hand-over happened at the end of the previous half-stage)
@@ -784,7 +827,11 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                     const int ph = (tf + 1) & 3;
                     const int tb = ph == 0 ? b + 2 : b + 1;      // target block; 8, 9 = blocks 0, 1 of the next half-stage
                     const int half = tb >= 8 ? 1 - s : s;
+#ifndef QOQ_EXP_NODEQ
                     deq_phase(ph, rq[tb & 7], half, S[tb & 3], B[tb & 3], dq, w_nxt);
+#else
+                    if (ph == 3) w_nxt = as_v4i(rq[tb & 7]);
+#endif
                 }
                 if (tf == 0) {                           // lane words four blocks ahead
                     if (s == 0 && b < 4) rq[b + 4] = lds_w(w_this, b + 4);
@@ -819,33 +866,59 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     }
 
     wait_vmcnt<0>();   // the repeated tail copies still target the ring
-    // ---- epilogue: lane (token r32, half hb = kb2) of fragment (cf, tf) holds rows 8*(v/4) + 4*hb + v%4 ----
+    const __half* e_sx = reinterpret_cast<const __half*>(ering);
+    const __half* e_sn = e_sx + 256;
+    const int* e_rs = reinterpret_cast<const int*>(ering + 1024);
+    const uint8_t* e_zn = reinterpret_cast<const uint8_t*>(ering + 2048);
+
+    // ---- epilogue.  Lane (token r32, half hb = kb2) of fragment (cf, tf) holds physical rows 8*(v/4) + 4*hb + v%4,
+    // i.e. logical channels 64*(cf/2) + 32*(v4%2) + 16*hb + 8*(cf%2) + 4*(v4/2) + v%4 of the wave's 128: for fixed
+    // (cf/2, v4%2) the four pieces (cf%2, v4/2) are 16 consecutive channels = one 32-byte row segment per token.
     const int hb = kb2;
 #pragma unroll
-    for (int cf = 0; cf < 4; ++cf) {
+    for (int ch = 0; ch < 2; ++ch) {
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            // four consecutive physical rows 8*v4 + 4*hb + (0..3) of the 32-row fragment
-            const int row = 8 * v4 + 4 * hb;
-            const int nf = nf_base + wn * 8 + 2 * cf + (row >> 4);
-            if (nf >= nf_total) continue;
-            const int i = row & 15;
-            const int n0 = (nf >> 2) * 64 + 16 * (i >> 2) + 4 * (nf & 3);
-            float sn[4];
-            int zn[4] = {0, 0, 0, 0};
+        for (int vl = 0; vl < 2; ++vl) {
+            const int nl = wn * 128 + 64 * ch + 32 * vl + 16 * hb;   // first of the 16 channels, inside the tile
+            const int n16 = tn * 256 + nl;
+            if (n16 >= p.N) continue;                    // N % 64 == 0: a 16-channel segment is all in or all out
+            float sn[16];
+            int zn[16];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) sn[x] = OUT == OUT_FP16 ? __half2float(p.scales[n0 + x]) : 0.f;
-            if (!GROUP) {
-#pragma unroll
-                for (int x = 0; x < 4; ++x) zn[x] = p.zeros[n0 + x];
-            }
+            for (int x = 0; x < 16; ++x) { sn[x] = OUT == OUT_FP16 ? __half2float(e_sn[nl + x]) : 0.f; zn[x] = GROUP ? 0 : (int)e_zn[nl + x]; }
 #pragma unroll
             for (int tf = 0; tf < 4; ++tf) {
-                const int m = m_base + wm * 128 + tf * 32 + r32;
+                const int ml = wm * 128 + tf * 32 + r32;
+                const int m = m_base + ml;
                 if (m >= p.M) continue;
-                const v4i val = {acc[cf][tf][4 * v4], acc[cf][tf][4 * v4 + 1], acc[cf][tf][4 * v4 + 2], acc[cf][tf][4 * v4 + 3]};
-                finish4<GROUP, OUT>(p, m, n0, val, sn, zn, OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f,
-                                    GROUP ? 0 : p.rowsum[m]);
+                const float sxm = OUT == OUT_FP16 ? __half2float(e_sx[ml]) : 0.f;
+                const int rs = GROUP ? 0 : e_rs[ml];
+                int t[16];
+#pragma unroll
+                for (int piece = 0; piece < 4; ++piece) {
+                    const int cf = 2 * ch + (piece >> 1), v4 = 2 * (piece & 1) + vl;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        t[4 * piece + x] = acc[cf][tf][4 * v4 + x];
+                        if (!GROUP) t[4 * piece + x] -= zn[4 * piece + x] * rs;
+                    }
+                }
+                if constexpr (OUT == OUT_I32) {
+                    int4* dst = reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n16);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) dst[q] = make_int4(t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]);
+                } else {
+                    uint32_t h[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const __half lo = __float2half_rn((float)t[2 * j] * (sxm * sn[2 * j]));
+                        const __half hi = __float2half_rn((float)t[2 * j + 1] * (sxm * sn[2 * j + 1]));
+                        h[j] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
+                    }
+                    uint4* dst = reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n16);
+                    dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
+                    dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
+                }
             }
         }
     }
