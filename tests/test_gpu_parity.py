@@ -86,7 +86,7 @@ def test_pack_quantized_roundtrip(api):
 
 
 # ---------------------------------------------------------------------------- activations
-@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008)])
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768), (3, 40960)])
 def test_act_quant_matches_oracle(api, M, K):
     _, x = rand_inputs(M, 64, K, seed=M * 7 + K)
     qx, sx, rowsum, tx = api.quant_act_per_token(x, want_rowsum=True, want_tx=True)
