@@ -389,13 +389,15 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
     const size_t m_g_stride = (size_t)nf_total * 32;
     int i_block = iw.block;
 
-    // Copies for the iteration at the issue walk.  Past the end of the run the last iteration is
-    // simply copied again, so that every iteration issues the same number of copies.
+    // Copies for the iteration at the issue walk.  Past the end of the run every iteration still issues
+    // the same number of copies (the wait counts rely on it); the walk then rests one group past the last
+    // one consumed, which may be group G, so the group index is clamped: group G of the last token row
+    // (or of the last fragment) would lie beyond the end of the tensor.
     int islot = 0;
     auto issue = [&]() {
         const int n = min(2, max(iw.left, 1));
         if (producer) {
-            const int g = iw.g + (pk < n ? pk : 0);
+            const int g = min(iw.g + (pk < n ? pk : 0), G - 1);
 #pragma unroll
             for (int b = 0; b < kABlocks; ++b)
                 dma16(abase + (size_t)g * kGroup, a_voff[b], aring_addr + islot * kASlot + b * 1024);
@@ -403,7 +405,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
             if (pk == 0) dma4(sbase, s_voff + (uint32_t)i_block * s_blk_stride, sring_addr + islot * 256);
             islot = islot + 1 == kARing ? 0 : islot + 1;
         } else {
-            dma16(w_row + (size_t)(iw.g + (e < n ? e : 0)) * 1024, w_voff, wring_addr + islot * 1024);
+            dma16(w_row + (size_t)min(iw.g + (e < n ? e : 0), G - 1) * 1024, w_voff, wring_addr + islot * 1024);
             islot = islot + 1 == kWRing ? 0 : islot + 1;
         }
         if (iw.left > 0 && walk_step(iw, n, G) && iw.left > 0) {
@@ -959,6 +961,19 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
 {
     const int64_t G = K / kGroup;
     tile_m = forced.tile_m ? forced.tile_m : (M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128);
+    if (!forced.tile_m && M > 64) {
+        // Between the two regimes (a few hundred tokens) the 256 x 256 tiles of the compute-bound kernel are
+        // too few to fill 256 CUs and each walks all of K serially, while the streaming kernel, run once per
+        // 64-token tile, re-reads the weights but spreads K over the whole chip.  Pick by a cost model fitted
+        // to measurements on MI355X (microseconds): streaming ~ 6 + m_tiles * max(7, weight MB / 2.3),
+        // compute-bound ~ rounds * (8 + 1.15 * groups).
+        const double m_tiles = (double)((M + 63) / 64);
+        const double w_mb = (double)K * (double)N / 2.0e6;
+        const double est_stream = 6.0 + m_tiles * (w_mb / 2.3 > 7.0 ? w_mb / 2.3 : 7.0);
+        const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+        const double est_mma = (double)((tiles + 255) / 256) * (8.0 + 1.15 * (double)G);
+        if (est_stream < 0.9 * est_mma) tile_m = 64;
+    }
     if (tile_m <= 64) {
         const int64_t units = (N / 64) * G;
         // one workgroup per CU; when the number of 64-channel blocks already fills most of the

@@ -152,6 +152,13 @@ def test_group_forced_variants(api, tile_m, split_k):
     run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
 
 
+@pytest.mark.parametrize("M,tile_m,split_k", [(256, 64, 0), (256, 64, 8), (200, 32, 6), (320, 64, 12)])
+def test_group_streaming_kernel_many_token_tiles(api, M, tile_m, split_k):
+    """The M <= 64 kernel forced onto several token tiles, with runs that end exactly at a block end and
+    blocks shared between workgroups (cross-workgroup reduction per token tile)."""
+    run_group_case(api, M, 256, 1024, seed=23, tile_m=tile_m, split_k=split_k)
+
+
 def test_group_several_tiles_all_axes(api):
     run_group_case(api, 300, 1088, 2048, seed=11)
 
