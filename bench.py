@@ -4,8 +4,8 @@
 Default workload (`llama2_7b_decode_m64`): the four Llama-2-7B-shaped linear layers (fused
 QKV, O-proj, fused gate+up, down) at M = 64 tokens, group size 128, seeded synthetic FP16
 weights/activations with 1% outlier channels.  One step = one pass over the four layers;
-each layer runs per-token activation quantization, then the W4A8 GEMM (weights are packed
-once, offline, before the timed region).  Several independently packed copies of the layer
+each layer runs per-token activation quantization and the W4A8 GEMM through qoq_w4a8_linear
+(two kernels back to back; weights are packed once, offline, before the timed region).  Several independently packed copies of the layer
 set are rotated so the weights of a step come from HBM, not from the 256 MB Infinity Cache,
 as they do when a whole model's layers stream through.
 
@@ -88,6 +88,7 @@ def main():
             qx=torch.empty((M, K), dtype=torch.int8, device=dev),
             sx=torch.empty(M, dtype=torch.float16, device=dev),
             out=torch.empty((M, N), dtype=torch.float16, device=dev),
+            rowsum=torch.empty(M, dtype=torch.int32, device=dev),
             ws=api.new_workspace(api.gemm_workspace_bytes(M, N, K), dev))
     L = api.lib()
     stream = torch.cuda.current_stream()
@@ -109,9 +110,9 @@ def main():
         s = sp if s is None else s
         for name, (K, N) in layers:
             b = bufs[name]
-            check(L.qoq_quant_act_per_token(P(xs[name]), M, K, P(b["qx"]), P(b["sx"]), None, None, s))
-            check(L.qoq_w4a8_gemm(P(b["qx"]), P(b["sx"]), None, P(blobs[name][step % args.copies]), M, N, K, 0,
-                                  P(b["out"]), P(b["ws"]), b["ws"].numel(), s))
+            # per-token activation quantization, then the GEMM (two kernels back to back)
+            check(L.qoq_w4a8_linear(P(xs[name]), P(blobs[name][step % args.copies]), M, N, K, 0, P(b["out"]),
+                                    P(b["qx"]), P(b["sx"]), P(b["rowsum"]), P(b["ws"]), b["ws"].numel(), s))
 
     def timed(fn, steps, warmup):
         """Warm up eagerly, then time `steps` steps.  The launches of `copies` consecutive steps are
@@ -153,7 +154,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "llama2_7b_decode_m%d" % M, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
                    "M": M, "group": 128, "mode": "group128", "weight_copies_rotated": args.copies,
-                   "step": "4 x (qoq_quant_act_per_token + qoq_w4a8_gemm), launches replayed from a HIP graph"},
+                   "step": "4 x qoq_w4a8_linear (per-token activation quantization + W4A8 GEMM), launches replayed from a HIP graph"},
         "roofline": {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH_DEFAULT if (M == 64 and args.copies == 8) else None,

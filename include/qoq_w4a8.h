@@ -114,6 +114,21 @@ int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packe
                       int64_t M, int64_t N, int64_t K, int mode,
                       int32_t* acc, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Activation quantization and GEMM in one call: exactly
+ *   qoq_quant_act_per_token(x -> qx, sx, rowsum);  qoq_w4a8_gemm(qx, sx, rowsum, packed -> out)
+ * enqueued back to back on `stream` (Section 5.1 places the activation quantization directly in front of
+ * the GEMM).  A single-launch variant, in which a few workgroups quantize the rows while the others
+ * prefetch weights and a counter releases them, was measured slower than the two launches on MI355X (the
+ * device-wide hand-over costs more than a launch) and is not part of the library.
+ *   x_fp16     [M, K] FP16 row-major (read only)
+ *   qx         [M, K] INT8 (written), sx_fp16 [M] FP16 (written)
+ *   rowsum     [M] INT32 (written); required in per-channel mode, may be NULL in group mode
+ *   workspace  as for qoq_w4a8_gemm (qoq_gemm_workspace_bytes)
+ * Same shape, alignment and error rules as qoq_w4a8_gemm. */
+int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N, int64_t K, int mode,
+                    void* out_fp16, int8_t* qx, void* sx_fp16, int32_t* rowsum,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
 /* Test/tuning hook: force the GEMM launch configuration instead of the built-in heuristic.
  * tile_m in {0 (auto), 16, 32, 64 (streaming kernel), 128 (tiled kernel)}.  split_k >= 0
  * (0 = auto): for the tiled kernel the number of k-slices per output tile, for the streaming

@@ -39,6 +39,9 @@ _SIGNATURES = {
     "qoq_w4a8_gemm_i32": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "qoq_w4a8_linear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                       ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_set_gemm_config": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
 }
 
@@ -189,3 +192,22 @@ def w4a8_gemm_i32(qx, packed, N, mode=QOQ_GROUP128, rowsum=None, out=None, works
     _check(lib().qoq_w4a8_gemm_i32(_ptr(qx), _ptr(rowsum), _ptr(packed), M, N, K, mode, _ptr(out),
                                    _ptr(workspace), ws_bytes, _stream(qx.device)))
     return out
+
+
+def w4a8_linear(x, packed, N, mode=QOQ_GROUP128, out=None, qx=None, sx=None, rowsum=None, workspace=None):
+    """Activation quantization + GEMM in one call; returns (out FP16 [M,N], qx, sx, rowsum)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    dev = x.device
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=dev)
+    if qx is None:
+        qx = torch.empty((M, K), dtype=torch.int8, device=dev)
+    if sx is None:
+        sx = torch.empty(M, dtype=torch.float16, device=dev)
+    if rowsum is None:
+        rowsum = torch.empty(M, dtype=torch.int32, device=dev)
+    workspace, ws_bytes = _workspace(M, N, K, mode, dev, workspace)
+    _check(lib().qoq_w4a8_linear(_ptr(x), _ptr(packed), M, N, K, mode, _ptr(out), _ptr(qx), _ptr(sx), _ptr(rowsum),
+                                 _ptr(workspace), ws_bytes, _stream(dev)))
+    return out, qx, sx, rowsum

@@ -34,8 +34,10 @@ int arch_ok()
 
 int check_shape(int64_t N, int64_t K, int mode) { return qoq::shape_ok(N, K, mode) ? QOQ_OK : QOQ_ERR_SHAPE; }
 
+// x_fp16 != NULL: quantize the activations first (into qx, sx, rowsum) by a launch of the activation kernel.
 int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const void* packed, int64_t M, int64_t N,
-                int64_t K, int mode, void* out16, int32_t* out32, void* ws, size_t ws_bytes, void* stream)
+                int64_t K, int mode, void* out16, int32_t* out32, void* ws, size_t ws_bytes, void* stream,
+                const void* x_fp16 = nullptr)
 {
     if (check_shape(N, K, mode) != QOQ_OK || M < 0 || M > (1 << 24)) return QOQ_ERR_SHAPE;
     if (M * N >= ((int64_t)1 << 40)) return QOQ_ERR_SHAPE;
@@ -49,7 +51,12 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     if ((uint64_t)M * (uint64_t)K >= ((uint64_t)1 << 32)) return QOQ_ERR_SHAPE;  // 32-bit activation offsets
     const size_t need = qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
     if (need && (!ws || ws_bytes < need)) return QOQ_ERR_WORKSPACE;
+    if (x_fp16 && !aligned16(x_fp16)) return QOQ_ERR_ALIGN;
     if (!arch_ok()) return QOQ_ERR_ARCH;
+    if (x_fp16 &&
+        qoq::launch_act_quant(x_fp16, M, K, const_cast<int8_t*>(qx), const_cast<void*>(sx), const_cast<int32_t*>(rowsum),
+                              nullptr, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QOQ_ERR_HIP;
     qoq::GemmArgs a;
     a.qx = qx; a.sx = sx; a.rowsum = rowsum; a.blob = static_cast<const uint8_t*>(packed);
     a.M = M; a.N = N; a.K = K; a.mode = mode;
@@ -88,6 +95,15 @@ size_t qoq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int mode)
     int tile_m, split_k;
     qoq::pick_gemm_config(M, N, K, forced(), tile_m, split_k);
     return qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
+}
+
+int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N, int64_t K, int mode, void* out_fp16,
+                    int8_t* qx, void* sx_fp16, int32_t* rowsum, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M > 0 && !x_fp16) return QOQ_ERR_NULL;
+    if (M > 0 && !out_fp16) return QOQ_ERR_NULL;
+    return gemm_common(qx, sx_fp16, rowsum, packed, M, N, K, mode, out_fp16, nullptr, workspace, workspace_bytes, stream,
+                       x_fp16);
 }
 
 int qoq_gemm_workspace_prepare(void* workspace, size_t workspace_bytes, void* stream)

@@ -247,3 +247,34 @@ def test_runtime_errors_leave_outputs_untouched(api):
     assert e.value.status == 4
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+# ---------------------------------------------------------------------------- quantization + GEMM in one call
+@pytest.mark.parametrize("M,N,K,mode", [(64, 256, 1024, 0), (1, 128, 256, 0), (17, 320, 640, 0), (48, 4096, 4096, 0),
+                                        (64, 256, 1024, 1), (33, 4096, 11008, 1), (100, 256, 1024, 0),
+                                        (300, 512, 1024, 1)])
+def test_linear_equals_quant_then_gemm(api, M, N, K, mode):
+    """qoq_w4a8_linear == qoq_quant_act_per_token followed by qoq_w4a8_gemm, bit for bit, and matches the
+    oracle; called three times on the same buffers with different inputs (the second and third call must
+    not see anything of the previous one: counters re-armed, no stale activations)."""
+    w, _ = rand_inputs(M, N, K, seed=5 + M + K + mode)
+    blob = api.pack_weights(w, mode)
+    dev = w.device
+    out = torch.empty((M, N), dtype=torch.float16, device=dev)
+    qx = torch.empty((M, K), dtype=torch.int8, device=dev)
+    sx = torch.empty(M, dtype=torch.float16, device=dev)
+    rowsum = torch.empty(M, dtype=torch.int32, device=dev)
+    ws = api.new_workspace(max(16, api.gemm_workspace_bytes(M, N, K, mode)), dev)
+    for rep in range(3):
+        x = wl.make_activations(M, K, 1000 * rep + M + K, DEV, outlier_count=max(1, K // 100))
+        if rep == 1 and M >= 4:
+            x[1] = 0
+        api.w4a8_linear(x, blob, N, mode, out=out, qx=qx, sx=sx, rowsum=rowsum, workspace=ws)
+        qx2, sx2, rowsum2, _ = api.quant_act_per_token(x)
+        out2 = api.w4a8_gemm(qx2, sx2, blob, N, mode, rowsum=rowsum2 if mode else None)
+        assert torch.equal(qx, qx2) and torch.equal(sx.view(torch.int16), sx2.view(torch.int16))
+        assert torch.equal(rowsum, rowsum2)
+        assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+        ref = (ogemm.forward_per_channel if mode else ogemm.forward_group)(_np(w), _np(x))
+        check_fp16(out, ref["out64"])
+        assert (_np(qx).astype(np.int64) == ref["qx"]).all()
