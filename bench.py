@@ -147,22 +147,32 @@ def main():
     gemm_gbs = byts / (ms_gemm * 1e-3) / 1e9
     gemm_tops = ops / (ms_gemm * 1e-3) / 1e12
 
+    # The GEMM launch is bound by HBM at decode sizes and by the INT8 matrix cores once there are a few hundred
+    # tokens (ridge of the published peaks: 629 ops per byte, i.e. about 160 tokens for 4-bit weights).
+    if M <= 128:
+        roofline = {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
+                    "traffic": TRAFFIC_BYTES_PER_LAUNCH_DEFAULT if (M == 64 and args.copies == 8) else None}
+    else:
+        roofline = {"bound": "mfma", "achieved": round(gemm_tops, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": None}
+    roofline.update({"kernel": "qoq_w4a8_gemm launch (average over the four layers)",
+                     "avg_launch_us": round(ms_gemm * 1e3 / len(layers), 3),
+                     "algorithmic_bytes_per_launch": round(byts / len(layers)),
+                     "algorithmic_ops_per_launch": round(ops / len(layers)),
+                     "gemm_only_tops": round(gemm_tops, 3), "gemm_only_gbs": round(gemm_gbs, 1),
+                     "int8_mfma_frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
+                     "hbm_frac": round(gemm_gbs / HBM_PEAK_GBS, 4)})
+
     result = {
         "metric": "W4A8 GEMM effective TOPS (Llama-2-7B-shaped layers, M=%d, g128)" % M,
         "value": round(tops, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "llama2_7b_decode_m%d" % M, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
+        "config": {"workload": ("llama2_7b_decode_m%d" if M <= 128 else "llama2_7b_prefill_m%d") % M, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
                    "M": M, "group": 128, "mode": "group128", "weight_copies_rotated": args.copies,
                    "step": "4 x qoq_w4a8_linear (per-token activation quantization + W4A8 GEMM), launches replayed from a HIP graph"},
-        "roofline": {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH_DEFAULT if (M == 64 and args.copies == 8) else None,
-                     "kernel": "qoq_w4a8_gemm launch (average over the four layers)",
-                     "avg_launch_us": round(ms_gemm * 1e3 / len(layers), 3),
-                     "algorithmic_bytes_per_launch": round(byts / len(layers)),
-                     "gemm_only_tops": round(gemm_tops, 3),
-                     "int8_mfma_frac": round(gemm_tops / INT8_PEAK_TOPS, 4)},
+        "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
