@@ -36,6 +36,7 @@
 //     order, double buffered, one barrier per group; plain split-k with the same counter scheme.
 //   * epilogue (Section 5.2.2): FP32 acc * (sx[m] * s[n]), one rounding to FP16.
 #include <hip/hip_fp16.h>
+#include <algorithm>
 #include <hip/hip_runtime.h>
 
 #include "qoq_internal.h"
@@ -613,7 +614,10 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int G = p.G, H = 2 * p.G;
+    const int G = p.G;
+    // split-k: blockIdx.y selects a run of p.gps groups; the slices of a tile meet in the workspace (below)
+    const int slice = blockIdx.y;
+    const int g_first = slice * p.gps, Gs = min(G - g_first, p.gps);
     // Workgroup -> tile.  Consecutive workgroup ids land on consecutive XCDs (8, each with its own L2), so
     // workgroup i is the (i / 8)-th of XCD i % 8.  Each XCD gets a contiguous run of a tile order that walks
     // panels of four token tiles column by column: the 32 tiles an XCD works on at a time form a 4 x 8 block
@@ -662,12 +666,13 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * 4 + u, nf_total - 1) * G * 1024;
     const char* mrow = reinterpret_cast<const char*>(p.meta) + (size_t)min(nf_base + wave * 4, nf_total - 4) * 32;
     const size_t m_g_stride = (size_t)nf_total * 32;
-    int ca = 0, cw = 0;   // next half-stage / group to copy; past the end the last one is copied again into a free slab
+    int ca = 2 * g_first, cw = g_first;   // next half-stage / group to copy; past the end of the slice the last one is copied again into a free slab
+    const int ca_last = 2 * (g_first + Gs) - 1, cw_last = g_first + Gs - 1;
     auto copy_a = [&](int t, int slot) { dma16(abase + (size_t)ca * 64, a_voff[t], a_dst + (uint32_t)(slot * kASlotBytes + t * 1024)); };
     auto copy_w = [&](int u, int slot) { dma16(wrow[u] + (size_t)cw * 1024, w_voff, w_dst + (uint32_t)(slot * kWSlotBytes + u * 1024)); };
     auto copy_m = [&](int slot) { if (GROUP) dma4(mrow + (size_t)cw * m_g_stride, m_voff, m_dst + (uint32_t)(slot * kMSlotBytes)); };
-    auto adv_a = [&]() { ca = min(ca + 1, H - 1); };
-    auto adv_w = [&]() { cw = min(cw + 1, G - 1); };
+    auto adv_a = [&]() { ca = min(ca + 1, ca_last); };
+    auto adv_w = [&]() { cw = min(cw + 1, cw_last); };
 
     // Epilogue constants of the tile (token scales, channel scales; per-channel mode: token sums, zero points)
     // are copied into LDS first of all, so they are the oldest entries of each wave's copy queue and cost no
@@ -804,7 +809,7 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     deq_phase(0, rq[1], 0, S[1], B[1], dq, w_nxt);        // block 1 is one phase ahead, as in the steady state
 
     int gs = 0;                                          // g % 3
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < Gs; ++g) {
         const int gp1 = gs == 2 ? 0 : gs + 1, gm1 = gs == 0 ? 2 : gs - 1;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {                    // half-stage h = 2g + s
@@ -868,6 +873,51 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     }
 
     wait_vmcnt<0>();   // the repeated tail copies still target the ring
+
+    // ---- split-k: every slice writes its partial tile through to memory and bumps the tile's counter; the last
+    // one to arrive adds the others' (integer sums: exact, order independent) and alone runs the epilogue.
+    // Same fence-free hand-over as in the streaming kernel; the counter is left at zero for the next launch.
+    if (p.S > 1) {
+        __shared__ int s_last;
+        const int tile_id = tm * n_tiles + tn;
+        int4* mine = p.parts + ((size_t)(tile_id * p.S + slice) * 64) * kMmaThreads + threadIdx.x;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) {
+            const int cf = j >> 4, tf = (j >> 2) & 3, qd = j & 3;
+            store_sc1(mine + (size_t)j * kMmaThreads, (v4i){acc[cf][tf][4 * qd], acc[cf][tf][4 * qd + 1],
+                                                            acc[cf][tf][4 * qd + 2], acc[cf][tf][4 * qd + 3]});
+        }
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int* ctr = p.counters + tile_id;
+            const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = old == p.S - 1;
+            if (s_last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!s_last) return;
+        for (int s2 = 0; s2 < p.S; ++s2) {
+            if (s2 == slice) continue;
+            const int4* theirs = p.parts + ((size_t)(tile_id * p.S + s2) * 64) * kMmaThreads + threadIdx.x;
+#pragma unroll
+            for (int j0 = 0; j0 < 64; j0 += 4) {
+                v4i t[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) load_sc1_nowait(t[x], theirs + (size_t)(j0 + x) * kMmaThreads);
+                wait_loads(t[0], t[1], t[2], t[3]);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int j = j0 + x, cf = j >> 4, tf = (j >> 2) & 3, qd = j & 3;
+                    acc[cf][tf][4 * qd] += t[x].x;
+                    acc[cf][tf][4 * qd + 1] += t[x].y;
+                    acc[cf][tf][4 * qd + 2] += t[x].z;
+                    acc[cf][tf][4 * qd + 3] += t[x].w;
+                }
+            }
+        }
+    }
+
     const __half* e_sx = reinterpret_cast<const __half*>(ering);
     const __half* e_sn = e_sx + 256;
     const int* e_rs = reinterpret_cast<const int*>(ering + 1024);
@@ -942,7 +992,7 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
         else if (tile_m == 32) launch_stream<2, GROUP>(p, fp16, grid, s);
         else launch_stream<4, GROUP>(p, fp16, grid, s);
     } else {
-        const dim3 grid((unsigned)(((p.N + 255) / 256) * ((p.M + 255) / 256)));
+        const dim3 grid((unsigned)(((p.N + 255) / 256) * ((p.M + 255) / 256)), (unsigned)p.S);
         if (fp16) mma_kernel<GROUP, OUT_FP16><<<grid, kMmaThreads, 0, s>>>(p);
         else mma_kernel<GROUP, OUT_I32><<<grid, kMmaThreads, 0, s>>>(p);
     }
@@ -957,6 +1007,20 @@ int64_t tiles_of(int64_t M, int64_t N, int tile_m)
 
 // split_k: tiled kernel = number of k-slices per tile; stream kernel = number of workgroups the
 // unit stream is dealt to (per m-tile).
+// k-slices of the compute-bound kernel: only when its 256 x 256 tiles leave most CUs idle and every slice
+// still has a long run of groups (a partial tile costs 256 KiB of traffic each way).
+static int mma_split(int64_t M, int64_t N, int64_t G, int forced_split)
+{
+    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    int64_t S = 1;
+    if (forced_split > 0) S = forced_split;
+    else if (tiles < 160) S = std::min<int64_t>(256 / tiles, G / 24);
+    if (S > G) S = G;
+    if (S < 1) S = 1;
+    const int64_t gps = (G + S - 1) / S;
+    return (int)((G + gps - 1) / gps);
+}
+
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
@@ -970,8 +1034,9 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
         const double m_tiles = (double)((M + 63) / 64);
         const double w_mb = (double)K * (double)N / 2.0e6;
         const double est_stream = 6.0 + m_tiles * (w_mb / 2.3 > 7.0 ? w_mb / 2.3 : 7.0);
-        const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
-        const double est_mma = (double)((tiles + 255) / 256) * (8.0 + 1.15 * (double)G);
+        const int S = mma_split(M, N, G, 0);
+        const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256) * S;
+        const double est_mma = (double)((tiles + 255) / 256) * (8.0 + 1.15 * (double)((G + S - 1) / S)) + (S > 1 ? 20.0 : 0.0);
         if (est_stream < 0.9 * est_mma) tile_m = 64;
     }
     if (tile_m <= 64) {
@@ -987,7 +1052,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
         split_k = (int)((units + upw - 1) / upw);
         return;
     }
-    split_k = 1;   // the compute-bound kernel does not split k
+    split_k = mma_split(M, N, G, forced.split_k);
 }
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
@@ -1000,7 +1065,9 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int spl
         const size_t counters = align256((size_t)(m_tiles * (N / 64)) * sizeof(int));
         return counters + (size_t)m_tiles * (size_t)split_k * 2 * (size_t)(tile_m * 64) * sizeof(int32_t);
     }
-    return 0;
+    if (split_k <= 1) return 0;
+    const size_t tiles = (size_t)(((M + 255) / 256) * ((N + 255) / 256));
+    return align256(tiles * sizeof(int)) + tiles * (size_t)split_k * 256 * 256 * sizeof(int32_t);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
@@ -1029,9 +1096,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         counters = align256((size_t)(((a.M + a.tile_m - 1) / a.tile_m) * (a.N / 64)) * sizeof(int));
     } else {
         p.upw = 0;
-        p.S = 1;
-        p.gps = (int)L.G;
-        counters = 0;
+        p.S = a.split_k;
+        p.gps = (int)((L.G + a.split_k - 1) / a.split_k);
+        counters = align256((size_t)(((a.M + 255) / 256) * ((a.N + 255) / 256)) * sizeof(int));
     }
     p.parts = reinterpret_cast<int4*>(reinterpret_cast<uint8_t*>(a.workspace) + counters);
     if (a.mode == 0) launch_any<true>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);
