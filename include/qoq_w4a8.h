@@ -130,10 +130,11 @@ int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* Test/tuning hook: force the GEMM launch configuration instead of the built-in heuristic.
- * tile_m in {0 (auto), 16, 32, 64 (streaming kernel), 128 (tiled kernel)}.  split_k >= 0
- * (0 = auto): for the tiled kernel the number of k-slices per output tile, for the streaming
- * kernel the number of workgroups the stream of work units is dealt to.  Process-wide; returns
- * QOQ_ERR_SHAPE for values outside the set.  Workspace sizes depend on it. */
+ * tile_m: 0 = auto; 16, 32, 64 = streaming kernel with that many tokens per tile; 128, 129, 130 =
+ * compute-bound kernel with tiles of 256 x 256, 128 x 256, 256 x 128 (tokens x channels).
+ * split_k >= 0 (0 = auto): for the compute-bound kernel the number of k-slices per output tile, for the
+ * streaming kernel the number of workgroups the stream of work units is dealt to.  Process-wide;
+ * returns QOQ_ERR_SHAPE for values outside the set.  Workspace sizes depend on it. */
 int qoq_set_gemm_config(int tile_m, int split_k);
 
 #ifdef __cplusplus

@@ -581,32 +581,43 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
 }
 
 // ------------------------------------------------------------------------------------------
-// "mma" kernel (compute bound, M > 64): 256 tokens x 256 channels per workgroup.
-// Four waves in a 2 x 2 grid own 128 x 128 outputs each: 256 accumulator registers per lane, so
-// exactly one wave per SIMD, and nothing but that wave's own instruction stream can keep the matrix
-// pipe busy.  The main loop is therefore software pipelined by hand into "chunks" of one
-// v_mfma_i32_32x32x32_i8 (32 cycles) plus what fits in its shadow: a quarter of the dequantization
-// of the NEXT weight operand (one operand = 4 dwords, reused by the four token fragments of the
-// wave: 3.5 vector instructions per MFMA), at most one LDS read and at most one copy.  A scheduling
-// barrier after every chunk keeps the compiler from regrouping them.
+// "mma" kernel (compute bound, M > 64).  Four waves per workgroup, exactly one per SIMD; a wave owns
+// 128 tokens x (32 * CF) channels in 4 x CF accumulator tiles of v_mfma_i32_32x32x32_i8 (CF = 4: 256
+// accumulator registers per lane).  Three workgroup shapes share the code:
+//     CF = 4, waves 2 x 2 : 256 tokens x 256 channels  (large problems: fewest bytes per MFMA)
+//     CF = 2, waves 1 x 4 : 128 tokens x 256 channels  (few tokens)
+//     CF = 2, waves 2 x 2 : 256 tokens x 128 channels  (few channels)
+// With one wave per SIMD nothing but that wave's own instruction stream keeps the matrix pipe busy, so the
+// main loop is software pipelined by hand into "chunks" of one MFMA (32 cycles) plus what fits in its
+// shadow: a quarter of the dequantization of a LATER weight operand (one operand = 4 dwords, reused by the
+// four token fragments of the wave: 3.5 vector instructions per MFMA), at most two LDS reads and at most
+// one copy.  A scheduling barrier after every chunk keeps the compiler from regrouping them.
 //
-// Copies are global->LDS DMA in half-group steps (k = 64): activations in a ring of six 16 KiB
-// slabs, packed weights (whole groups: the 16-byte lane word covers both halves) and metadata in
-// rings of three.  During half-stage h, six blocks in, a wave waits for its own copies of half-stage
-// h+1 and all waves meet: that publishes h+1 and proves h-1 is no longer read, so its slab is
-// refilled with h+5 (weights of group g+2 go out with the even half-stages).  The last two blocks
-// of h overlap the first LDS reads and the first dequantization of h+1, so the matrix pipe does not
-// drain at the barrier.  grid = (m-tiles * n-tiles).
+// Copies are global->LDS DMA in half-group steps (k = 64): activations in a ring of six slabs, packed
+// weights (whole groups: the 16-byte lane word covers both halves) and metadata in rings of three.  In the
+// middle of half-stage h a wave waits for its own copies of half-stage h+1 and all waves meet: that
+// publishes h+1 and proves h-1 is no longer read, so its slab is refilled with h+5 (weights of group g+2 go
+// out with the even half-stages).  The rest of h overlaps the first LDS reads and the first dequantization
+// of h+1, so the matrix pipe does not drain at the barrier.  grid = (m-tiles * n-tiles, k-slices).
 // ------------------------------------------------------------------------------------------
 typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kMmaThreads = 256;
-constexpr int kASlots = 6, kASlotBytes = 16384;     // activations: 256 tokens x 64 k per half-stage
-constexpr int kWSlots = 3, kWSlotBytes = 16384;     // weights: 16 units (256 channels x 128 k)
+constexpr int kASlots = 6;                          // activation slabs: (tokens of the tile) x 64 k per half-stage
+constexpr int kWSlots = 3;                          // weight slabs: (channels of the tile) x 128 k, 1 KiB per 16 channels
 constexpr int kMSlotBytes = 1024;                   // metadata: 256 B per copying wave
 
-template <bool GROUP, int OUT>
+template <bool GROUP, int OUT, int CF, int WM>
 __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 {
+    constexpr int WN = 4 / WM;                      // waves along the channels
+    constexpr int TMt = 128 * WM, TNt = 32 * CF * WN;   // tile: tokens x channels
+    constexpr int kABlocks = TMt / 16;              // 1 KiB blocks (16 tokens x 64 k) per activation slab
+    constexpr int kUnits = TNt / 16;                // 1 KiB weight units per slab
+    constexpr int kASlotBytes = kABlocks * 1024, kWSlotBytes = kUnits * 1024;
+    constexpr int kACopies = kABlocks / 4, kWCopies = kUnits / 4;     // per wave
+    constexpr int NB = 2 * CF;                      // blocks (k32-step jj, channel fragment cf) per half-stage
+    constexpr int NC = 4 * NB;                      // chunks per half-stage
+    constexpr int BAR = CF == 4 ? 16 : 4;           // chunk in front of which the half-stage's barrier sits
     __shared__ __attribute__((aligned(16))) char aring[kASlots * kASlotBytes];
     __shared__ __attribute__((aligned(16))) char wring[kWSlots * kWSlotBytes];
     __shared__ __attribute__((aligned(16))) char mring[kWSlots * kMSlotBytes];
@@ -622,7 +633,7 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     // workgroup i is the (i / 8)-th of XCD i % 8.  Each XCD gets a contiguous run of a tile order that walks
     // panels of four token tiles column by column: the 32 tiles an XCD works on at a time form a 4 x 8 block
     // sharing 4 activation slabs and 8 weight slabs through that XCD's L2.
-    const int n_tiles = (p.N + 255) / 256, m_tiles = (p.M + 255) / 256;
+    const int n_tiles = (p.N + TNt - 1) / TNt, m_tiles = (p.M + TMt - 1) / TMt;
     int tm, tn;
     {
         const int T = n_tiles * m_tiles, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -636,35 +647,36 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         tn = rem / rows;
         tm = panel * kPanel + (rem - tn * rows);
     }
-    const int m_base = tm * 256;
-    const int nf_base = tn * 16;                         // first 16-row fragment (unit row) of the tile
+    const int m_base = tm * TMt, n_base = tn * TNt;
+    const int nf_base = tn * kUnits;                     // first 16-row fragment (unit row) of the tile
     const int nf_total = p.N / 16;
 
-    // ---- copy role: wave w copies token fragments 4w..4w+3, weight units 4w..4w+3 and their metadata.
+    // ---- copy role: wave w copies token blocks kACopies*w.., weight units kWCopies*w.. and their metadata.
     // Activation block = (16-token fragment, 64-wide half-stage): lane 4r+c copies 16-byte chunk
     // c ^ h(r) of token r, so a quad reads one 64-byte row segment and fragment reads are conflict free.
-    constexpr int kOdd = 4, kEven = 8 + (GROUP ? 1 : 0);   // copies a wave issues after an odd / even half-stage's barrier
-    uint32_t a_voff[4];
+    constexpr int kOdd = kACopies, kEven = kACopies + kWCopies + (GROUP ? 1 : 0);   // copies per wave after an odd / even half-stage's barrier
+    static_assert(2 * kOdd + kEven < 64, "vmcnt range");
+    uint32_t a_voff[kACopies];
     {
         const int r = lane >> 2, c = lane & 3;
         const int h = ((r >> 1) ^ (r >> 2)) & 3;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int row = min(m_base + (wave * 4 + t) * 16 + r, p.M - 1);   // rows past M repeat the last one
+        for (int t = 0; t < kACopies; ++t) {
+            const int row = min(m_base + (wave * kACopies + t) * 16 + r, p.M - 1);   // rows past M repeat the last one
             a_voff[t] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((c ^ h) * 16);
         }
     }
     const uint32_t w_voff = (uint32_t)lane * 16u;
-    const uint32_t m_voff = (uint32_t)(lane & 31) * 4u;
-    const uint32_t a_dst = (uint32_t)(uintptr_t)&aring[0] + (uint32_t)wave * 4096u;
-    const uint32_t w_dst = (uint32_t)(uintptr_t)&wring[0] + (uint32_t)wave * 4096u;
+    const uint32_t m_voff = (uint32_t)(lane & (kWCopies * 8 - 1)) * 4u;   // 32 B of metadata per unit
+    const uint32_t a_dst = (uint32_t)(uintptr_t)&aring[0] + (uint32_t)(wave * kACopies) * 1024u;
+    const uint32_t w_dst = (uint32_t)(uintptr_t)&wring[0] + (uint32_t)(wave * kWCopies) * 1024u;
     const uint32_t m_dst = (uint32_t)(uintptr_t)&mring[0] + (uint32_t)wave * 256u;
     const char* abase = reinterpret_cast<const char*>(p.qx);
-    const char* wrow[4];
+    const char* wrow[kWCopies];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)   // units past N repeat the last one; their results are never stored
-        wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * 4 + u, nf_total - 1) * G * 1024;
-    const char* mrow = reinterpret_cast<const char*>(p.meta) + (size_t)min(nf_base + wave * 4, nf_total - 4) * 32;
+    for (int u = 0; u < kWCopies; ++u)   // units past N repeat the last one; their results are never stored
+        wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * kWCopies + u, nf_total - 1) * G * 1024;
+    const char* mrow = reinterpret_cast<const char*>(p.meta) + (size_t)min(nf_base + wave * kWCopies, nf_total - kWCopies) * 32;
     const size_t m_g_stride = (size_t)nf_total * 32;
     int ca = 2 * g_first, cw = g_first;   // next half-stage / group to copy; past the end of the slice the last one is copied again into a free slab
     const int ca_last = 2 * (g_first + Gs) - 1, cw_last = g_first + Gs - 1;
@@ -673,28 +685,33 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     auto copy_m = [&](int slot) { if (GROUP) dma4(mrow + (size_t)cw * m_g_stride, m_voff, m_dst + (uint32_t)(slot * kMSlotBytes)); };
     auto adv_a = [&]() { ca = min(ca + 1, ca_last); };
     auto adv_w = [&]() { cw = min(cw + 1, cw_last); };
+    // k-th copy a wave issues after the barrier of an even (s == 0) or odd half-stage
+    auto refill = [&](int k, int s, int a_islot, int w_islot) {
+        if (k < kACopies) copy_a(k, a_islot);
+        else if (s == 0 && k < kACopies + kWCopies) copy_w(k - kACopies, w_islot);
+        else if (s == 0 && k == kACopies + kWCopies) copy_m(w_islot);
+    };
 
     // Epilogue constants of the tile (token scales, channel scales; per-channel mode: token sums, zero points)
     // are copied into LDS first of all, so they are the oldest entries of each wave's copy queue and cost no
-    // separate wait.  Indices past M / N repeat the last valid dword (never stored from).
+    // separate wait.  256 entries of each are fetched whatever the tile shape; indices past M / N repeat the
+    // last valid dword and are never used.
     {
         const uint32_t e_dst = (uint32_t)(uintptr_t)&ering[0];
+        const int d = wave * 64 + lane;
         if (OUT == OUT_FP16) {
-            if (wave < 2) {
-                const int last = (p.M - m_base - 1) >> 1;                 // dword holding the last token of the tile
-                dma4(reinterpret_cast<const char*>(p.sx) + (size_t)m_base * 2, (uint32_t)min(wave * 64 + lane, last) * 4u,
+            if (wave < 2)      // waves 0, 1: 2 x 64 dwords = 256 token scales
+                dma4(reinterpret_cast<const char*>(p.sx) + (size_t)m_base * 2, (uint32_t)min(d, (p.M - m_base - 1) >> 1) * 4u,
                      e_dst + (uint32_t)wave * 256u);
-            } else {
-                const int last = ((p.N - tn * 256) >> 1) - 1;
-                dma4(reinterpret_cast<const char*>(p.scales) + (size_t)tn * 512, (uint32_t)min((wave - 2) * 64 + lane, last) * 4u,
-                     e_dst + 512u + (uint32_t)(wave - 2) * 256u);
-            }
+            else               // waves 2, 3: 256 channel scales
+                dma4(reinterpret_cast<const char*>(p.scales) + (size_t)n_base * 2,
+                     (uint32_t)min(d - 128, ((p.N - n_base) >> 1) - 1) * 4u, e_dst + 512u + (uint32_t)(wave - 2) * 256u);
         }
         if (!GROUP) {
-            dma4(reinterpret_cast<const char*>(p.rowsum) + (size_t)m_base * 4, (uint32_t)min(wave * 64 + lane, p.M - m_base - 1) * 4u,
+            dma4(reinterpret_cast<const char*>(p.rowsum) + (size_t)m_base * 4, (uint32_t)min(d, p.M - m_base - 1) * 4u,
                  e_dst + 1024u + (uint32_t)wave * 256u);
             if (wave == 0)
-                dma4(reinterpret_cast<const char*>(p.zeros) + (size_t)tn * 256, (uint32_t)min(lane, ((p.N - tn * 256) >> 2) - 1) * 4u,
+                dma4(reinterpret_cast<const char*>(p.zeros) + (size_t)n_base, (uint32_t)min(lane, ((p.N - n_base) >> 2) - 1) * 4u,
                      e_dst + 2048u);
         }
     }
@@ -703,22 +720,22 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 #pragma unroll
     for (int hh = 0; hh < 5; ++hh) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) copy_a(t, hh);
+        for (int t = 0; t < kACopies; ++t) copy_a(t, hh);
         adv_a();
         if (hh & 1) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) copy_w(u, hh >> 1);
+            for (int u = 0; u < kWCopies; ++u) copy_w(u, hh >> 1);
             copy_m(hh >> 1);
             adv_w();
         }
     }
 
     // ---- compute role ---------------------------------------------------------------------------
-    const int wm = wave >> 1, wn = wave & 1;             // 128-token half, 128-channel half
+    const int wm = wave / WN, wn = wave % WN;            // 128-token part, (32 * CF)-channel part of the tile
     const int r32 = lane & 31, kb2 = lane >> 5;
-    v16i acc[4][4];                                      // [channel fragment][token fragment]
+    v16i acc[CF][4];                                     // [channel fragment][token fragment]
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < CF; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -733,21 +750,26 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
         a_rd[jj] = (uint32_t)((wm * 8 + (r32 >> 4)) * 1024 + (4 * arow + (((2 * jj + kb2) & 3) ^ ah)) * 16);
-        //   weights, channel fragment cf (+ cf * 2048; 32 rows = units 2cf, 2cf+1), half s (+ s * 8):
-        //   unit wn*8 + 2cf + r32/16, lane word ((2jj + kb2) % 4) * 16 + r32 % 16
-        w_rd[jj] = (uint32_t)((wn * 8 + (r32 >> 4)) * 1024 + ((((2 * jj + kb2) & 3) * 16) + (r32 & 15)) * 16);
+        //   weights, channel fragment cf (+ cf * 2048; 32 rows = units 2cf, 2cf+1), both halves in one lane word:
+        //   unit wn*2*CF + 2cf + r32/16, lane word ((2jj + kb2) % 4) * 16 + r32 % 16
+        w_rd[jj] = (uint32_t)((wn * 2 * CF + (r32 >> 4)) * 1024 + ((((2 * jj + kb2) & 3) * 16) + (r32 & 15)) * 16);
     }
-    //   metadata of fragment cf: + (cf / 2) * 256 + (cf % 2) * 64
-    const uint32_t m_rd = (uint32_t)(wn * 512 + ((r32 >> 4) * 16 + (r32 & 15)) * 2);
+    //   metadata of unit u = wn*2*CF + 2cf + r32/16: in the 256 B of copying wave u / kWCopies, 32 B per unit
+    uint32_t m_rd[CF];
+#pragma unroll
+    for (int cf = 0; cf < CF; ++cf) {
+        const int u = wn * 2 * CF + 2 * cf + (r32 >> 4);
+        m_rd[cf] = (uint32_t)((u / kWCopies) * 256 + ((u % kWCopies) * 16 + (r32 & 15)) * 2);
+    }
 
     auto lds_a = [&](uint32_t slab, int jj, int tf) {
         return as_v4i(*reinterpret_cast<const uint4*>(aring + slab + a_rd[jj] + tf * 2048));
     };
     auto lds_w = [&](uint32_t slab, int blk) {           // lane word (both halves) of block blk = (jj, cf)
-        return *reinterpret_cast<const uint4*>(wring + slab + w_rd[blk >> 2] + (blk & 3) * 2048);
+        return *reinterpret_cast<const uint4*>(wring + slab + w_rd[blk / CF] + (blk % CF) * 2048);
     };
     auto lds_m = [&](uint32_t slab, int cf) {
-        return (uint32_t)*reinterpret_cast<const uint16_t*>(mring + slab + m_rd + (cf >> 1) * 256 + (cf & 1) * 64);
+        return (uint32_t)*reinterpret_cast<const uint16_t*>(mring + slab + m_rd[cf]);
     };
     const uint32_t nib_mask = 0x0F0F0F0Fu, sign = 0x80808080u;
     auto src_dword = [&](uint4 r, int half, int d) { return half == 0 ? (d < 2 ? r.x : r.y) : (d < 2 ? r.z : r.w); };
@@ -784,29 +806,31 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     wait_vmcnt<2 * kOdd + kEven>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    uint32_t S[4] = {0, 0, 0, 0}, B[4] = {0, 0, 0, 0}, mt[4] = {0, 0, 0, 0};
-    if (GROUP) {
+    uint32_t S[CF], B[CF], mt[CF];
 #pragma unroll
-        for (int cf = 0; cf < 4; ++cf) {
+    for (int cf = 0; cf < CF; ++cf) {
+        S[cf] = B[cf] = mt[cf] = 0;
+        if (GROUP) {
             mt[cf] = lds_m(0, cf);
             S[cf] = __builtin_amdgcn_perm(mt[cf], mt[cf], 0x0c000c00u);
             B[cf] = __builtin_amdgcn_perm(mt[cf], mt[cf], 0x01010101u);
         }
     }
-    // Register-level pipeline.  rq[blk]: lane words of the eight blocks of a group, read four blocks ahead
-    // (blocks 4..7 during blocks 0..3 of the first half, blocks 0..3 of the next group after the barrier of the
-    // second half).  a0: activations of k32-step 0 of a half-stage (read in blocks 4, 5 of the half-stage
-    // before), a1[s]: k32-step 1 (read in blocks 6, 7 of the half-stage before, hence two sets).
-    uint4 rq[8];
+    // Register-level pipeline.  rq[blk]: lane words (both k-halves) of the NB blocks of a group.  CF = 4: blocks
+    // 4..7 are read during blocks 0..3 of the first half-stage, blocks 0..3 of the next group after the barrier
+    // of the second.  CF = 2: all four of the next group are read during the second half-stage, each as soon as
+    // its register is free.  a0: activations of k32-step 0 of a half-stage, a1[s]: k32-step 1 (two sets); both
+    // are read after the barrier of the half-stage before.
+    uint4 rq[NB];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) rq[i] = i < 4 ? lds_w(0, i) : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < NB; ++i) rq[i] = (CF == 2 || i < NB / 2) ? lds_w(0, i) : make_uint4(0, 0, 0, 0);
     v4i a0[4], a1[2][4];
 #pragma unroll
     for (int tf = 0; tf < 4; ++tf) { a0[tf] = lds_a(0, 0, tf); a1[0][tf] = lds_a(0, 1, tf); a1[1][tf] = (v4i){0, 0, 0, 0}; }
     v4i w_cur = {deq1(rq[0], 0, 0, S[0], B[0]), deq1(rq[0], 0, 1, S[0], B[0]), deq1(rq[0], 0, 2, S[0], B[0]), deq1(rq[0], 0, 3, S[0], B[0])};
     v4i w_nxt = {0, 0, 0, 0};
     uint32_t dq[4] = {0, 0, 0, 0};
-    deq_phase(0, rq[1], 0, S[1], B[1], dq, w_nxt);        // block 1 is one phase ahead, as in the steady state
+    deq_phase(0, rq[1], 0, S[1 % CF], B[1 % CF], dq, w_nxt);   // block 1 is one phase ahead, as in the steady state
 
     int gs = 0;                                          // g % 3
     for (int g = 0; g < Gs; ++g) {
@@ -819,50 +843,58 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
             const int a_islot = s == 0 ? 2 * gm1 + 1 : 2 * gs;   // slab of half-stage h-1 = (h+5) % 6
             const int w_islot = gm1;                             // slab of group g-1 = (g+2) % 3
 #pragma unroll
-            for (int c = 0; c < 32; ++c) {               // chunk = (block b = (jj, cf), token fragment tf)
-                const int b = c >> 2, tf = c & 3, jj = b >> 2, cf = b & 3;
-                if (c == 16) {
+            for (int c = 0; c < NC; ++c) {               // chunk = (block b = (jj, cf), token fragment tf)
+                const int b = c >> 2, tf = c & 3, jj = b / CF, cf = b % CF;
+                if (c == BAR) {
                     if (s == 0) wait_vmcnt<2 * kOdd + kEven>(); else wait_vmcnt<kOdd + kEven>();
-#ifndef QOQ_EXP_NOBAR
                     __builtin_amdgcn_s_barrier();
-#endif
                     asm volatile("" ::: "memory");
                 }
                 if (tf == 0 && c != 0) w_cur = w_nxt;    // (for c == 0 the hand-over happened at the end of the previous half-stage)
                 acc[cf][tf] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w_cur, jj == 0 ? a0[tf] : a1[s][tf], acc[cf][tf], 0, 0, 0);
-                {   // one phase of a later operand: chunks (b,0..2) finish block b+1, chunk (b,3) starts block b+2
+                {   // one phase of a later operand: chunks (b,0..2) finish block b+1, chunk (b,3) starts block b+2;
+                    // blocks NB, NB+1 are blocks 0, 1 of the next half-stage
                     const int ph = (tf + 1) & 3;
-                    const int tb = ph == 0 ? b + 2 : b + 1;      // target block; 8, 9 = blocks 0, 1 of the next half-stage
-                    const int half = tb >= 8 ? 1 - s : s;
-#ifndef QOQ_EXP_NODEQ
-                    deq_phase(ph, rq[tb & 7], half, S[tb & 3], B[tb & 3], dq, w_nxt);
-#else
-                    if (ph == 3) w_nxt = as_v4i(rq[tb & 7]);
-#endif
+                    const int tb = ph == 0 ? b + 2 : b + 1;
+                    const int half = tb >= NB ? 1 - s : s;
+                    deq_phase(ph, rq[tb % NB], half, S[tb % CF], B[tb % CF], dq, w_nxt);
                 }
-                if (tf == 0) {                           // lane words four blocks ahead
-                    if (s == 0 && b < 4) rq[b + 4] = lds_w(w_this, b + 4);
-                    if (s == 1 && b >= 4) rq[b - 4] = lds_w(w_next, b - 4);
-                }
-                if (b >= 4 && (tf & 1)) {                // activations of the next half-stage, two fragments per block
-                    const int q = (b & 1) * 2 + (tf >> 1);
-                    if (b < 6) a0[q] = lds_a(a_nxt, 0, q);
-                    else a1[1 - s][q] = lds_a(a_nxt, 1, q);
-                }
-                if (GROUP && s == 1) {                   // level-2 constants of the next group, each after the last use of the old one
-                    if (b == 4) mt[tf] = lds_m(m_nxt, tf);
-                    const int pc = c == 20 ? 0 : c == 22 ? 1 : c == 24 ? 2 : c == 28 ? 3 : -1;
-                    if (pc >= 0) {
-                        S[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x0c000c00u);
-                        B[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x01010101u);
+                if (CF == 4) {
+                    if (tf == 0) {                       // lane words four blocks ahead
+                        if (s == 0 && b < 4) rq[b + 4] = lds_w(w_this, b + 4);
+                        if (s == 1 && b >= 4) rq[b - 4] = lds_w(w_next, b - 4);
+                    }
+                    if (b >= 4 && (tf & 1)) {            // activations of the next half-stage, two fragments per block
+                        const int q = (b & 1) * 2 + (tf >> 1);
+                        if (b < 6) a0[q] = lds_a(a_nxt, 0, q);
+                        else a1[1 - s][q] = lds_a(a_nxt, 1, q);
+                    }
+                    if (GROUP && s == 1) {               // level-2 constants of the next group, each after the last use of the old one
+                        if (b == 4) mt[tf] = lds_m(m_nxt, tf);
+                        const int pc = c == 20 ? 0 : c == 22 ? 1 : c == 24 ? 2 : c == 28 ? 3 : -1;
+                        if (pc >= 0) {
+                            S[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x0c000c00u);
+                            B[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x01010101u);
+                        }
+                    }
+                } else {
+                    if (s == 1) {                        // lane words of the next group, each once its register is free
+                        const int e = c == 4 ? 0 : c == 5 ? 1 : c == 8 ? 2 : c == 12 ? 3 : -1;
+                        if (e >= 0) rq[e] = lds_w(w_next, e);
+                    }
+                    if (c >= 5 && c <= 8) a0[c - 5] = lds_a(a_nxt, 0, c - 5);          // a0[q] is last used in chunk 4 + q
+                    if (c >= 9 && c <= 12) a1[1 - s][c - 9] = lds_a(a_nxt, 1, c - 9);
+                    if (GROUP && s == 1) {
+                        if (c == 4) mt[0] = lds_m(m_nxt, 0);
+                        if (c == 6) mt[1] = lds_m(m_nxt, 1);
+                        const int pc = c == 8 ? 0 : c == 12 ? 1 : -1;                  // old S[0] / S[1] are last used in chunks 5 / 9
+                        if (pc >= 0) {
+                            S[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x0c000c00u);
+                            B[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x01010101u);
+                        }
                     }
                 }
-                if (c >= 16) {                           // refill the slabs the barrier has just freed
-                    const int k = c - 16;
-                    if (k < 4) copy_a(k, a_islot);
-                    else if (k < 8 && s == 0) copy_w(k - 4, w_islot);
-                    else if (k == 8 && s == 0) copy_m(w_islot);
-                }
+                if (c >= BAR) refill(c - BAR, s, a_islot, w_islot);   // refill the slabs the barrier has just freed
                 __builtin_amdgcn_sched_barrier(0);
             }
             w_cur = w_nxt;
@@ -879,10 +911,11 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     // Same fence-free hand-over as in the streaming kernel; the counter is left at zero for the next launch.
     if (p.S > 1) {
         __shared__ int s_last;
+        constexpr int NJ = CF * 16;                      // int4 per thread in a partial tile
         const int tile_id = tm * n_tiles + tn;
-        int4* mine = p.parts + ((size_t)(tile_id * p.S + slice) * 64) * kMmaThreads + threadIdx.x;
+        int4* mine = p.parts + ((size_t)(tile_id * p.S + slice) * NJ) * kMmaThreads + threadIdx.x;
 #pragma unroll
-        for (int j = 0; j < 64; ++j) {
+        for (int j = 0; j < NJ; ++j) {
             const int cf = j >> 4, tf = (j >> 2) & 3, qd = j & 3;
             store_sc1(mine + (size_t)j * kMmaThreads, (v4i){acc[cf][tf][4 * qd], acc[cf][tf][4 * qd + 1],
                                                             acc[cf][tf][4 * qd + 2], acc[cf][tf][4 * qd + 3]});
@@ -899,15 +932,16 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         if (!s_last) return;
         for (int s2 = 0; s2 < p.S; ++s2) {
             if (s2 == slice) continue;
-            const int4* theirs = p.parts + ((size_t)(tile_id * p.S + s2) * 64) * kMmaThreads + threadIdx.x;
+            const int4* theirs = p.parts + ((size_t)(tile_id * p.S + s2) * NJ) * kMmaThreads + threadIdx.x;
 #pragma unroll
-            for (int j0 = 0; j0 < 64; j0 += 4) {
-                v4i t[4];
+            for (int j0 = 0; j0 < NJ; j0 += 16) {          // sixteen loads in flight: the sum is pure load latency
+                v4i t[16];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) load_sc1_nowait(t[x], theirs + (size_t)(j0 + x) * kMmaThreads);
-                wait_loads(t[0], t[1], t[2], t[3]);
+                for (int x = 0; x < 16; ++x) load_sc1_nowait(t[x], theirs + (size_t)(j0 + x) * kMmaThreads);
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
+                for (int x = 0; x < 16; x += 4) wait_loads(t[x], t[x + 1], t[x + 2], t[x + 3]);
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
                     const int j = j0 + x, cf = j >> 4, tf = (j >> 2) & 3, qd = j & 3;
                     acc[cf][tf][4 * qd] += t[x].x;
                     acc[cf][tf][4 * qd + 1] += t[x].y;
@@ -924,15 +958,15 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     const uint8_t* e_zn = reinterpret_cast<const uint8_t*>(ering + 2048);
 
     // ---- epilogue.  Lane (token r32, half hb = kb2) of fragment (cf, tf) holds physical rows 8*(v/4) + 4*hb + v%4,
-    // i.e. logical channels 64*(cf/2) + 32*(v4%2) + 16*hb + 8*(cf%2) + 4*(v4/2) + v%4 of the wave's 128: for fixed
+    // i.e. logical channels 64*(cf/2) + 32*(v4%2) + 16*hb + 8*(cf%2) + 4*(v4/2) + v%4 of the wave's 32*CF: for fixed
     // (cf/2, v4%2) the four pieces (cf%2, v4/2) are 16 consecutive channels = one 32-byte row segment per token.
     const int hb = kb2;
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
+    for (int ch = 0; ch < CF / 2; ++ch) {
 #pragma unroll
         for (int vl = 0; vl < 2; ++vl) {
-            const int nl = wn * 128 + 64 * ch + 32 * vl + 16 * hb;   // first of the 16 channels, inside the tile
-            const int n16 = tn * 256 + nl;
+            const int nl = wn * 32 * CF + 64 * ch + 32 * vl + 16 * hb;   // first of the 16 channels, inside the tile
+            const int n16 = n_base + nl;
             if (n16 >= p.N) continue;                    // N % 64 == 0: a 16-channel segment is all in or all out
             float sn[16];
             int zn[16];
@@ -983,6 +1017,17 @@ void launch_stream(const GemmDev& p, bool fp16, dim3 grid, hipStream_t s)
     else stream_kernel<MF, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
 }
 
+template <bool GROUP, int CF, int WM>
+void launch_mma(const GemmDev& p, bool fp16, hipStream_t s)
+{
+    constexpr int TMt = 128 * WM, TNt = 32 * CF * (4 / WM);
+    const dim3 grid((unsigned)(((p.N + TNt - 1) / TNt) * ((p.M + TMt - 1) / TMt)), (unsigned)p.S);
+    if (fp16) mma_kernel<GROUP, OUT_FP16, CF, WM><<<grid, kMmaThreads, 0, s>>>(p);
+    else mma_kernel<GROUP, OUT_I32, CF, WM><<<grid, kMmaThreads, 0, s>>>(p);
+}
+
+// tile_m selects the kernel and its shape: 16 / 32 / 64 = streaming kernel with that many tokens per tile;
+// 128 = compute-bound kernel, 256 tokens x 256 channels; 129 = 128 tokens x 256 channels; 130 = 256 x 128.
 template <bool GROUP>
 void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
@@ -991,27 +1036,37 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
         if (tile_m == 16) launch_stream<1, GROUP>(p, fp16, grid, s);
         else if (tile_m == 32) launch_stream<2, GROUP>(p, fp16, grid, s);
         else launch_stream<4, GROUP>(p, fp16, grid, s);
+    } else if (tile_m == 129) {
+        launch_mma<GROUP, 2, 1>(p, fp16, s);
+    } else if (tile_m == 130) {
+        launch_mma<GROUP, 2, 2>(p, fp16, s);
     } else {
-        const dim3 grid((unsigned)(((p.N + 255) / 256) * ((p.M + 255) / 256)), (unsigned)p.S);
-        if (fp16) mma_kernel<GROUP, OUT_FP16><<<grid, kMmaThreads, 0, s>>>(p);
-        else mma_kernel<GROUP, OUT_I32><<<grid, kMmaThreads, 0, s>>>(p);
+        launch_mma<GROUP, 4, 2>(p, fp16, s);
     }
-}
-
-int64_t tiles_of(int64_t M, int64_t N, int tile_m)
-{
-    return tile_m <= 64 ? (N / 64) * ((M + tile_m - 1) / tile_m) : ((N + 255) / 256) * ((M + 255) / 256);
 }
 
 }  // namespace
 
-// split_k: tiled kernel = number of k-slices per tile; stream kernel = number of workgroups the
-// unit stream is dealt to (per m-tile).
-// k-slices of the compute-bound kernel: only when its 256 x 256 tiles leave most CUs idle and every slice
-// still has a long run of groups (a partial tile costs 256 KiB of traffic each way).
-static int mma_split(int64_t M, int64_t N, int64_t G, int forced_split)
+// ---- launch configuration --------------------------------------------------------------------------
+// tile_m: 16 / 32 / 64 = streaming kernel with that many tokens per tile; 128 / 129 / 130 = compute-bound kernel
+// with 256 x 256, 128 x 256, 256 x 128 (tokens x channels) tiles.  split_k: streaming kernel = number of
+// workgroups the unit stream is dealt to (per token tile); compute-bound kernel = k-slices per tile.
+static void mma_tile_shape(int tile_m, int64_t& tm, int64_t& tn)
 {
-    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    tm = tile_m == 129 ? 128 : 256;
+    tn = tile_m == 130 ? 128 : 256;
+}
+static int64_t mma_tiles(int64_t M, int64_t N, int tile_m)
+{
+    int64_t tm, tn;
+    mma_tile_shape(tile_m, tm, tn);
+    return ((M + tm - 1) / tm) * ((N + tn - 1) / tn);
+}
+// k-slices of the compute-bound kernel: only when its tiles leave most CUs idle and every slice still has a
+// long run of groups (a partial tile costs 128-256 KiB of traffic each way plus a device-wide hand-over).
+static int mma_split(int64_t M, int64_t N, int64_t G, int tile_m, int forced_split)
+{
+    const int64_t tiles = mma_tiles(M, N, tile_m);
     int64_t S = 1;
     if (forced_split > 0) S = forced_split;
     else if (tiles < 160) S = std::min<int64_t>(256 / tiles, G / 24);
@@ -1020,24 +1075,36 @@ static int mma_split(int64_t M, int64_t N, int64_t G, int forced_split)
     const int64_t gps = (G + S - 1) / S;
     return (int)((G + gps - 1) / gps);
 }
+// Cost model fitted to measurements on MI355X, in microseconds: a workgroup needs about 8 us of prologue and
+// epilogue plus 1.15 us per group with 256 x 256 tiles (0.72 us with the half-size tiles); workgroups run in
+// rounds of one per CU; a split adds about 20 us (14 us) for the hand-over.
+static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
+{
+    S = mma_split(M, N, G, tile_m, 0);
+    const int64_t wgs = mma_tiles(M, N, tile_m) * S;
+    const double per_group = tile_m == 128 ? 1.15 : 0.72;
+    return (double)((wgs + 255) / 256) * (8.0 + per_group * (double)((G + S - 1) / S)) +
+           (S > 1 ? (tile_m == 128 ? 20.0 : 14.0) : 0.0);
+}
 
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
     tile_m = forced.tile_m ? forced.tile_m : (M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128);
     if (!forced.tile_m && M > 64) {
-        // Between the two regimes (a few hundred tokens) the 256 x 256 tiles of the compute-bound kernel are
-        // too few to fill 256 CUs and each walks all of K serially, while the streaming kernel, run once per
-        // 64-token tile, re-reads the weights but spreads K over the whole chip.  Pick by a cost model fitted
-        // to measurements on MI355X (microseconds): streaming ~ 6 + m_tiles * max(7, weight MB / 2.3),
-        // compute-bound ~ rounds * (8 + 1.15 * groups).
+        // Cheapest of the three tile shapes of the compute-bound kernel and, for a few hundred tokens, the
+        // streaming kernel run once per 64-token tile (it re-reads the weights but spreads K over the whole
+        // chip): streaming ~ 6 + m_tiles * max(7, weight MB / 2.3) microseconds.
+        int S;
+        double best = mma_cost(M, N, G, 128, S);
+        for (int cand = 129; cand <= 130; ++cand) {
+            const double c = mma_cost(M, N, G, cand, S);
+            if (c < 0.95 * best) { best = c; tile_m = cand; }
+        }
         const double m_tiles = (double)((M + 63) / 64);
         const double w_mb = (double)K * (double)N / 2.0e6;
         const double est_stream = 6.0 + m_tiles * (w_mb / 2.3 > 7.0 ? w_mb / 2.3 : 7.0);
-        const int S = mma_split(M, N, G, 0);
-        const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256) * S;
-        const double est_mma = (double)((tiles + 255) / 256) * (8.0 + 1.15 * (double)((G + S - 1) / S)) + (S > 1 ? 20.0 : 0.0);
-        if (est_stream < 0.9 * est_mma) tile_m = 64;
+        if (est_stream < 0.9 * best) tile_m = 64;
     }
     if (tile_m <= 64) {
         const int64_t units = (N / 64) * G;
@@ -1052,7 +1119,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
         split_k = (int)((units + upw - 1) / upw);
         return;
     }
-    split_k = mma_split(M, N, G, forced.split_k);
+    split_k = mma_split(M, N, G, tile_m, forced.split_k);
 }
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
@@ -1066,8 +1133,10 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int spl
         return counters + (size_t)m_tiles * (size_t)split_k * 2 * (size_t)(tile_m * 64) * sizeof(int32_t);
     }
     if (split_k <= 1) return 0;
-    const size_t tiles = (size_t)(((M + 255) / 256) * ((N + 255) / 256));
-    return align256(tiles * sizeof(int)) + tiles * (size_t)split_k * 256 * 256 * sizeof(int32_t);
+    int64_t tm, tn;
+    mma_tile_shape(tile_m, tm, tn);
+    const size_t tiles = (size_t)mma_tiles(M, N, tile_m);
+    return align256(tiles * sizeof(int)) + tiles * (size_t)split_k * (size_t)(tm * tn) * sizeof(int32_t);
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
@@ -1098,7 +1167,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         p.upw = 0;
         p.S = a.split_k;
         p.gps = (int)((L.G + a.split_k - 1) / a.split_k);
-        counters = align256((size_t)(((a.M + 255) / 256) * ((a.N + 255) / 256)) * sizeof(int));
+        counters = align256((size_t)mma_tiles(a.M, a.N, a.tile_m) * sizeof(int));
     }
     p.parts = reinterpret_cast<int4*>(reinterpret_cast<uint8_t*>(a.workspace) + counters);
     if (a.mode == 0) launch_any<true>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);

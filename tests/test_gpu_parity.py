@@ -147,7 +147,7 @@ def test_group_ragged_m(api, M):
 
 
 @pytest.mark.parametrize("tile_m,split_k", [(16, 1), (32, 1), (64, 1), (128, 1), (16, 3), (64, 5), (128, 2), (32, 9),
-                                            (64, 2), (128, 9)])
+                                            (64, 2), (128, 9), (129, 1), (130, 1), (129, 3), (130, 2), (129, 9), (130, 4)])
 def test_group_forced_variants(api, tile_m, split_k):
     run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
 
@@ -161,6 +161,13 @@ def test_group_streaming_kernel_many_token_tiles(api, M, tile_m, split_k):
 
 def test_group_several_tiles_all_axes(api):
     run_group_case(api, 300, 1088, 2048, seed=11)
+
+
+@pytest.mark.parametrize("tile_m,split_k", [(128, 1), (129, 1), (130, 1), (129, 2), (130, 3)])
+def test_group_compute_kernel_shapes_ragged(api, tile_m, split_k):
+    """Every tile shape of the compute-bound kernel on a problem ragged in tokens and channels (M % 128 != 0,
+    N % 128 != 0) with several tiles on both axes and, with a split, odd slice lengths (17 groups)."""
+    run_group_case(api, 389, 1472, 2176, seed=13, tile_m=tile_m, split_k=split_k)
 
 
 def _pack_logical(api, code, s1, z, s0):
@@ -205,7 +212,7 @@ def test_per_channel_gemm(api, M, N, K):
     ref = ogemm.forward_per_channel(_np(w), _np(x))
     blob = api.pack_weights(w, api.QOQ_PER_CHANNEL)
     qx, sx, rowsum, _ = api.quant_act_per_token(x)
-    for tile_m, split_k in [(0, 0), (32, 3), (128, 1)]:
+    for tile_m, split_k in [(0, 0), (32, 3), (128, 1), (129, 1), (130, 1), (129, 2), (128, 3)]:
         api.set_gemm_config(tile_m, split_k)
         try:
             acc = api.w4a8_gemm_i32(qx, blob, N, api.QOQ_PER_CHANNEL, rowsum=rowsum)
