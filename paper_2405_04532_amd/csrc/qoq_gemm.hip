@@ -1,40 +1,37 @@
 // W4A8 GEMM for gfx950 (Section 5.2 of arXiv 2405.04532, re-designed for CDNA4).
 //
-// out^T tile = W_tile (MFMA operand A, rows = output channels) x X_tile^T (operand B, columns
-// = tokens), v_mfma_i32_16x16x64_i8, exact INT32 accumulation.
-//   * weights: each lane streams its pre-ordered 128-bit words straight from global memory
-//     into registers (one word = one lane's codes for a whole quantization group of one
-//     row: two MFMA k-steps), prefetched one group ahead.  No LDS, no address arithmetic
-//     beyond a running pointer (Section 5.2.1).
-//   * UINT4 -> INT8 in registers (Sections 5.2.2-5.2.3): 3 logic ops unpack 8 codes into two
-//     operand registers; per group one packed 16-bit multiply-add per register computes
-//     code*s1 + (128 - z*s1) in all four bytes at once (no carries because the protective
-//     range keeps every byte in [1, 255]), and one XOR turns the +128 bias into two's
-//     complement.  The per-channel variant feeds the codes unchanged and folds the zero
-//     point into the epilogue through the token's row sum (Eq. 6).
-//   * two kernels.  "stream" (M <= 64, memory bound): a multi-stage pipeline of direct
-//     global->LDS copies (the asynchronous-copy, multi-stage software pipeline of Section 5.2.4 in
-//     its gfx950 form) over a balanced, stream-k style partition of the work.
-//       - Work unit = one quantization group of one 64-channel block (4 KiB of packed weights).
-//         The N/64 * K/128 units are dealt out in equal contiguous runs to about one workgroup
-//         per CU, whatever the layer shape; a run may start and end in the middle of a block.
-//       - HBM latency under load is about 1.5 us here, so some 50 KiB per CU must be in
-//         flight.  Each of eight consumer waves (fragment f, group parity e) copies the units
-//         it will itself consume into a private 8-deep LDS ring: no barrier guards the weights.
-//         Activations come from L2 and need far less lead, but a wave's outstanding loads retire
-//         in order, so a wave issuing both would stall its deep weight prefetch on every
-//         activation wait.  A ninth wave therefore copies the activation slabs, level-2 metadata
-//         and channel scales three iterations ahead; one barrier per iteration (two groups)
-//         publishes them.  Copies are issued from inline assembly and waited for with explicit
-//         s_waitcnt vmcnt(n): the compiler's own bookkeeping would wait for ALL outstanding
-//         copies before every LDS read.
-//       - A block finished inside one run is scaled and stored at once.  Blocks shared by
-//         several runs meet in the workspace: partial INT32 tiles are written through to
-//         memory, a per-block counter elects the last workgroup to arrive, which adds all
-//         partials (integer sums are exact and order independent) and runs the epilogue.
-//     "tiled" (larger M): 128 x 256 tile, activations staged through LDS in operand-fragment
-//     order, double buffered, one barrier per group; plain split-k with the same counter scheme.
-//   * epilogue (Section 5.2.2): FP32 acc * (sx[m] * s[n]), one rounding to FP16.
+// out^T tile = W_tile (MFMA operand A, rows = output channels) x X_tile^T (operand B, columns = tokens),
+// INT8 x INT8 -> INT32 on the matrix cores, exact accumulation.
+//   * Weights stay packed (two codes per byte) in HBM and in LDS, in the order the MFMA lanes consume them
+//     (Section 5.2.1): one 128-bit word per lane and quantization group, no address arithmetic per fragment.
+//   * UINT4 -> INT8 in registers (Sections 5.2.2-5.2.3): 3 logic ops unpack 8 codes into two operand
+//     registers; per group one packed 16-bit multiply-add per register computes code*s1 + (128 - z*s1) in
+//     all four bytes at once (no carries because the protective range keeps every byte in [1, 255]), and
+//     one XOR turns the +128 bias into two's complement.  The per-channel variant feeds the codes unchanged
+//     and folds the zero point into the epilogue through the token's row sum (Eq. 6).
+//   * Two kernels.
+//     "stream" (M <= 64 per tile, memory bound, v_mfma_i32_16x16x64_i8): a multi-stage pipeline of direct
+//     global->LDS copies (the asynchronous-copy software pipeline of Section 5.2.4 in its gfx950 form) over
+//     a balanced, stream-k style partition of the work.
+//       - Work unit = one quantization group of one 64-channel block (4 KiB of packed weights).  The
+//         N/64 * K/128 units are dealt out in equal contiguous runs to about one workgroup per CU, whatever
+//         the layer shape; a run may start and end in the middle of a block.
+//       - HBM latency under load is about 1.5-2.5 us here, so some 50-100 KiB per CU must be in flight.
+//         Each of eight consumer waves (fragment f, group parity e) copies the units it will itself consume
+//         into a private 10-12 deep LDS ring: no barrier guards the weights.  Activations come from L2 and
+//         need far less lead, but a wave's outstanding copies retire in order, so a wave issuing both would
+//         stall its deep weight prefetch on every activation wait: two producer waves copy the activation
+//         slabs, level-2 metadata and channel scales a couple of iterations ahead; one barrier per iteration
+//         (two groups) publishes them.  Copies are issued from inline assembly and waited for with explicit
+//         s_waitcnt vmcnt(n): the compiler's own bookkeeping would wait for ALL outstanding copies before
+//         every LDS read.
+//       - A block finished inside one run is scaled and stored at once.  Blocks shared by several runs meet
+//         in the workspace: partial INT32 tiles are written through to memory, a per-block counter elects
+//         the last workgroup to arrive, which adds all partials (integer sums are exact and order
+//         independent) and runs the epilogue.
+//     "mma" (larger M, compute bound, v_mfma_i32_32x32x32_i8): large output tiles, one wave per SIMD, a
+//     hand software-pipelined main loop; see the comment in front of it.
+//   * Epilogue (Section 5.2.2): FP32 acc * (sx[m] * s[n]), one rounding to FP16.
 #include <hip/hip_fp16.h>
 #include <algorithm>
 #include <hip/hip_runtime.h>
@@ -48,15 +45,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Streaming (non-temporal) 128-bit load: weights are read exactly once per GEMM.
-__device__ inline uint4 load_stream(const uint4* ptr)
-{
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ptr));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 constexpr int kThreads = 256;
-constexpr int kWaves = 4;
 constexpr int kNFrag = 4;  // 16-row fragments per wave = 64 output channels
 
 struct GemmDev {
@@ -103,112 +92,12 @@ __device__ inline v4i dequant(uint32_t x0, uint32_t x1, uint32_t S, uint32_t B)
 
 __device__ inline v4i as_v4i(uint4 t) { return (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w}; }
 
-// Split-k across workgroups.  Every workgroup of a tile stores its CNT int4 values per thread;
-// the last one to arrive (per-tile counter) adds the others' and returns true.
-//
-// Visibility between workgroups (which may sit on different XCDs, each with its own L2) is
-// obtained without device-wide fences: a release/acquire fence pair writes back and
-// invalidates a whole L2 and was measured to cost tens of microseconds per GEMM here.  The
-// partial tiles are instead written and read with relaxed device-scope atomic accesses, which
-// go through to memory past the non-coherent caches; a workgroup waits for its own stores to
-// complete (s_waitcnt) before it bumps the tile's counter with a device-scope atomic, and the
-// last arriver reads the partials only after that atomic has returned.
-__device__ inline void store_coherent(int4* dst, int4 v)
-{
-    int* d = reinterpret_cast<int*>(dst);
-    __hip_atomic_store(d + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(d + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(d + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(d + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline int4 load_coherent(const int4* src)
-{
-    int* s = const_cast<int*>(reinterpret_cast<const int*>(src));
-    int4 v;
-    v.x = __hip_atomic_load(s + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.y = __hip_atomic_load(s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.z = __hip_atomic_load(s + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.w = __hip_atomic_load(s + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return v;
-}
-
-// `tid` in [0, 256) indexes the 256 value-holding threads of the tile; threads with
-// active == false only take part in the barriers.
-template <int CNT>
-__device__ inline bool splitk_combine(int4 (&v)[CNT], const GemmDev& p, int tile, int split, int tid, bool active)
-{
-    __shared__ int s_last;
-    if (active) {
-        int4* mine = p.parts + ((size_t)tile * p.S + split) * CNT * kThreads + tid;
-#pragma unroll
-        for (int i = 0; i < CNT; ++i) store_coherent(mine + (size_t)i * kThreads, v[i]);
-    }
-    __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    __builtin_amdgcn_s_waitcnt(0);  // every store of this thread has completed at memory
-    __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    __syncthreads();                // ... and of every thread of the workgroup
-    if (active && tid == 0)
-        s_last = __hip_atomic_fetch_add(p.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.S - 1;
-    __syncthreads();
-    if (!s_last) return false;
-    if (active) {
-        for (int s = 0; s < p.S; ++s) {
-            if (s == split) continue;
-            const int4* other = p.parts + ((size_t)tile * p.S + s) * CNT * kThreads + tid;
-#pragma unroll
-            for (int i = 0; i < CNT; ++i) {
-                const int4 o = load_coherent(other + (size_t)i * kThreads);
-                v[i].x += o.x; v[i].y += o.y; v[i].z += o.z; v[i].w += o.w;
-            }
-        }
-        if (tid == 0) __hip_atomic_store(p.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    return true;
-}
-
-// Epilogue for ROWS consecutive output channels n0.. of token m held in v[0..ROWS).
-template <bool GROUP, int OUT, int ROWS>
-__device__ inline void store_row(const GemmDev& p, int m, int n0, int (&v)[ROWS])
-{
-    static_assert(ROWS == 4 || ROWS == 16, "row segment");
-    if constexpr (!GROUP) {
-        const int rs = p.rowsum[m];
-        uint32_t zw[ROWS / 4];
-        if constexpr (ROWS == 4) {
-            zw[0] = *reinterpret_cast<const uint32_t*>(p.zeros + n0);
-        } else {
-            const uint4 zz = *reinterpret_cast<const uint4*>(p.zeros + n0);
-            zw[0] = zz.x; zw[1] = zz.y; zw[2] = zz.z; zw[3] = zz.w;
-        }
-#pragma unroll
-        for (int j = 0; j < ROWS; ++j) v[j] -= (int)((zw[j >> 2] >> (8 * (j & 3))) & 0xFFu) * rs;
-    }
-    if constexpr (OUT == OUT_I32) {
-        int4* dst = reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n0);
-#pragma unroll
-        for (int j = 0; j < ROWS / 4; ++j) dst[j] = make_int4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
-    } else {
-        const float sxm = __half2float(p.sx[m]);
-        const uint32_t* sp = reinterpret_cast<const uint32_t*>(p.scales + n0);
-        uint32_t h[ROWS / 2];
-#pragma unroll
-        for (int j = 0; j < ROWS / 2; ++j) {
-            const uint32_t sw = sp[j];
-            const float s_a = __half2float(__ushort_as_half((unsigned short)(sw & 0xFFFFu)));
-            const float s_b = __half2float(__ushort_as_half((unsigned short)(sw >> 16)));
-            const __half a = __float2half_rn((float)v[2 * j] * (sxm * s_a));
-            const __half b = __float2half_rn((float)v[2 * j + 1] * (sxm * s_b));
-            h[j] = (uint32_t)__half_as_ushort(a) | ((uint32_t)__half_as_ushort(b) << 16);
-        }
-        if constexpr (ROWS == 4) {
-            *reinterpret_cast<uint2*>(p.out16 + (size_t)m * p.N + n0) = make_uint2(h[0], h[1]);
-        } else {
-            uint4* dst = reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n0);
-            dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
-            dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
-        }
-    }
-}
+// Hand-over of partial tiles between workgroups (which may sit on different XCDs, each with its own L2)
+// without device-wide fences: a release/acquire fence pair writes back and invalidates a whole L2 and was
+// measured to cost tens of microseconds per GEMM here.  Partial tiles are instead written with sc1
+// (write-through) stores and read with sc1 loads, which go to memory past the non-coherent caches; a
+// workgroup waits for its own stores to complete (s_waitcnt) before it bumps the tile's counter with a
+// relaxed device-scope atomic, and the last arriver reads the partials only after that atomic has returned.
 
 // ------------------------------------------------------------------------------------------
 // "stream" kernel: 16*MF <= 64 tokens; nine waves; grid = (workgroups, m-tiles).
@@ -1077,14 +966,14 @@ static int mma_split(int64_t M, int64_t N, int64_t G, int tile_m, int forced_spl
 }
 // Cost model fitted to measurements on MI355X, in microseconds: a workgroup needs about 8 us of prologue and
 // epilogue plus 1.15 us per group with 256 x 256 tiles (0.72 us with the half-size tiles); workgroups run in
-// rounds of one per CU; a split adds about 20 us (14 us) for the hand-over.
+// rounds of one per CU; a split adds about 30 us (14 us) for the hand-over.
 static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 {
     S = mma_split(M, N, G, tile_m, 0);
     const int64_t wgs = mma_tiles(M, N, tile_m) * S;
     const double per_group = tile_m == 128 ? 1.15 : 0.72;
     return (double)((wgs + 255) / 256) * (8.0 + per_group * (double)((G + S - 1) / S)) +
-           (S > 1 ? (tile_m == 128 ? 20.0 : 14.0) : 0.0);
+           (S > 1 ? (tile_m == 128 ? 30.0 : 14.0) : 0.0);
 }
 
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
