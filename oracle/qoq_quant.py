@@ -171,3 +171,21 @@ def output_fp64(acc, sx, sw):
 def output_fp16(acc, sx, sw):
     """FP16 GEMM output (Section 5.1: every GEMM produces FP16): one RNE rounding."""
     return output_fp64(acc, sx, sw).astype(np.float16)
+
+
+def output_fp64_token_sum(raw, sx, sw, z, tx):
+    """Per-channel epilogue in the subtraction-after-multiplication form the paper fuses into the
+    GEMM (Section 5.2.2, Eq. 6 with the quantized activations of its second term replaced by the
+    unquantized ones, Eq. 7):
+
+        out[m, n] = raw[m, n] * sx[m] * sw[n]  -  tx[m] * (z[n] * sw[n]),
+
+    raw = sum_k qx * Q (unsigned codes, no zero point), tx[m] = sum_k X[m, k] over the UNQUANTIZED
+    activations.  It differs from the exact fold (per_channel_acc + output_fp64) by
+    z[n] * sw[n] * sum_k (X - qx * sx)[m, k], the quantization error of the token summed over k.
+    """
+    s = np.asarray(sw, dtype=np.float16).astype(np.float64)
+    first = (np.asarray(raw, dtype=np.float64)
+             * np.asarray(sx, dtype=np.float16).astype(np.float64)[:, None] * s[None, :])
+    second = np.asarray(tx, dtype=np.float64)[:, None] * (np.asarray(z, dtype=np.float64) * s)[None, :]
+    return first - second

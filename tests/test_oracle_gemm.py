@@ -131,3 +131,70 @@ def test_gemm_pins_catch_planted_mistakes(bad, monkeypatch):
         monkeypatch.setattr(qq, "output_fp64", lambda acc, sx, sw: orig(acc, sx, np.roll(np.asarray(sw), 1)))
         with pytest.raises(AssertionError):
             test_group_forward_vs_dequantized_fp64_matmul()
+
+
+# ------------------------------------------------------------------ token-sum form of the per-channel epilogue
+def _per_channel_case(seed, M=6, N=5, K=64):
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    code, z, sw = qq.per_channel_quant(w)
+    qx, sx, rowsum, tx = qq.act_quant(x)
+    raw = qq.gemm_i64_numpy(qx, code)
+    return w, x, code, z, sw, qx, sx, rowsum, tx, raw
+
+
+def test_token_sum_form_matches_matrix_form():
+    """Eq. 7 written out with matrices: X_hat (W_hat + ZS) - X ZS, all operands dequantized to FP64."""
+    w, x, code, z, sw, qx, sx, rowsum, tx, raw = _per_channel_case(3)
+    s = sw.astype(np.float64)
+    x_hat = qx.astype(np.float64) * sx.astype(np.float64)[:, None]
+    qs = code.astype(np.float64) * s[:, None]                   # Q_W (.) S_W, [N, K]
+    zs = np.repeat((z.astype(np.float64) * s)[:, None], x.shape[1], axis=1)   # ZS_W, [N, K]
+    expect = x_hat @ qs.T - x.astype(np.float64) @ zs.T
+    got = qq.output_fp64_token_sum(raw, sx, sw, z, tx)
+    assert np.allclose(got, expect, rtol=1e-12, atol=1e-12)
+
+
+def test_token_sum_form_equals_exact_fold_when_activations_are_on_the_grid():
+    """If every activation is an exact multiple of its token scale, X_hat == X and both forms coincide."""
+    rng = np.random.default_rng(5)
+    qx0 = rng.integers(-127, 128, size=(4, 64))
+    qx0[:, 0] = 127                                              # pins absmax so that sx is the chosen scale
+    sx0 = np.array([0.5, 0.25, 1.0, 0.125])
+    x = (qx0 * sx0[:, None]).astype(np.float16)
+    assert np.array_equal(x.astype(np.float64), qx0 * sx0[:, None])
+    w = (rng.standard_normal((7, 64)) * 0.05).astype(np.float16)
+    code, z, sw = qq.per_channel_quant(w)
+    qx, sx, rowsum, tx = qq.act_quant(x)
+    assert np.array_equal(qx, qx0)
+    raw = qq.gemm_i64_numpy(qx, code)
+    exact = qq.output_fp64(qq.per_channel_acc(raw, z, rowsum), sx, sw)
+    assert np.allclose(qq.output_fp64_token_sum(raw, sx, sw, z, tx), exact, rtol=1e-13, atol=1e-13)
+
+
+def test_token_sum_form_differs_by_the_summed_quantization_error():
+    w, x, code, z, sw, qx, sx, rowsum, tx, raw = _per_channel_case(9, M=8, N=6, K=128)
+    exact = qq.output_fp64(qq.per_channel_acc(raw, z, rowsum), sx, sw)
+    approx = qq.output_fp64_token_sum(raw, sx, sw, z, tx)
+    err_sum = (x.astype(np.float64) - qx * sx.astype(np.float64)[:, None]).sum(axis=1)       # [M]
+    zs = z.astype(np.float64) * sw.astype(np.float64)
+    assert np.allclose(exact - approx, err_sum[:, None] * zs[None, :], rtol=1e-10, atol=1e-12)
+    # and the bound that follows from |X - qx*sx| <= sx/2 per element
+    bound = (x.shape[1] * sx.astype(np.float64) / 2)[:, None] * zs[None, :]
+    assert np.all(np.abs(exact - approx) <= bound + 1e-12)
+
+
+@pytest.mark.parametrize("bad", ["plus", "rowsum", "no_scale"])
+def test_token_sum_pins_catch_planted_mistakes(bad, monkeypatch):
+    def wrong(raw, sx, sw, z, tx):
+        s = np.asarray(sw, dtype=np.float16).astype(np.float64)
+        first = np.asarray(raw, dtype=np.float64) * np.asarray(sx, dtype=np.float16).astype(np.float64)[:, None] * s[None, :]
+        if bad == "plus":
+            return first + np.asarray(tx)[:, None] * (np.asarray(z, dtype=np.float64) * s)[None, :]
+        if bad == "no_scale":
+            return first - np.asarray(tx)[:, None] * np.asarray(z, dtype=np.float64)[None, :]
+        return first - np.asarray(tx)[:, None] * (np.asarray(z, dtype=np.float64) * s)[None, :] * 1.01
+    monkeypatch.setattr(qq, "output_fp64_token_sum", wrong)
+    with pytest.raises(AssertionError):
+        test_token_sum_form_matches_matrix_form()
