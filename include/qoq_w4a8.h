@@ -114,6 +114,19 @@ int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packe
                       int64_t M, int64_t N, int64_t K, int mode,
                       int32_t* acc, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Per-channel W4A8 GEMM with the zero point subtracted after the multiplication exactly as Section 5.2.2
+ * fuses it into the epilogue (its Eq. 6 with the quantized activations of the second term replaced by the
+ * unquantized ones, Eq. 7):
+ *     out[m, n] = fp16( acc[m, n] * sx[m] * sw[n]  -  tx[m] * (z[n] * sw[n]) ),   acc = sum_k qx * Q  (raw codes),
+ * evaluated in FP32.  tx [M] FP32 = sum_k X[m, k] over the UNQUANTIZED activations, as produced by
+ * qoq_quant_act_per_token.  It approximates qoq_w4a8_gemm in per-channel mode (which folds the zero point in
+ * exact integers through the row sums of qx); the two differ by z*sw times the token's summed quantization error.
+ *   packed     a blob packed with mode QOQ_PER_CHANNEL
+ * Other arguments, workspace and error rules as for qoq_w4a8_gemm. */
+int qoq_w4a8_gemm_token_sum(const int8_t* qx, const void* sx_fp16, const float* tx, const void* packed,
+                            int64_t M, int64_t N, int64_t K, void* out_fp16,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Activation quantization and GEMM in one call: exactly
  *   qoq_quant_act_per_token(x -> qx, sx, rowsum);  qoq_w4a8_gemm(qx, sx, rowsum, packed -> out)
  * enqueued back to back on `stream` (Section 5.1 places the activation quantization directly in front of

@@ -39,6 +39,9 @@ _SIGNATURES = {
     "qoq_w4a8_gemm_i32": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "qoq_w4a8_gemm_token_sum": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_w4a8_linear": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                        ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
@@ -211,3 +214,16 @@ def w4a8_linear(x, packed, N, mode=QOQ_GROUP128, out=None, qx=None, sx=None, row
     _check(lib().qoq_w4a8_linear(_ptr(x), _ptr(packed), M, N, K, mode, _ptr(out), _ptr(qx), _ptr(sx), _ptr(rowsum),
                                  _ptr(workspace), ws_bytes, _stream(dev)))
     return out, qx, sx, rowsum
+
+
+def w4a8_gemm_token_sum(qx, sx, tx, packed, N, out=None, workspace=None):
+    """Per-channel GEMM with the token-sum (subtraction after multiplication) epilogue; tx = FP32 [M]."""
+    _dev(qx, torch.int8, "qx")
+    _dev(tx, torch.float32, "tx")
+    M, K = qx.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=qx.device)
+    workspace, ws_bytes = _workspace(M, N, K, QOQ_PER_CHANNEL, qx.device, workspace)
+    _check(lib().qoq_w4a8_gemm_token_sum(_ptr(qx), _ptr(sx), _ptr(tx), _ptr(packed), M, N, K, _ptr(out),
+                                         _ptr(workspace), ws_bytes, _stream(qx.device)))
+    return out

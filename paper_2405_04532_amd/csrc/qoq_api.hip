@@ -37,13 +37,14 @@ int check_shape(int64_t N, int64_t K, int mode) { return qoq::shape_ok(N, K, mod
 // x_fp16 != NULL: quantize the activations first (into qx, sx, rowsum) by a launch of the activation kernel.
 int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const void* packed, int64_t M, int64_t N,
                 int64_t K, int mode, void* out16, int32_t* out32, void* ws, size_t ws_bytes, void* stream,
-                const void* x_fp16 = nullptr)
+                const void* x_fp16 = nullptr, const float* tx = nullptr)
 {
     if (check_shape(N, K, mode) != QOQ_OK || M < 0 || M > (1 << 24)) return QOQ_ERR_SHAPE;
     if (M * N >= ((int64_t)1 << 40)) return QOQ_ERR_SHAPE;
     if (M == 0) return QOQ_OK;  // empty batch: nothing to do
     if (!qx || !packed || (!out16 && !out32) || (out16 && !sx)) return QOQ_ERR_NULL;
-    if (mode == QOQ_PER_CHANNEL && !rowsum) return QOQ_ERR_NULL;
+    if (mode == QOQ_PER_CHANNEL && !rowsum && !tx) return QOQ_ERR_NULL;
+    if (tx && (reinterpret_cast<uintptr_t>(tx) & 3u)) return QOQ_ERR_ALIGN;
     if (!aligned16(qx) || !aligned16(packed) || !aligned16(out16) || !aligned16(out32) || !aligned16(ws))
         return QOQ_ERR_ALIGN;
     int tile_m, split_k;
@@ -58,7 +59,7 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
                               nullptr, static_cast<hipStream_t>(stream)) != hipSuccess)
         return QOQ_ERR_HIP;
     qoq::GemmArgs a;
-    a.qx = qx; a.sx = sx; a.rowsum = rowsum; a.blob = static_cast<const uint8_t*>(packed);
+    a.qx = qx; a.sx = sx; a.rowsum = rowsum; a.tx = tx; a.blob = static_cast<const uint8_t*>(packed);
     a.M = M; a.N = N; a.K = K; a.mode = mode;
     a.out_fp16 = out16; a.out_i32 = out32; a.workspace = ws;
     a.tile_m = tile_m; a.split_k = split_k;
@@ -104,6 +105,14 @@ int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N
     if (M > 0 && !out_fp16) return QOQ_ERR_NULL;
     return gemm_common(qx, sx_fp16, rowsum, packed, M, N, K, mode, out_fp16, nullptr, workspace, workspace_bytes, stream,
                        x_fp16);
+}
+
+int qoq_w4a8_gemm_token_sum(const int8_t* qx, const void* sx_fp16, const float* tx, const void* packed, int64_t M,
+                            int64_t N, int64_t K, void* out_fp16, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (M > 0 && (!tx || !out_fp16)) return QOQ_ERR_NULL;
+    return gemm_common(qx, sx_fp16, nullptr, packed, M, N, K, QOQ_PER_CHANNEL, out_fp16, nullptr, workspace,
+                       workspace_bytes, stream, nullptr, tx);
 }
 
 int qoq_gemm_workspace_prepare(void* workspace, size_t workspace_bytes, void* stream)

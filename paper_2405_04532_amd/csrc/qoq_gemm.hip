@@ -62,6 +62,7 @@ struct GemmDev {
     int4* parts;    // split-k: [tile][split][value][thread]
     int M, N, K, G, gps, S;  // gps = groups per k-split, S = number of k-splits (tiled kernel)
     int upw;                 // stream kernel: work units per workgroup
+    int token_sum;           // per-channel FP16 epilogue in the token-sum form: `rowsum` then holds the FP32 sums t_X
 };
 
 enum { OUT_FP16 = 0, OUT_I32 = 1 };
@@ -183,18 +184,29 @@ __device__ __forceinline__ void finish4(const GemmDev& p, int m, int n0, v4i v, 
                                         const int (&zn)[4], float sxm, int rs)
 {
     int t[4] = {v.x, v.y, v.z, v.w};
+    // Per-channel zero point: exact integer fold acc - z * rowsum (Eq. 6), or, in the token-sum form (Eq. 7),
+    // acc * sx * s - t_X * (z * s) in FP32 with `rs` carrying the bits of t_X.
+    const bool token_sum = !GROUP && OUT == OUT_FP16 && p.token_sum;
     if constexpr (!GROUP) {
+        if (!token_sum) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) t[j] -= zn[j] * rs;
+            for (int j = 0; j < 4; ++j) t[j] -= zn[j] * rs;
+        }
     }
     if constexpr (OUT == OUT_I32) {
         *reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n0) = make_int4(t[0], t[1], t[2], t[3]);
     } else {
+        const float txm = __int_as_float(rs);
         uint32_t h[2];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const __half a = __float2half_rn((float)t[2 * j] * (sxm * sn[2 * j]));
-            const __half b = __float2half_rn((float)t[2 * j + 1] * (sxm * sn[2 * j + 1]));
+            float ra = (float)t[2 * j] * (sxm * sn[2 * j]), rb = (float)t[2 * j + 1] * (sxm * sn[2 * j + 1]);
+            if (token_sum) {
+                ra -= txm * ((float)zn[2 * j] * sn[2 * j]);
+                rb -= txm * ((float)zn[2 * j + 1] * sn[2 * j + 1]);
+            }
+            const __half a = __float2half_rn(ra);
+            const __half b = __float2half_rn(rb);
             h[j] = (uint32_t)__half_as_ushort(a) | ((uint32_t)__half_as_ushort(b) << 16);
         }
         *reinterpret_cast<uint2*>(p.out16 + (size_t)m * p.N + n0) = make_uint2(h[0], h[1]);
@@ -868,6 +880,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                 if (m >= p.M) continue;
                 const float sxm = OUT == OUT_FP16 ? __half2float(e_sx[ml]) : 0.f;
                 const int rs = GROUP ? 0 : e_rs[ml];
+                const bool token_sum = !GROUP && OUT == OUT_FP16 && p.token_sum;   // Eq. 7 form, rs = bits of t_X
+                const float txm = __int_as_float(rs);
                 int t[16];
 #pragma unroll
                 for (int piece = 0; piece < 4; ++piece) {
@@ -875,7 +889,7 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
                         t[4 * piece + x] = acc[cf][tf][4 * v4 + x];
-                        if (!GROUP) t[4 * piece + x] -= zn[4 * piece + x] * rs;
+                        if (!GROUP && !token_sum) t[4 * piece + x] -= zn[4 * piece + x] * rs;
                     }
                 }
                 if constexpr (OUT == OUT_I32) {
@@ -886,8 +900,13 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                     uint32_t h[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const __half lo = __float2half_rn((float)t[2 * j] * (sxm * sn[2 * j]));
-                        const __half hi = __float2half_rn((float)t[2 * j + 1] * (sxm * sn[2 * j + 1]));
+                        float ra = (float)t[2 * j] * (sxm * sn[2 * j]), rb = (float)t[2 * j + 1] * (sxm * sn[2 * j + 1]);
+                        if (token_sum) {
+                            ra -= txm * ((float)zn[2 * j] * sn[2 * j]);
+                            rb -= txm * ((float)zn[2 * j + 1] * sn[2 * j + 1]);
+                        }
+                        const __half lo = __float2half_rn(ra);
+                        const __half hi = __float2half_rn(rb);
                         h[j] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
                     }
                     uint4* dst = reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n16);
@@ -1039,7 +1058,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     p.scales = reinterpret_cast<const __half*>(a.blob + L.scale_off);
     p.zeros = a.blob + L.zero_off;
     p.sx = static_cast<const __half*>(a.sx);
-    p.rowsum = a.rowsum;
+    p.rowsum = a.tx ? reinterpret_cast<const int32_t*>(a.tx) : a.rowsum;
+    p.token_sum = a.tx ? 1 : 0;
     p.out16 = static_cast<__half*>(a.out_fp16);
     p.out32 = a.out_i32;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K; p.G = (int)L.G;

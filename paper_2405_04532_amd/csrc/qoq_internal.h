@@ -23,6 +23,7 @@ struct GemmArgs {
     const int8_t* qx;
     const void* sx;          // FP16 [M] (null for the INT32 entry)
     const int32_t* rowsum;   // INT32 [M], per-channel mode
+    const float* tx;         // FP32 [M] sums of the unquantized tokens: per-channel FP16 epilogue in the token-sum form
     const uint8_t* blob;
     int64_t M, N, K;
     int mode;

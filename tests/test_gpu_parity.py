@@ -285,3 +285,38 @@ def test_linear_equals_quant_then_gemm(api, M, N, K, mode):
         ref = (ogemm.forward_per_channel if mode else ogemm.forward_group)(_np(w), _np(x))
         check_fp16(out, ref["out64"])
         assert (_np(qx).astype(np.int64) == ref["qx"]).all()
+
+
+# ---------------------------------------------------------------------------- token-sum form of the per-channel epilogue
+@pytest.mark.parametrize("M,N,K,cfg", [(16, 256, 256, (0, 0)), (64, 512, 4096, (0, 0)), (70, 192, 640, (32, 3)),
+                                       (200, 448, 1152, (128, 1)), (200, 448, 1152, (129, 2)), (300, 320, 2048, (130, 1))])
+def test_per_channel_token_sum_epilogue(api, M, N, K, cfg):
+    """out = acc * sx * sw - t_X * (z * sw) with t_X summed over the unquantized activations (Section 5.2.2),
+    against the oracle's FP64 form.  Tolerance: the stated 1e-3 relative on the result plus the FP32 rounding
+    of the two products, which nearly cancel (2^-21 of their magnitudes)."""
+    w, x = rand_inputs(M, N, K, seed=3 * M + N)
+    blob = api.pack_weights(w, api.QOQ_PER_CHANNEL)
+    qx, sx, rowsum, tx = api.quant_act_per_token(x, want_rowsum=True, want_tx=True)
+    api.set_gemm_config(*cfg)
+    try:
+        out = api.w4a8_gemm_token_sum(qx, sx, tx, blob, N)
+        exact = api.w4a8_gemm(qx, sx, blob, N, api.QOQ_PER_CHANNEL, rowsum=rowsum)
+        torch.cuda.synchronize()
+    finally:
+        api.set_gemm_config(0, 0)
+    code, z, sw = qq.per_channel_quant(_np(w))
+    oqx, osx, orow, otx = qq.act_quant(_np(x))
+    raw = ogemm.gemm_i64(oqx, code)
+    s = sw.astype(np.float64)
+    first = raw.astype(np.float64) * osx.astype(np.float64)[:, None] * s[None, :]
+    second = otx[:, None] * (z.astype(np.float64) * s)[None, :]
+    ref = qq.output_fp64_token_sum(raw, osx, sw, z, otx)
+    # the kernel takes t_X from the activation kernel, which sums the row in FP32: 2^-18 of sum |x| covers it
+    tx_err = 2.0 ** -18 * np.abs(_np(x).astype(np.float64)).sum(axis=1)
+    tol = 1e-3 * np.abs(ref) + 2.0 ** -24 + 2.0 ** -21 * (np.abs(first) + np.abs(second)) + \
+        tx_err[:, None] * (z.astype(np.float64) * s)[None, :]
+    got = _np(out).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= tol), f"worst {np.max(np.abs(got - ref) - tol)}"
+    # and it is an approximation of the exact fold, not the same thing: bounded by z*sw*K*sx/2
+    bound = (K * osx.astype(np.float64) / 2)[:, None] * (z.astype(np.float64) * s)[None, :]
+    assert np.all(np.abs(got - _np(exact).astype(np.float64)) <= bound + 2e-3 * (np.abs(ref) + 1e-3))
