@@ -189,3 +189,26 @@ def output_fp64_token_sum(raw, sx, sw, z, tx):
              * np.asarray(sx, dtype=np.float16).astype(np.float64)[:, None] * s[None, :])
     second = np.asarray(tx, dtype=np.float64)[:, None] * (np.asarray(z, dtype=np.float64) * s)[None, :]
     return first - second
+
+
+# --- memory-bound producers the activation quantization is fused into (Section 5.1) -------------
+# The paper quantizes the activations inside the kernel that produces them: the normalisation in front
+# of the QKV and first FFN projections, the activation function in front of the second FFN projection.
+# The Llama-family models it evaluates use RMSNorm and SiLU(gate) * up.  Both producers emit FP16
+# (every tensor between kernels is FP16, Section 5.1), so the fused result is defined as
+# act_quant(fp16(producer(x))): one FP64 evaluation, one RNE rounding to FP16, then the quantizer.
+
+def rmsnorm_fp16(x_fp16, gamma_fp16, eps):
+    """y[m, k] = fp16( x[m, k] / sqrt(mean_k x[m, :]^2 + eps) * gamma[k] ), evaluated in float64."""
+    x = np.asarray(x_fp16, dtype=np.float16).astype(np.float64)
+    g = np.asarray(gamma_fp16, dtype=np.float16).astype(np.float64)
+    ms = (x * x).sum(axis=1) / x.shape[1]
+    return (x / np.sqrt(ms + float(eps))[:, None] * g[None, :]).astype(np.float16)
+
+
+def silu_mul_fp16(gate_up_fp16):
+    """gate_up [M, 2K]: gate = first K columns, up = last K.  y = fp16( gate / (1 + exp(-gate)) * up )."""
+    a = np.asarray(gate_up_fp16, dtype=np.float16).astype(np.float64)
+    k = a.shape[1] // 2
+    gate, up = a[:, :k], a[:, k:]
+    return (gate / (1.0 + np.exp(-gate)) * up).astype(np.float16)

@@ -264,3 +264,57 @@ def test_pins_catch_planted_mistakes(bad, monkeypatch):
         monkeypatch.setattr(qq, "level2_group_params", near)
         with pytest.raises(AssertionError):
             test_level2_exhaustive_inside_protective_range()
+
+
+# ------------------------------------------------------------------ producers of the fused quantization
+def test_rmsnorm_closed_forms():
+    import math
+    # constant row c: mean square c^2, y = gamma * c / sqrt(c^2 + eps)
+    x = np.full((1, 64), 0.5, dtype=np.float16)
+    g = np.linspace(0.5, 2.0, 64).astype(np.float16)
+    y = qq.rmsnorm_fp16(x, g, 1e-5)
+    expect = (g.astype(np.float64) * 0.5 / math.sqrt(0.25 + 1e-5)).astype(np.float16)
+    assert np.array_equal(y[0].view(np.uint16), expect.view(np.uint16))
+    # eps = 0: scale invariance, and unit mean square before gamma
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((3, 128)).astype(np.float16)
+    ones = np.ones(128, dtype=np.float16)
+    y1 = qq.rmsnorm_fp16(x, ones, 0.0).astype(np.float64)
+    y2 = qq.rmsnorm_fp16((x.astype(np.float64) * 4).astype(np.float16), ones, 0.0).astype(np.float64)   # exact scaling by 4
+    assert np.array_equal(y1, y2)
+    assert np.allclose((y1 * y1).mean(axis=1), 1.0, atol=2e-3)
+
+
+def test_rmsnorm_against_per_element_fractions():
+    from fractions import Fraction
+    import math
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((2, 16)).astype(np.float16)
+    g = (rng.random(16) + 0.5).astype(np.float16)
+    eps = 1e-6
+    y = qq.rmsnorm_fp16(x, g, eps)
+    for m in range(2):
+        ms = sum(Fraction(float(v)) ** 2 for v in x[m]) / 16 + Fraction(eps)
+        inv = 1.0 / math.sqrt(float(ms))
+        for k in range(16):
+            want = np.float16(float(x[m, k]) * inv * float(g[k]))
+            assert abs(float(y[m, k]) - float(want)) <= abs(float(want)) * 2 ** -10   # at most one FP16 ulp apart
+
+
+def test_silu_mul_identities():
+    import math
+    g = np.array([[0.0, 1.0, -1.0, 8.0, -8.0, 0.5]], dtype=np.float16)
+    u = np.array([[3.0, 2.0, 2.0, 1.0, 1.0, -4.0]], dtype=np.float16)
+    y = qq.silu_mul_fp16(np.concatenate([g, u], axis=1)).astype(np.float64)[0]
+    for i in range(6):
+        gv, uv = float(g[0, i]), float(u[0, i])
+        want = np.float16(gv / (1.0 + math.exp(-gv)) * uv)
+        assert float(y[i]) == float(want)
+    assert y[0] == 0.0
+    # silu(x) - silu(-x) == x, checked through two columns with up = 1
+    gg = np.array([[1.5, -1.5]], dtype=np.float16)
+    yy = qq.silu_mul_fp16(np.concatenate([gg, np.ones((1, 2), np.float16)], axis=1)).astype(np.float64)[0]
+    assert abs((yy[0] - yy[1]) - 1.5) <= 2 ** -10
+    # orientation: gate is the FIRST half
+    z = qq.silu_mul_fp16(np.array([[0.0, 5.0]], dtype=np.float16))
+    assert float(z[0, 0]) == 0.0
