@@ -114,6 +114,22 @@ int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packe
                       int64_t M, int64_t N, int64_t K, int mode,
                       int32_t* acc, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Activation quantization fused into the memory-bound kernel that produces the activations (Section 5.1: into
+ * the normalisation in front of the QKV and first FFN projections, into the activation function in front of the
+ * second FFN projection; RMSNorm and SiLU(gate) * up for the Llama-family layers the paper evaluates).
+ *   qoq_rmsnorm_quant:   y[m, k] = x[m, k] * r[m] * gamma[k],  r[m] = 1 / sqrt(mean_k x[m, :]^2 + eps)
+ *   qoq_silu_mul_quant:  y[m, k] = g / (1 + exp(-g)) * u,  g = gate_up[m, k], u = gate_up[m, K + k]  (gate_up is [M, 2K])
+ * y is evaluated in FP64 and rounded once to FP16, the tensor an unfused pipeline would pass on; (qx, sx, rowsum, tx)
+ * are then exactly qoq_quant_act_per_token(y).  One read of the input, no intermediate tensor.
+ *   x_fp16 / gate_up_fp16   FP16, row-major (read only); gamma_fp16 [K] FP16; eps >= 0
+ *   y_fp16     [M, K] FP16, optional (NULL: the FP16 activations are not written at all)
+ *   qx, sx_fp16, rowsum (nullable), tx (nullable): as for qoq_quant_act_per_token
+ * K % 128 == 0 and K <= 32768 (a token row is held in registers); otherwise QOQ_ERR_SHAPE. */
+int qoq_rmsnorm_quant(const void* x_fp16, const void* gamma_fp16, double eps, int64_t M, int64_t K, void* y_fp16,
+                      int8_t* qx, void* sx_fp16, int32_t* rowsum, float* tx, void* stream);
+int qoq_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K, void* y_fp16,
+                       int8_t* qx, void* sx_fp16, int32_t* rowsum, float* tx, void* stream);
+
 /* Per-channel W4A8 GEMM with the zero point subtracted after the multiplication exactly as Section 5.2.2
  * fuses it into the epilogue (its Eq. 6 with the quantized activations of the second term replaced by the
  * unquantized ones, Eq. 7):

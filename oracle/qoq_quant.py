@@ -199,11 +199,13 @@ def output_fp64_token_sum(raw, sx, sw, z, tx):
 # act_quant(fp16(producer(x))): one FP64 evaluation, one RNE rounding to FP16, then the quantizer.
 
 def rmsnorm_fp16(x_fp16, gamma_fp16, eps):
-    """y[m, k] = fp16( x[m, k] / sqrt(mean_k x[m, :]^2 + eps) * gamma[k] ), evaluated in float64."""
+    """y[m, k] = fp16( x[m, k] * r[m] * gamma[k] ), r[m] = 1 / sqrt(mean_k x[m, :]^2 + eps): the reciprocal root is
+    formed once per token and multiplied in (the usual statement of RMSNorm), all in float64."""
     x = np.asarray(x_fp16, dtype=np.float16).astype(np.float64)
     g = np.asarray(gamma_fp16, dtype=np.float16).astype(np.float64)
     ms = (x * x).sum(axis=1) / x.shape[1]
-    return (x / np.sqrt(ms + float(eps))[:, None] * g[None, :]).astype(np.float16)
+    r = 1.0 / np.sqrt(ms + float(eps))
+    return (x * r[:, None] * g[None, :]).astype(np.float16)
 
 
 def silu_mul_fp16(gate_up_fp16):

@@ -39,6 +39,11 @@ _SIGNATURES = {
     "qoq_w4a8_gemm_i32": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "qoq_rmsnorm_quant": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p]),
+    "qoq_silu_mul_quant": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "qoq_w4a8_gemm_token_sum": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
@@ -227,3 +232,34 @@ def w4a8_gemm_token_sum(qx, sx, tx, packed, N, out=None, workspace=None):
     _check(lib().qoq_w4a8_gemm_token_sum(_ptr(qx), _ptr(sx), _ptr(tx), _ptr(packed), M, N, K, _ptr(out),
                                          _ptr(workspace), ws_bytes, _stream(qx.device)))
     return out
+
+
+def _quant_outputs(M, K, dev, want_y, want_rowsum, want_tx):
+    y = torch.empty((M, K), dtype=torch.float16, device=dev) if want_y else None
+    qx = torch.empty((M, K), dtype=torch.int8, device=dev)
+    sx = torch.empty(M, dtype=torch.float16, device=dev)
+    rowsum = torch.empty(M, dtype=torch.int32, device=dev) if want_rowsum else None
+    tx = torch.empty(M, dtype=torch.float32, device=dev) if want_tx else None
+    return y, qx, sx, rowsum, tx
+
+
+def rmsnorm_quant(x, gamma, eps, want_y=True, want_rowsum=True, want_tx=False):
+    """RMSNorm with the per-token quantization fused in; returns (y FP16 | None, qx, sx, rowsum | None, tx | None)."""
+    _dev(x, torch.float16, "x")
+    _dev(gamma, torch.float16, "gamma")
+    M, K = x.shape
+    y, qx, sx, rowsum, tx = _quant_outputs(M, K, x.device, want_y, want_rowsum, want_tx)
+    _check(lib().qoq_rmsnorm_quant(_ptr(x), _ptr(gamma), float(eps), M, K, _ptr(y), _ptr(qx), _ptr(sx), _ptr(rowsum),
+                                   _ptr(tx), _stream(x.device)))
+    return y, qx, sx, rowsum, tx
+
+
+def silu_mul_quant(gate_up, want_y=True, want_rowsum=True, want_tx=False):
+    """SiLU(gate) * up on a fused [M, 2K] tensor with the per-token quantization fused in."""
+    _dev(gate_up, torch.float16, "gate_up")
+    M, K2 = gate_up.shape
+    K = K2 // 2
+    y, qx, sx, rowsum, tx = _quant_outputs(M, K, gate_up.device, want_y, want_rowsum, want_tx)
+    _check(lib().qoq_silu_mul_quant(_ptr(gate_up), M, K, _ptr(y), _ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(tx),
+                                    _stream(gate_up.device)))
+    return y, qx, sx, rowsum, tx

@@ -93,26 +93,19 @@ __global__ __launch_bounds__(kThreads) void act_quant_kernel(const __half* __res
 // Single-read variant: 512 threads, up to kCache 16-byte chunks (8 halves each) per thread in registers.
 constexpr int kWide = 512;
 constexpr int kCache = 8;
+constexpr int64_t kMaxCachedK = (int64_t)kWide * kCache * 8;
 
-__global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* __restrict__ x, int64_t K,
-                                                                 int8_t* __restrict__ qx, __half* __restrict__ sx,
-                                                                 int32_t* __restrict__ rowsum, float* __restrict__ tx)
+// Quantize a token row that the workgroup holds in registers (chunk c = threadIdx.x + i * kWide in v[i],
+// zeros past the end): absmax, scale, INT8 codes, sums.  Used by the plain quantizer and by the producers the
+// quantization is fused into.
+template <int CACHE>
+__device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, int64_t m, int64_t K,
+                                           int8_t* __restrict__ qx, __half* __restrict__ sx,
+                                           int32_t* __restrict__ rowsum, float* __restrict__ tx, float* s_f, int* s_i)
 {
-    __shared__ float s_f[kWide / 64];
-    __shared__ int s_i[kWide / 64];
-    const int64_t m = blockIdx.x;
-    const uint4* row = reinterpret_cast<const uint4*>(x + m * K);
-    const int chunks = (int)(K / 8);
-
-    uint4 v[kCache];
-#pragma unroll
-    for (int i = 0; i < kCache; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
-        v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
-    }
     float amax = 0.f;
 #pragma unroll
-    for (int i = 0; i < kCache; ++i) {
+    for (int i = 0; i < CACHE; ++i) {
         const __half2* h = reinterpret_cast<const __half2*>(&v[i]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -136,7 +129,7 @@ __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* _
     float fsum = 0.f;
     uint2* qrow = reinterpret_cast<uint2*>(qx + m * K);
 #pragma unroll
-    for (int i = 0; i < kCache; ++i) {
+    for (int i = 0; i < CACHE; ++i) {
         const int c = (int)threadIdx.x + i * kWide;
         if (c < chunks) {
             const __half2* h = reinterpret_cast<const __half2*>(&v[i]);
@@ -169,19 +162,183 @@ __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* _
     }
 }
 
+__global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* __restrict__ x, int64_t K,
+                                                                 int8_t* __restrict__ qx, __half* __restrict__ sx,
+                                                                 int32_t* __restrict__ rowsum, float* __restrict__ tx)
+{
+    __shared__ float s_f[kWide / 64];
+    __shared__ int s_i[kWide / 64];
+    const int64_t m = blockIdx.x;
+    const uint4* row = reinterpret_cast<const uint4*>(x + m * K);
+    const int chunks = (int)(K / 8);
+    uint4 v[kCache];
+#pragma unroll
+    for (int i = 0; i < kCache; ++i) {
+        const int c = (int)threadIdx.x + i * kWide;
+        v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
+}
+
+// ---- producers with the quantization fused in (Section 5.1: the activations are quantized inside the
+// normalisation in front of the QKV / first FFN projection and inside the activation function in front of the
+// second FFN projection).  The producer is evaluated in FP64 and rounded once to FP16 (the exact bit routine
+// below), which defines the tensor an unfused pipeline would hand to the quantizer; the codes are then decided
+// from that FP16 value exactly as in the stand-alone kernel.
+__device__ inline uint16_t double_to_half_rne(double d)   // finite d; exact round-to-nearest-even, integer arithmetic only
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(d);
+    const uint16_t sign = (uint16_t)((bits >> 48) & 0x8000u);
+    const int e = (int)((bits >> 52) & 0x7FF) - 1023;    // d = 1.m * 2^e (FP64 subnormals are far below FP16's range)
+    if (e < -25) return sign;                            // below half of the smallest FP16 subnormal (or zero)
+    if (e > 15) return sign | 0x7C00u;
+    const uint64_t mant = (bits & 0xFFFFFFFFFFFFFull) | (1ull << 52);   // 53 significant bits
+    // FP16 keeps 10 fraction bits for e >= -14, fewer below: drop `shift` low bits with round-half-to-even
+    const int shift = e >= -14 ? 42 : 42 + (-14 - e);    // 42 .. 53
+    const uint64_t kept = mant >> shift, rest = mant & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+    const uint64_t rounded = kept + ((rest > half || (rest == half && (kept & 1))) ? 1 : 0);
+    // e >= -14: rounded in [1024, 2048]; the biased exponent is added on top of the hidden bit, so a carry to
+    // 2048 bumps the exponent by itself (and 65520 and above become infinity).  e < -14: rounded is the
+    // subnormal pattern (1024 = smallest normal).
+    const uint32_t h = e >= -14 ? (uint32_t)((e + 14) << 10) + (uint32_t)rounded : (uint32_t)rounded;
+    return sign | (uint16_t)(h > 0x7C00u ? 0x7C00u : h);
+}
+
+__device__ inline void unpack8(const uint4& v, double (&f)[8])
+{
+    const __half* h = reinterpret_cast<const __half*>(&v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) f[j] = (double)__half2float(h[j]);
+}
+
+__device__ inline uint4 pack8(const double (&f)[8])
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        w[j] = (uint32_t)double_to_half_rne(f[2 * j]) | ((uint32_t)double_to_half_rne(f[2 * j + 1]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// y = x * (1 / sqrt(mean(x^2) + eps)) * gamma
+template <int CACHE>
+__global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __restrict__ x, const __half* __restrict__ gamma,
+                                                              double eps, int64_t K, __half* __restrict__ y,
+                                                              int8_t* __restrict__ qx, __half* __restrict__ sx,
+                                                              int32_t* __restrict__ rowsum, float* __restrict__ tx)
+{
+    __shared__ float s_f[kWide / 64];
+    __shared__ int s_i[kWide / 64];
+    __shared__ double s_d[kWide / 64];
+    const int64_t m = blockIdx.x;
+    const uint4* row = reinterpret_cast<const uint4*>(x + m * K);
+    const uint4* grow = reinterpret_cast<const uint4*>(gamma);
+    const int chunks = (int)(K / 8);
+    uint4 v[CACHE];
+    double ss = 0.0;
+#pragma unroll
+    for (int i = 0; i < CACHE; ++i) {
+        const int c = (int)threadIdx.x + i * kWide;
+        v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
+        double f[8];
+        unpack8(v[i], f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += f[j] * f[j];
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if ((threadIdx.x & 63) == 0) s_d[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWide / 64; ++w) ss += s_d[w];
+    const double inv = 1.0 / sqrt(ss / (double)K + eps);
+#pragma unroll
+    for (int i = 0; i < CACHE; ++i) {
+        const int c = (int)threadIdx.x + i * kWide;
+        if (c < chunks) {
+            double f[8], g[8];
+            unpack8(v[i], f);
+            const uint4 gv = grow[c];
+            unpack8(gv, g);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) f[j] = f[j] * inv * g[j];
+            v[i] = pack8(f);
+            if (y) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
+        }
+    }
+    quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
+}
+
+// gate_up [M, 2K]: y = gate / (1 + exp(-gate)) * up with gate = first K columns, up = last K
+template <int CACHE>
+__global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __restrict__ gate_up, int64_t K,
+                                                               __half* __restrict__ y, int8_t* __restrict__ qx,
+                                                               __half* __restrict__ sx, int32_t* __restrict__ rowsum,
+                                                               float* __restrict__ tx)
+{
+    __shared__ float s_f[kWide / 64];
+    __shared__ int s_i[kWide / 64];
+    const int64_t m = blockIdx.x;
+    const uint4* grow = reinterpret_cast<const uint4*>(gate_up + m * 2 * K);
+    const uint4* urow = reinterpret_cast<const uint4*>(gate_up + m * 2 * K + K);
+    const int chunks = (int)(K / 8);
+    uint4 v[CACHE];
+#pragma unroll
+    for (int i = 0; i < CACHE; ++i) {
+        const int c = (int)threadIdx.x + i * kWide;
+        v[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (c < chunks) {
+            double g[8], u[8];
+            const uint4 gv = grow[c], uv = urow[c];
+            unpack8(gv, g);
+            unpack8(uv, u);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) g[j] = g[j] / (1.0 + exp(-g[j])) * u[j];
+            v[i] = pack8(g);
+            if (y) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
+        }
+    }
+    quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
+}
+
 }  // namespace
 
 hipError_t launch_act_quant(const void* x_fp16, int64_t M, int64_t K, int8_t* qx, void* sx, int32_t* rowsum,
                             float* tx, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
-    if (K <= (int64_t)kWide * kCache * 8) {
+    if (K <= kMaxCachedK) {
         act_quant_cached_kernel<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx,
                                                                    static_cast<__half*>(sx), rowsum, tx);
         return hipGetLastError();
     }
     act_quant_kernel<<<dim3((unsigned)M), kThreads, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx,
                                                            static_cast<__half*>(sx), rowsum, tx);
+    return hipGetLastError();
+}
+
+int64_t fused_quant_max_k() { return kMaxCachedK; }
+
+hipError_t launch_rmsnorm_quant(const void* x_fp16, const void* gamma_fp16, double eps, int64_t M, int64_t K, void* y_fp16,
+                                int8_t* qx, void* sx, int32_t* rowsum, float* tx, hipStream_t s)
+{
+    if (M == 0) return hipSuccess;
+    // shorter rows need fewer cached chunks per thread: far fewer registers, more waves per CU
+    auto* kern = K <= (int64_t)kWide * 2 * 8 ? rmsnorm_quant_kernel<2>
+               : K <= (int64_t)kWide * 4 * 8 ? rmsnorm_quant_kernel<4> : rmsnorm_quant_kernel<kCache>;
+    kern<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), static_cast<const __half*>(gamma_fp16), eps, K,
+                                            static_cast<__half*>(y_fp16), qx, static_cast<__half*>(sx), rowsum, tx);
+    return hipGetLastError();
+}
+
+hipError_t launch_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K, void* y_fp16, int8_t* qx, void* sx,
+                                 int32_t* rowsum, float* tx, hipStream_t s)
+{
+    if (M == 0) return hipSuccess;
+    auto* kern = K <= (int64_t)kWide * 2 * 8 ? silu_mul_quant_kernel<2>
+               : K <= (int64_t)kWide * 4 * 8 ? silu_mul_quant_kernel<4> : silu_mul_quant_kernel<kCache>;
+    kern<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(gate_up_fp16), K, static_cast<__half*>(y_fp16), qx,
+                                            static_cast<__half*>(sx), rowsum, tx);
     return hipGetLastError();
 }
 

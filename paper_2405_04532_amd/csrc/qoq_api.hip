@@ -181,6 +181,31 @@ int qoq_quant_act_per_token(const void* x_fp16_dev, int64_t M, int64_t K, int8_t
                    hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
 
+int qoq_rmsnorm_quant(const void* x_fp16, const void* gamma_fp16, double eps, int64_t M, int64_t K, void* y_fp16,
+                      int8_t* qx, void* sx_fp16, int32_t* rowsum, float* tx, void* stream)
+{
+    if (M < 0 || M > (1 << 24) || K <= 0 || (K % qoq::kGroup) != 0 || K > qoq::fused_quant_max_k() || !(eps >= 0.0))
+        return QOQ_ERR_SHAPE;
+    if (M == 0) return QOQ_OK;
+    if (!x_fp16 || !gamma_fp16 || !qx || !sx_fp16) return QOQ_ERR_NULL;
+    if (!aligned16(x_fp16) || !aligned16(gamma_fp16) || !aligned16(qx) || !aligned16(y_fp16)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_rmsnorm_quant(x_fp16, gamma_fp16, eps, M, K, y_fp16, qx, sx_fp16, rowsum, tx,
+                                     static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K, void* y_fp16, int8_t* qx, void* sx_fp16,
+                       int32_t* rowsum, float* tx, void* stream)
+{
+    if (M < 0 || M > (1 << 24) || K <= 0 || (K % qoq::kGroup) != 0 || K > qoq::fused_quant_max_k()) return QOQ_ERR_SHAPE;
+    if (M == 0) return QOQ_OK;
+    if (!gate_up_fp16 || !qx || !sx_fp16) return QOQ_ERR_NULL;
+    if (!aligned16(gate_up_fp16) || !aligned16(qx) || !aligned16(y_fp16)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_silu_mul_quant(gate_up_fp16, M, K, y_fp16, qx, sx_fp16, rowsum, tx,
+                                      static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
 int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum, const void* packed, int64_t M,
                   int64_t N, int64_t K, int mode, void* out_fp16, void* workspace, size_t workspace_bytes,
                   void* stream)

@@ -18,6 +18,13 @@ hipError_t launch_unpack(const uint8_t* blob, const BlobLayout& L, uint8_t* q, u
 hipError_t launch_act_quant(const void* x_fp16, int64_t M, int64_t K, int8_t* qx, void* sx, int32_t* rowsum,
                             float* tx, hipStream_t s);
 
+// producers with the quantization fused in (rows of at most fused_quant_max_k() elements)
+int64_t fused_quant_max_k();
+hipError_t launch_rmsnorm_quant(const void* x_fp16, const void* gamma_fp16, double eps, int64_t M, int64_t K, void* y_fp16,
+                                int8_t* qx, void* sx, int32_t* rowsum, float* tx, hipStream_t s);
+hipError_t launch_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K, void* y_fp16, int8_t* qx, void* sx,
+                                 int32_t* rowsum, float* tx, hipStream_t s);
+
 // qoq_gemm.hip
 struct GemmArgs {
     const int8_t* qx;

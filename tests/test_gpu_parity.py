@@ -320,3 +320,52 @@ def test_per_channel_token_sum_epilogue(api, M, N, K, cfg):
     # and it is an approximation of the exact fold, not the same thing: bounded by z*sw*K*sx/2
     bound = (K * osx.astype(np.float64) / 2)[:, None] * (z.astype(np.float64) * s)[None, :]
     assert np.all(np.abs(got - _np(exact).astype(np.float64)) <= bound + 2e-3 * (np.abs(ref) + 1e-3))
+
+
+# ---------------------------------------------------------------------------- quantization fused into the producer
+def _producer_inputs(M, K, seed):
+    x = wl.make_activations(M, K, seed, DEV, outlier_count=max(1, K // 100))
+    gamma = (wl.normal(seed + 1, 7, K, DEV) * 0.1 + 1.0).to(torch.float16)
+    return x, gamma
+
+
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768)])
+def test_rmsnorm_quant_matches_oracle(api, M, K):
+    x, gamma = _producer_inputs(M, K, seed=11 * M + K)
+    if M >= 4:
+        x[2] = 0                                   # all-zero token: y = 0, scale 1.0
+    eps = 1e-5
+    y, qx, sx, rowsum, tx = api.rmsnorm_quant(x, gamma, eps, want_y=True, want_rowsum=True, want_tx=True)
+    ry = qq.rmsnorm_fp16(_np(x), _np(gamma), eps)
+    assert (_np(y).view(np.uint16) == ry.view(np.uint16)).all()
+    rqx, rsx, rrow, rtx = qq.act_quant(ry)
+    assert (_np(sx).view(np.uint16) == rsx.view(np.uint16)).all()
+    assert (_np(qx).astype(np.int64) == rqx).all()
+    assert (_np(rowsum).astype(np.int64) == rrow).all()
+    assert np.allclose(_np(tx), rtx, rtol=1e-4, atol=1e-2)
+    # without the FP16 activations written, and equal to the unfused path on the same y
+    _, qx2, sx2, _, _ = api.rmsnorm_quant(x, gamma, eps, want_y=False, want_rowsum=False)
+    qx3, sx3, _, _ = api.quant_act_per_token(y)
+    assert torch.equal(qx, qx2) and torch.equal(qx, qx3)
+    assert torch.equal(sx.view(torch.int16), sx2.view(torch.int16)) and torch.equal(sx.view(torch.int16), sx3.view(torch.int16))
+
+
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 11008), (4, 14336), (2, 28672)])
+def test_silu_mul_quant_matches_oracle(api, M, K):
+    gu = wl.make_activations(M, 2 * K, 5 * M + K, DEV, outlier_count=max(1, K // 50), gain=6.0)
+    y, qx, sx, rowsum, tx = api.silu_mul_quant(gu, want_y=True, want_rowsum=True, want_tx=True)
+    ry = qq.silu_mul_fp16(_np(gu))
+    assert (_np(y).view(np.uint16) == ry.view(np.uint16)).all()
+    rqx, rsx, rrow, rtx = qq.act_quant(ry)
+    assert (_np(sx).view(np.uint16) == rsx.view(np.uint16)).all()
+    assert (_np(qx).astype(np.int64) == rqx).all()
+    assert (_np(rowsum).astype(np.int64) == rrow).all()
+    assert np.allclose(_np(tx), rtx, rtol=1e-4, atol=1e-2)
+
+
+def test_fused_producers_reject_long_rows(api):
+    x = torch.zeros((1, 40960), dtype=torch.float16, device=DEV)
+    g = torch.ones(40960, dtype=torch.float16, device=DEV)
+    with pytest.raises(api.QoqError) as e:
+        api.rmsnorm_quant(x, g, 1e-5)
+    assert e.value.status == 2
