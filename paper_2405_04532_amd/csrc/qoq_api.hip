@@ -50,6 +50,7 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     int tile_m, split_k;
     qoq::pick_gemm_config(M, N, K, forced(), tile_m, split_k);
     if ((uint64_t)M * (uint64_t)K >= ((uint64_t)1 << 32)) return QOQ_ERR_SHAPE;  // 32-bit activation offsets
+    if (tile_m <= 64 && (uint64_t)N * (uint64_t)K >= ((uint64_t)1 << 33)) return QOQ_ERR_SHAPE;  // 32-bit weight offsets (4 GiB packed)
     const size_t need = qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
     if (need && (!ws || ws_bytes < need)) return QOQ_ERR_WORKSPACE;
     if (x_fp16 && !aligned16(x_fp16)) return QOQ_ERR_ALIGN;

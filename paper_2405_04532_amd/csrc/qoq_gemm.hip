@@ -37,6 +37,7 @@
 #include <hip/hip_runtime.h>
 
 #include "qoq_internal.h"
+#include "qoq_walk.h"
 
 namespace qoq {
 namespace {
@@ -134,9 +135,30 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 // Write-through store / cache-bypassing load of 16 bytes (device-coherent without fences).
+// A store of more than 8 bytes reads its data registers over several cycles after issue; the instruction that
+// follows must not write them (a documented wait-state requirement the compiler honours for its own stores but
+// cannot for inline assembly, which it does not know to be a store: partial sums whose registers were reused at
+// once came out corrupted in a few lanes).  Hence the idle cycles inside the store statements.  The streaming
+// kernel goes further and keeps its stores out of the loop altogether (below): they go out after the last copy,
+// together with the wait for their completion, from registers the same statement keeps alive.
 __device__ __forceinline__ void store_sc1(int4* ptr, v4i v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(ptr), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" :: "v"(ptr), "v"(v) : "memory");
+}
+template <int CNT>
+__device__ __forceinline__ void store_sc1_and_wait(int4* ptr, int stride, const v4i (&v)[CNT])
+{
+    static_assert(CNT == 1 || CNT == 2 || CNT == 4, "fragments per lane");
+    if constexpr (CNT == 1)
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" :: "v"(ptr), "v"(v[0]) : "memory");
+    else if constexpr (CNT == 2)
+        asm volatile("global_store_dwordx4 %0, %2, off sc1\n\tglobal_store_dwordx4 %1, %3, off sc1\n\ts_waitcnt vmcnt(0)"
+                     :: "v"(ptr), "v"(ptr + stride), "v"(v[0]), "v"(v[1]) : "memory");
+    else
+        asm volatile("global_store_dwordx4 %0, %4, off sc1\n\tglobal_store_dwordx4 %1, %5, off sc1\n\t"
+                     "global_store_dwordx4 %2, %6, off sc1\n\tglobal_store_dwordx4 %3, %7, off sc1\n\ts_waitcnt vmcnt(0)"
+                     :: "v"(ptr), "v"(ptr + stride), "v"(ptr + 2 * stride), "v"(ptr + 3 * stride), "v"(v[0]), "v"(v[1]), "v"(v[2]),
+                     "v"(v[3]) : "memory");
 }
 __device__ __forceinline__ void load_sc1_nowait(v4i& v, const int4* ptr)
 {
@@ -147,37 +169,7 @@ __device__ __forceinline__ void wait_loads(v4i& a, v4i& b, v4i& c, v4i& d)
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) :: "memory");
 }
 
-constexpr int kStreamThreads = 640;  // eight consumer waves + two producer waves
-
-// Walk over a workgroup's run of work units (unit u = block * G + g), two units per iteration.
-// A pair never straddles a block boundary or the end of the run.  Kept to a handful of scalar
-// instructions per step: nine waves execute it every iteration and the scalar unit is shared.
-struct Walk {
-    int block, g;   // first unit of the next iteration
-    int left;       // units left in the current block segment (0 = run exhausted)
-    int rem;        // units of the run after this segment
-};
-__device__ __forceinline__ void walk_init(Walk& w, int u0, int u1, int G)
-{
-    w.block = __builtin_amdgcn_readfirstlane(u0 / G);
-    w.g = u0 - w.block * G;
-    w.left = min(G - w.g, u1 - u0);
-    w.rem = (u1 - u0) - w.left;
-}
-// advance by the iteration's n = min(2, left) units; returns true if that finished the segment
-__device__ __forceinline__ bool walk_step(Walk& w, int n, int G)
-{
-    w.g += n;
-    w.left -= n;
-    if (w.left > 0) return false;
-    if (w.rem > 0) {
-        w.block += 1;
-        w.g = 0;
-        w.left = min(G, w.rem);
-        w.rem -= w.left;
-    }
-    return true;
-}
+constexpr int kStreamThreads = 768;  // eight consumer waves + four producer waves
 
 template <bool GROUP, int OUT>
 __device__ __forceinline__ void finish4(const GemmDev& p, int m, int n0, v4i v, const float (&sn)[4],
@@ -214,17 +206,20 @@ __device__ __forceinline__ void finish4(const GemmDev& p, int m, int n0, v4i v, 
 }
 
 template <int MF, bool GROUP, int OUT>
-__global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void stream_kernel(GemmDev p)
 {
     // Weights: every consumer wave owns a deep private ring of 1 KiB units.  Activations, metadata and
     // scales: shallow rings, one slot per iteration (= two consecutive groups of a block), filled by
-    // the two producer waves (producer k serves the k-th group of the pair).
+    // four producer waves (producer (pk, ph) copies half ph of the activation blocks of the pk-th group of
+    // the pair; the ph = 0 ones also the group's metadata, producer (0, 1) the block's scales).  Producers and
+    // consumers run separate, tight loops that meet at the same barriers: with one loop for both roles every
+    // wave branched around the other role's code, and the producers' ten copies plus that branching set
+    // the pace of the whole workgroup (measured with s_memtime probes).
     constexpr int kWRing = MF == 4 ? 10 : 12;
     constexpr int kARing = 3;
     constexpr int kABlocks = 2 * MF;                                  // 1 KiB blocks (m-fragment, k-step) per group
-    constexpr int kProducerDma0 = kABlocks + (GROUP ? 1 : 0) + 1;     // producer 0 also copies the scales
-    constexpr int kProducerDma1 = kABlocks + (GROUP ? 1 : 0);
-    static_assert(kWRing - 2 < 64 && (kARing - 2) * kProducerDma0 < 64, "vmcnt range");
+    constexpr int kAHalf = kABlocks / 2;                              // activation blocks per producer wave
+    static_assert(kWRing - 2 < 64 && (kARing - 2) * (kAHalf + 1) < 64, "vmcnt range");
     __shared__ uint4 wring[8][kWRing][64];            // private ring of weight units per consumer wave
     __shared__ uint4 aring[kARing][2][kABlocks * 64]; // activation slabs of the iteration's two groups
     __shared__ uint4 mring[kARing][2][16];            // level-2 metadata: 4 fragments x 16 rows x uint16
@@ -238,6 +233,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool producer = wave >= 8;
     const int pk = wave & 1;                               // producer: which group of the pair
+    const int ph = (wave >> 1) & 1;                        // producer: which half of the group's activation blocks
     const int f = (wave & 7) >> 1, e = wave & 1;           // consumer: fragment, group parity
     const int wg = blockIdx.x;
     const int m0 = blockIdx.y * (16 * MF);
@@ -249,10 +245,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
     const int q = lane >> 4, ml = lane & 15;
     const int nf_total = p.N / 16;
 
-    Walk cw;                                               // what is being consumed
-    walk_init(cw, u0, u1, G);
-    Walk iw = cw;                                          // what this wave copies next (runs ahead)
-    const int first_g = cw.g;
+    // The run's iteration structure in closed form (qoq_walk.h), all wave-uniform.
+    RunShape run = make_run(u0, u1, G);
+    run.b0 = __builtin_amdgcn_readfirstlane(run.b0); run.g0 = __builtin_amdgcn_readfirstlane(run.g0);
+    run.full = __builtin_amdgcn_readfirstlane(run.full); run.last_len = __builtin_amdgcn_readfirstlane(run.last_len);
+    const int T = __builtin_amdgcn_readfirstlane(run.T);
 
     v4i acc[MF];
 #pragma unroll
@@ -261,14 +258,15 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
     // ---- copy roles -----------------------------------------------------------------------
     // producer: lane 4r+c copies 16-byte chunk c ^ h(r) of row r of a 16-row activation block: a quad
     // reads one 64-byte row segment; h spreads the rows over the LDS banks for the fragment reads
-    uint32_t a_voff[kABlocks];
+    uint32_t a_voff[kAHalf];                               // blocks ph * kAHalf .. of the group
     {
         const int r = lane >> 2, c = lane & 3;
         const int h = ((r >> 1) ^ (r >> 2)) & 3;
 #pragma unroll
-        for (int b = 0; b < kABlocks; ++b) {
+        for (int j = 0; j < kAHalf; ++j) {
+            const int b = ph * kAHalf + j;
             const int row = min(m0 + (b >> 1) * 16 + r, p.M - 1);  // rows past M repeat the last one; never stored
-            a_voff[b] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((b & 1) * 64 + (c ^ h) * 16);
+            a_voff[j] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((b & 1) * 64 + (c ^ h) * 16);
         }
     }
     const uint32_t m_voff = (uint32_t)(lane & 31) * 4u;                      // 128 B of metadata; upper lanes re-read
@@ -277,44 +275,62 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
     const uint32_t s_voff = (lane < 32 || GROUP) ? (uint32_t)(lane & 31) * 4u : zero_delta + (uint32_t)((lane - 32) & 15) * 4u;
     const uint32_t s_blk_stride = (lane < 32 || GROUP) ? 128u : 64u;         // bytes per block in either array
     const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0] + (uint32_t)(wave & 7) * (kWRing * 1024);
-    const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)pk * (kABlocks * 1024);
+    const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)(pk * kABlocks + ph * kAHalf) * 1024u;
     const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * 256;
     const uint32_t sring_addr = (uint32_t)(uintptr_t)&sring[0][0];
     constexpr uint32_t kASlot = 2 * kABlocks * 1024;
     const char* abase = reinterpret_cast<const char*>(p.qx);
     const char* sbase = reinterpret_cast<const char*>(p.scales);
     const uint32_t w_voff = (uint32_t)lane * 16u;
-    // per-block base pointers, refreshed only when the walk enters a new block
-    const size_t w_block_stride = (size_t)kNFrag * G * 1024;
-    const char* w_row = reinterpret_cast<const char*>(p.codes) + ((size_t)(iw.block * kNFrag + f) * G) * 1024;
-    const char* m_row = reinterpret_cast<const char*>(p.meta) + (size_t)iw.block * kNFrag * 32;
-    const size_t m_g_stride = (size_t)nf_total * 32;
-    int i_block = iw.block;
+    const char* codes_base = reinterpret_cast<const char*>(p.codes);
+    const char* meta_base = reinterpret_cast<const char*>(p.meta);
+    const uint32_t m_g_stride = (uint32_t)nf_total * 32u;
 
-    // Copies for the iteration at the issue walk.  Past the end of the run every iteration still issues
-    // the same number of copies (the wait counts rely on it); the walk then rests one group past the last
-    // one consumed, which may be group G, so the group index is clamped: group G of the last token row
-    // (or of the last fragment) would lie beyond the end of the tensor.
-    int islot = 0;
-    auto issue = [&]() {
-        const int n = min(2, max(iw.left, 1));
+    // Tables: lane j of a wave holds what the wave needs to know about iteration tbase + j (iterations past the
+    // end of the run repeat the last one: every iteration issues the same number of copies, the wait counts rely
+    // on it, and a repeated copy reads valid memory).  The loop reads them with v_readlane instead of stepping a
+    // state machine in scalar registers: with twelve waves per workgroup the scalar instructions, not the
+    // copies, set the pace of an iteration.
+    //   info  = first group | (units - 1) << 24 | ends a segment << 25 | that segment is a whole block << 26
+    //   block = 64-channel block
+    //   off0  = consumer: byte offset of the wave's weight unit; producer: column offset of its group
+    //   off1  = producer: byte offset of the group's metadata row
+    struct Tables { uint32_t info, block, off0, off1; };
+    auto build_tables = [&](int base) __attribute__((always_inline)) {
+        Tables t;
+        const IterInfo o = run_iteration(run, min(base + lane, T - 1));
+        t.info = (uint32_t)o.g | ((uint32_t)(o.n - 1) << 24) | ((uint32_t)(o.seg_end ? 1 : 0) << 25) |
+                 ((uint32_t)(o.complete ? 1 : 0) << 26);
+        t.block = (uint32_t)o.block;
         if (producer) {
-            const int g = min(iw.g + (pk < n ? pk : 0), G - 1);
-#pragma unroll
-            for (int b = 0; b < kABlocks; ++b)
-                dma16(abase + (size_t)g * kGroup, a_voff[b], aring_addr + islot * kASlot + b * 1024);
-            if (GROUP) dma4(m_row + (size_t)g * m_g_stride, m_voff, mring_addr + islot * 512);
-            if (pk == 0) dma4(sbase, s_voff + (uint32_t)i_block * s_blk_stride, sring_addr + islot * 256);
-            islot = islot + 1 == kARing ? 0 : islot + 1;
+            const int gsel = min(o.g + (pk < o.n ? pk : 0), G - 1);
+            t.off0 = (uint32_t)gsel * (uint32_t)kGroup;
+            t.off1 = (uint32_t)gsel * m_g_stride + (uint32_t)o.block * (uint32_t)(kNFrag * 32);
         } else {
-            dma16(w_row + (size_t)min(iw.g + (e < n ? e : 0), G - 1) * 1024, w_voff, wring_addr + islot * 1024);
-            islot = islot + 1 == kWRing ? 0 : islot + 1;
+            const int gsel = min(o.g + (e < o.n ? e : 0), G - 1);
+            t.off0 = (uint32_t)((o.block * kNFrag + f) * G + gsel) << 10;
+            t.off1 = 0;
         }
-        if (iw.left > 0 && walk_step(iw, n, G) && iw.left > 0) {
-            i_block = iw.block;
-            w_row += w_block_stride;
-            m_row += kNFrag * 32;
-        }
+        return t;
+    };
+    int tbase = 0;
+    Tables tb = build_tables(0);
+    auto lookup = [](uint32_t table, int j) __attribute__((always_inline)) { return (uint32_t)__builtin_amdgcn_readlane((int)table, j); };
+
+    // Copies for the iteration with table index j.
+    int islot = 0;
+    auto issue_producer = [&](int j) __attribute__((always_inline)) {
+        const uint32_t aoff = lookup(tb.off0, j);
+#pragma unroll
+        for (int b = 0; b < kAHalf; ++b)
+            dma16(abase, a_voff[b] + aoff, aring_addr + islot * kASlot + b * 1024);
+        if (GROUP && ph == 0) dma4(meta_base, m_voff + lookup(tb.off1, j), mring_addr + islot * 512);
+        if (pk == 0 && ph == 1) dma4(sbase, s_voff + lookup(tb.block, j) * s_blk_stride, sring_addr + islot * 256);
+        islot = islot + 1 == kARing ? 0 : islot + 1;
+    };
+    auto issue_consumer = [&](int j) __attribute__((always_inline)) {
+        dma16(codes_base, w_voff + lookup(tb.off0, j), wring_addr + islot * 1024);
+        islot = islot + 1 == kWRing ? 0 : islot + 1;
     };
 
     const int hsw = ((ml >> 1) ^ (ml >> 2)) & 3;
@@ -350,82 +366,113 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(GemmDev p)
     const bool owner = !producer && e == 0;
     int4* my_parts = p.parts + (size_t)(blockIdx.y * gridDim.x + wg) * 2 * (MF * kThreads);
     int npart = 0, part_block[2] = {0, 0};
-    int seg_first_g = first_g, seg_index = 0;
+    // Partial tiles of the run (at most two: a first segment that starts inside a block, a last one that ends
+    // inside a block) stay in registers and are written out after the loop, so that no store sits among the copies.
+    v4i part0[MF], part1[MF];
+    bool has_part0 = false, has_part1 = false;
+#pragma unroll
+    for (int mf = 0; mf < MF; ++mf) part0[mf] = part1[mf] = (v4i){0, 0, 0, 0};
+    int seg_index = 0;
+
+    // bookkeeping every wave keeps identically: segments of the run that end inside a shared block
+    auto close_segment = [&](bool complete, int block_now) __attribute__((always_inline)) {
+        if (!complete) { part_block[npart] = block_now; ++npart; }
+        ++seg_index;
+    };
 
     if (producer) {
+        // ---- producer loop: copies only; same barriers as the consumer loop below --------------------
+        const int my_dma = kAHalf + ((GROUP && ph == 0) ? 1 : 0) + ((pk == 0 && ph == 1) ? 1 : 0);
 #pragma unroll
-        for (int k = 0; k < kARing - 1; ++k) issue();
+        for (int k = 0; k < kARing - 1; ++k) issue_producer(k);
         // per-token epilogue constants go through LDS so that the consumer waves never issue a
         // register load whose compiler-placed wait would drain their copy queue
-        if (pk == 1 && lane < 16 * MF) {
+        if (pk == 1 && ph == 1 && lane < 16 * MF) {
             const int m = min(m0 + lane, p.M - 1);
             sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
             rs_lds[lane] = GROUP ? 0 : p.rowsum[m];
         }
+        for (int it = 0; it < T; ++it) {
+            int j = it - tbase;
+            if (j + kARing - 1 >= 64) { tb = build_tables(it); tbase = it; j = 0; }
+            const uint32_t info = lookup(tb.info, j);
+            if (my_dma == kAHalf) wait_vmcnt<(kARing - 2) * kAHalf>();
+            else wait_vmcnt<(kARing - 2) * (kAHalf + 1)>();
+            __syncthreads();
+            issue_producer(j + kARing - 1);
+            if (!(info & (1u << 25))) continue;
+            __syncthreads();                               // the consumers' hand-over barrier
+            close_segment((info >> 26) & 1, (int)lookup(tb.block, j));
+        }
     } else {
+        // ---- consumer loop ------------------------------------------------------------------------------
 #pragma unroll
-        for (int k = 0; k < kWRing - 1; ++k) issue();
-    }
-    while (cw.left > 0) {
-        const int n = min(2, cw.left);
-        if (!producer) wait_vmcnt<kWRing - 2>();
-        else if (pk == 0) wait_vmcnt<(kARing - 2) * kProducerDma0>();
-        else wait_vmcnt<(kARing - 2) * kProducerDma1>();
-        __syncthreads();
-        issue();
-        if (!producer && e < n) compute();
-        const int aslot_now = aslot;
-        wslot = wslot + 1 == kWRing ? 0 : wslot + 1;
-        aslot = aslot + 1 == kARing ? 0 : aslot + 1;
-        const int block_now = cw.block;
-        const bool wrapped = cw.g + n >= G;
-        if (!walk_step(cw, n, G)) continue;
+        for (int k = 0; k < kWRing - 1; ++k) issue_consumer(k);
+        for (int it = 0; it < T; ++it) {
+            int j = it - tbase;
+            if (j + kWRing - 1 >= 64) { tb = build_tables(it); tbase = it; j = 0; }
+            const uint32_t info = lookup(tb.info, j);
+            wait_vmcnt<kWRing - 2>();
+            __syncthreads();
+            issue_consumer(j + kWRing - 1);
+            if (e == 0 || (info & (1u << 24))) compute();
+            const int aslot_now = aslot;
+            wslot = wslot + 1 == kWRing ? 0 : wslot + 1;
+            aslot = aslot + 1 == kARing ? 0 : aslot + 1;
+            if (!(info & (1u << 25))) continue;
+            const int block_now = (int)lookup(tb.block, j);
 
-        // ---- end of this run's share of block_now: parity-1 waves hand over, owners finish -----
-        if (!producer && e == 1) {
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                red[(f * MF + mf) * 64 + lane] = make_int4(acc[mf].x, acc[mf].y, acc[mf].z, acc[mf].w);
-                acc[mf] = (v4i){0, 0, 0, 0};
-            }
-        }
-        __syncthreads();
-        const bool complete = seg_first_g == 0 && wrapped;
-        if (owner) {
-            float sn[4] = {0.f, 0.f, 0.f, 0.f};
-            int zn[4] = {0, 0, 0, 0};
-            if (complete) {
-                const char* sc = reinterpret_cast<const char*>(&sring[aslot_now][0]);
-                const uint2 sw = *reinterpret_cast<const uint2*>(sc + (16 * q + 4 * f) * 2);
-                sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
-                sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
-                sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
-                sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
-                if (!GROUP) {
-                    const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 128 + 16 * q + 4 * f);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
+            // ---- end of this run's share of block_now: parity-1 waves hand over, owners finish -----
+            if (e == 1) {
+    #pragma unroll
+                for (int mf = 0; mf < MF; ++mf) {
+                    red[(f * MF + mf) * 64 + lane] = make_int4(acc[mf].x, acc[mf].y, acc[mf].z, acc[mf].w);
+                    acc[mf] = (v4i){0, 0, 0, 0};
                 }
             }
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                const int4 o = red[(f * MF + mf) * 64 + lane];
-                v4i v = acc[mf];
-                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                acc[mf] = (v4i){0, 0, 0, 0};
+            __syncthreads();
+            const bool complete = (info >> 26) & 1;
+            if (owner) {
+                float sn[4] = {0.f, 0.f, 0.f, 0.f};
+                int zn[4] = {0, 0, 0, 0};
                 if (complete) {
-                    const int m = m0 + mf * 16 + ml;
-                    if (m < p.M)
-                        finish4<GROUP, OUT>(p, m, block_now * 64 + 16 * q + 4 * f, v, sn, zn, sx_lds[mf * 16 + ml],
-                                            rs_lds[mf * 16 + ml]);
-                } else {
-                    store_sc1(my_parts + (size_t)(seg_index ? 1 : 0) * (MF * kThreads) + mf * kThreads + tid, v);
+                    const char* sc = reinterpret_cast<const char*>(&sring[aslot_now][0]);
+                    const uint2 sw = *reinterpret_cast<const uint2*>(sc + (16 * q + 4 * f) * 2);
+                    sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
+                    sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
+                    sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
+                    sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
+                    if (!GROUP) {
+                        const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 128 + 16 * q + 4 * f);
+    #pragma unroll
+                        for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
+                    }
+                }
+    #pragma unroll
+                for (int mf = 0; mf < MF; ++mf) {
+                    const int4 o = red[(f * MF + mf) * 64 + lane];
+                    v4i v = acc[mf];
+                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                    acc[mf] = (v4i){0, 0, 0, 0};
+                    if (complete) {
+                        const int m = m0 + mf * 16 + ml;
+                        if (m < p.M)
+                            finish4<GROUP, OUT>(p, m, block_now * 64 + 16 * q + 4 * f, v, sn, zn, sx_lds[mf * 16 + ml],
+                                                rs_lds[mf * 16 + ml]);
+                    } else if (seg_index == 0) {
+                        part0[mf] = v;
+                    } else {
+                        part1[mf] = v;
+                    }
                 }
             }
+            if (!complete) { if (seg_index == 0) has_part0 = true; else has_part1 = true; }
+            close_segment(complete, block_now);
         }
-        if (!complete) { part_block[npart] = block_now; ++npart; }
-        seg_first_g = 0;
-        ++seg_index;
+        if (owner) {
+            if (has_part0) store_sc1_and_wait<MF>(my_parts + tid, kThreads, part0);
+            if (has_part1) store_sc1_and_wait<MF>(my_parts + MF * kThreads + tid, kThreads, part1);
+        }
     }
     wait_vmcnt<0>();   // tail copies still target the rings; partial tiles have reached memory
     if (npart == 0) return;
@@ -818,8 +865,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             const int cf = j >> 4, tf = (j >> 2) & 3, qd = j & 3;
-            store_sc1(mine + (size_t)j * kMmaThreads, (v4i){acc[cf][tf][4 * qd], acc[cf][tf][4 * qd + 1],
-                                                            acc[cf][tf][4 * qd + 2], acc[cf][tf][4 * qd + 3]});
+            store_sc1(mine + (size_t)j * kMmaThreads, (v4i){acc[cf][tf][4 * qd], acc[cf][tf][4 * qd + 1], acc[cf][tf][4 * qd + 2],
+                                                            acc[cf][tf][4 * qd + 3]});
         }
         wait_vmcnt<0>();
         __syncthreads();

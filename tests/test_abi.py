@@ -119,3 +119,52 @@ int main() {
     subprocess.check_call(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "paper_2405_04532_amd", "csrc"),
                            str(src), "-o", str(exe)])
     assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "ok"
+
+
+def test_run_walk_closed_form(tmp_path):
+    """Host logic of the streaming kernel: the closed form that gives any iteration of a workgroup's run
+    (block, first group, units, segment end, whole block) equals stepping through the run unit by unit."""
+    src = tmp_path / "w.cpp"
+    src.write_text(r'''
+#include "qoq_walk.h"
+#include <cstdio>
+#include <cstdlib>
+using namespace qoq;
+int main() {
+    long checked = 0;
+    for (int G = 1; G <= 13; ++G)
+        for (int u0 = 0; u0 < 4 * G + 3; ++u0)
+            for (int U = 1; U <= 5 * G + 2; ++U) {
+                const int u1 = u0 + U;
+                RunShape r = make_run(u0, u1, G);
+                // reference state machine
+                int block = u0 / G, g = u0 - block * G, left = (G - g) < U ? (G - g) : U, rem = U - left, seg_first = g, it = 0;
+                while (left > 0) {
+                    const int n = left < 2 ? left : 2;
+                    if (it >= r.T) { printf("too many iterations G=%d u0=%d U=%d\n", G, u0, U); return 1; }
+                    IterInfo o = run_iteration(r, it);
+                    const bool wrapped = g + n >= G;
+                    const int block_now = block, g_now = g;
+                    g += n; left -= n;
+                    bool seg_end = false;
+                    if (left <= 0) { seg_end = true; if (rem > 0) { block += 1; g = 0; left = G < rem ? G : rem; rem -= left; } }
+                    const bool complete = seg_end && seg_first == 0 && wrapped;
+                    if (o.block != block_now || o.g != g_now || o.n != n || o.seg_end != seg_end || o.complete != complete) {
+                        printf("mismatch G=%d u0=%d U=%d it=%d: got (%d,%d,%d,%d,%d) want (%d,%d,%d,%d,%d)\n", G, u0, U, it, o.block, o.g, o.n,
+                               o.seg_end, o.complete, block_now, g_now, n, seg_end, complete);
+                        return 1;
+                    }
+                    if (seg_end) seg_first = 0;
+                    ++it; ++checked;
+                }
+                if (it != r.T) { printf("T mismatch G=%d u0=%d U=%d: %d vs %d\n", G, u0, U, it, r.T); return 1; }
+            }
+    printf("ok %ld iterations checked\n", checked);
+    return 0;
+}
+''')
+    exe = tmp_path / "w"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "paper_2405_04532_amd", "csrc"),
+                           str(src), "-o", str(exe)])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.startswith("ok"), out.stdout
