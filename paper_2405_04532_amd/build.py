@@ -20,9 +20,25 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def _compile(src, extra):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS + extra
+    cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj, "-save-temps=obj"] + FLAGS + extra
     subprocess.check_call(cmd)
+    _check_device_asm(os.path.join(OBJ, src.replace(".hip", "-hip-amdgcn-amd-amdhsa-gfx950.s")))
     return obj
+
+
+def _check_device_asm(path):
+    """Refuse kernels that read the dispatch packet.  The compiler does that when it moves an indexed per-thread
+    array into LDS (it then needs the workgroup size and all three thread ids); the packet lives in host-visible
+    queue memory, and the scalar load from it was measured to cost every workgroup several microseconds."""
+    if not os.path.exists(path):
+        return
+    kernel = None
+    for line in open(path):
+        t = line.strip()
+        if t.startswith(".amdhsa_kernel "):
+            kernel = t.split()[1]
+        elif t == ".amdhsa_user_sgpr_dispatch_ptr 1":
+            raise RuntimeError(f"{kernel} reads the dispatch packet: an indexed private array was moved to LDS")
 
 
 def build(extra_flags=(), verbose=False):

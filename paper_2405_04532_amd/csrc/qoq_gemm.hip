@@ -145,10 +145,38 @@ __device__ __forceinline__ void store_sc1(int4* ptr, v4i v)
 {
     asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" :: "v"(ptr), "v"(v) : "memory");
 }
+// Compiler-visible write-through store / cache-bypassing load (two relaxed device-scope 8-byte atomics each): the
+// compiler tracks their registers and waits itself.  For code with no copy queue to preserve, and wherever
+// control flow lies between a load and its use (the compiler may copy a register it believes already loaded).
+__device__ __forceinline__ void store_through(int4* ptr, int a, int b, int c, int d)
+{
+    unsigned long long* q = reinterpret_cast<unsigned long long*>(ptr);
+    __hip_atomic_store(q, (unsigned long long)(uint32_t)a | ((unsigned long long)(uint32_t)b << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, (unsigned long long)(uint32_t)c | ((unsigned long long)(uint32_t)d << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ v4i load_through(const int4* ptr)
+{
+    unsigned long long* q = const_cast<unsigned long long*>(reinterpret_cast<const unsigned long long*>(ptr));
+    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return (v4i){(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
+}
 template <int CNT>
 __device__ __forceinline__ void store_sc1_and_wait(int4* ptr, int stride, const v4i (&v)[CNT])
 {
-    static_assert(CNT == 1 || CNT == 2 || CNT == 4, "fragments per lane");
+    static_assert(CNT == 1 || CNT == 2 || CNT == 4 || CNT == 8, "fragments per lane (of one or two tiles)");
+    if constexpr (CNT == 8) {
+        asm volatile("global_store_dwordx4 %0, %8, off sc1\n\tglobal_store_dwordx4 %1, %9, off sc1\n\t"
+                     "global_store_dwordx4 %2, %10, off sc1\n\tglobal_store_dwordx4 %3, %11, off sc1\n\t"
+                     "global_store_dwordx4 %4, %12, off sc1\n\tglobal_store_dwordx4 %5, %13, off sc1\n\t"
+                     "global_store_dwordx4 %6, %14, off sc1\n\tglobal_store_dwordx4 %7, %15, off sc1\n\ts_waitcnt vmcnt(0)"
+                     :: "v"(ptr), "v"(ptr + stride), "v"(ptr + 2 * stride), "v"(ptr + 3 * stride), "v"(ptr + 4 * stride),
+                     "v"(ptr + 5 * stride), "v"(ptr + 6 * stride), "v"(ptr + 7 * stride), "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]),
+                     "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]) : "memory");
+        return;
+    }
     if constexpr (CNT == 1)
         asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" :: "v"(ptr), "v"(v[0]) : "memory");
     else if constexpr (CNT == 2)
@@ -205,6 +233,128 @@ __device__ __forceinline__ void finish4(const GemmDev& p, int m, int n0, v4i v, 
     }
 }
 
+// Blocks shared with other workgroups: this workgroup has written its partial tiles (at most two) to the
+// workspace and waited for them.  It bumps each block's counter; whoever arrives last at a block adds every
+// contributor's partial tile and runs the epilogue.  Called by all THREADS threads of the workgroup.
+template <int MF, bool GROUP, int OUT, int THREADS>
+__device__ __forceinline__ void finish_shared_blocks(const GemmDev& p, int npart, int part_block0, int part_block1, int m0, int* s_flag)
+{
+    const int G = p.G, blocks = p.N / 64;
+    // ---- blocks shared with other workgroups ---------------------------------------------------
+    // Every step here is a round trip to memory (about a microsecond), so whatever can be in flight together is:
+    // both counters, then every partial-tile load and every epilogue constant of both blocks.
+    __syncthreads();
+    if (threadIdx.x < npart) {
+        const int b = threadIdx.x == 0 ? part_block0 : part_block1;
+        const int w_first = (b * G) / p.upw, w_last = (b * G + G - 1) / p.upw;
+        int* ctr = p.counters + blockIdx.y * blocks + b;
+        const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = old == w_last - w_first;
+        s_flag[threadIdx.x] = last;
+        if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    // last to arrive at a block: add every contributor's partial tile, element by element, and finish it
+    constexpr int kEl = MF * kThreads;                                     // int4 elements of a partial tile
+    constexpr int kRounds = (kEl + THREADS - 1) / THREADS;   // elements per thread
+    constexpr int kBatch = MF == 4 ? 5 : 6;                                // contributors loaded at once
+    v4i t[2 * kRounds * kBatch];
+    uint2 c_s[2 * kRounds];
+    uint32_t c_z[2 * kRounds];
+    float c_sx[2 * kRounds];
+    int c_rs[2 * kRounds];
+#pragma unroll
+    for (int x = 0; x < 2 * kRounds * kBatch; ++x) t[x] = (v4i){0, 0, 0, 0};
+    bool mine[2];
+    int blk[2], wf[2], wl[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        mine[k] = k < npart && s_flag[k];                                  // everything here is workgroup-uniform
+        blk[k] = __builtin_amdgcn_readfirstlane(k == 0 ? part_block0 : part_block1);
+        wf[k] = __builtin_amdgcn_readfirstlane((blk[k] * G) / p.upw);
+        wl[k] = __builtin_amdgcn_readfirstlane((blk[k] * G + G - 1) / p.upw);
+    }
+    // a contributor's partial tile of block blk[k] is its first one iff its run starts inside that block
+    auto first_partial = [&](int ww, int k) __attribute__((always_inline)) {
+        const int us = ww * p.upw;
+        return us >= blk[k] * G && us < (blk[k] + 1) * G;
+    };
+    auto element = [&](int r, int& el, int& m, int& n_rel) __attribute__((always_inline)) {
+        el = min((int)threadIdx.x + r * THREADS, kEl - 1);          // clamped: loads stay in bounds
+        const int mf = el / kThreads, ft = (el % kThreads) >> 6, ln = el & 63;
+        m = m0 + mf * 16 + (ln & 15);
+        n_rel = 16 * (ln >> 4) + 4 * ft;
+    };
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (!mine[k]) continue;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            int el, m, n_rel;
+            element(r, el, m, n_rel);
+            const int n0 = blk[k] * 64 + n_rel, mc = min(m, p.M - 1);
+            c_s[k * kRounds + r] = OUT == OUT_FP16 ? *reinterpret_cast<const uint2*>(p.scales + n0) : make_uint2(0, 0);
+            c_z[k * kRounds + r] = GROUP ? 0u : *reinterpret_cast<const uint32_t*>(p.zeros + n0);
+            c_sx[k * kRounds + r] = OUT == OUT_FP16 ? __half2float(p.sx[mc]) : 0.f;
+            c_rs[k * kRounds + r] = GROUP ? 0 : p.rowsum[mc];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (!mine[k]) continue;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            int el, m, n_rel;
+            element(r, el, m, n_rel);
+            if ((int)threadIdx.x + r * THREADS >= kEl) continue;     // whole waves: no element in this round
+#pragma unroll
+            for (int x = 0; x < kBatch; ++x) {
+                const int ww = wf[k] + x;
+                if (ww > wl[k]) break;                                      // these loads go to memory: none is issued twice
+                const int which = first_partial(ww, k) ? 0 : 1;
+                t[(k * kRounds + r) * kBatch + x] =
+                    load_through(p.parts + ((size_t)(blockIdx.y * gridDim.x + ww) * 2 + which) * kEl + el);
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (!mine[k]) continue;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            int el, m, n_rel;
+            element(r, el, m, n_rel);
+            v4i sum = (v4i){0, 0, 0, 0};
+#pragma unroll
+            for (int x = 0; x < kBatch; ++x)
+                if (wf[k] + x <= wl[k]) sum += t[(k * kRounds + r) * kBatch + x];
+            for (int w = wf[k] + kBatch; w <= wl[k]; w += 4) {              // more contributors than one batch holds
+                v4i u[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int ww = w + x;
+                    u[x] = (v4i){0, 0, 0, 0};
+                    if (ww > wl[k]) continue;
+                    const int which = first_partial(ww, k) ? 0 : 1;
+                    u[x] = load_through(p.parts + ((size_t)(blockIdx.y * gridDim.x + ww) * 2 + which) * kEl + el);
+                }
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if (w + x <= wl[k]) sum += u[x];
+            }
+            if ((int)threadIdx.x + r * THREADS >= kEl || m >= p.M) continue;
+            const uint2 sw = c_s[k * kRounds + r];
+            const float sn[4] = {__half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu))),
+                                 __half2float(__ushort_as_half((unsigned short)(sw.x >> 16))),
+                                 __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu))),
+                                 __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)))};
+            const uint32_t zw = c_z[k * kRounds + r];
+            const int zn[4] = {(int)(zw & 0xFFu), (int)((zw >> 8) & 0xFFu), (int)((zw >> 16) & 0xFFu), (int)(zw >> 24)};
+            finish4<GROUP, OUT>(p, m, blk[k] * 64 + n_rel, sum, sn, zn, c_sx[k * kRounds + r], c_rs[k * kRounds + r]);
+        }
+    }
+}
+
 template <int MF, bool GROUP, int OUT>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void stream_kernel(GemmDev p)
 {
@@ -246,7 +396,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     const int nf_total = p.N / 16;
 
     // The run's iteration structure in closed form (qoq_walk.h), all wave-uniform.
-    RunShape run = make_run(u0, u1, G);
+    RunShape run = make_run(u0, u1, G, 2);
     run.b0 = __builtin_amdgcn_readfirstlane(run.b0); run.g0 = __builtin_amdgcn_readfirstlane(run.g0);
     run.full = __builtin_amdgcn_readfirstlane(run.full); run.last_len = __builtin_amdgcn_readfirstlane(run.last_len);
     const int T = __builtin_amdgcn_readfirstlane(run.T);
@@ -365,7 +515,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     const int tid = f * 64 + lane;                          // owner lanes: index inside a partial tile
     const bool owner = !producer && e == 0;
     int4* my_parts = p.parts + (size_t)(blockIdx.y * gridDim.x + wg) * 2 * (MF * kThreads);
-    int npart = 0, part_block[2] = {0, 0};
+    int npart = 0, part_block0 = 0, part_block1 = 0;   // (scalars: an indexed array would be moved to LDS)
     // Partial tiles of the run (at most two: a first segment that starts inside a block, a last one that ends
     // inside a block) stay in registers and are written out after the loop, so that no store sits among the copies.
     v4i part0[MF], part1[MF];
@@ -376,7 +526,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 
     // bookkeeping every wave keeps identically: segments of the run that end inside a shared block
     auto close_segment = [&](bool complete, int block_now) __attribute__((always_inline)) {
-        if (!complete) { part_block[npart] = block_now; ++npart; }
+        if (!complete) { if (npart == 0) part_block0 = block_now; else part_block1 = block_now; ++npart; }
         ++seg_index;
     };
 
@@ -470,62 +620,219 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
             close_segment(complete, block_now);
         }
         if (owner) {
-            if (has_part0) store_sc1_and_wait<MF>(my_parts + tid, kThreads, part0);
-            if (has_part1) store_sc1_and_wait<MF>(my_parts + MF * kThreads + tid, kThreads, part1);
+            if (has_part0 && has_part1) {                  // one wait for both
+                v4i both[2 * MF];
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) { both[mf] = part0[mf]; both[MF + mf] = part1[mf]; }
+                store_sc1_and_wait<2 * MF>(my_parts + tid, kThreads, both);
+            } else if (has_part0) {
+                store_sc1_and_wait<MF>(my_parts + tid, kThreads, part0);
+            } else if (has_part1) {
+                store_sc1_and_wait<MF>(my_parts + MF * kThreads + tid, kThreads, part1);
+            }
         }
     }
     wait_vmcnt<0>();   // tail copies still target the rings; partial tiles have reached memory
     if (npart == 0) return;
 
-    // ---- blocks shared with other workgroups ---------------------------------------------------
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int k = 0; k < npart; ++k) {
-            const int b = part_block[k];
-            const int w_first = (b * G) / p.upw, w_last = (b * G + G - 1) / p.upw;
-            int* ctr = p.counters + blockIdx.y * blocks + b;
-            const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_flag[k] = old == w_last - w_first;
-            if (s_flag[k]) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    __syncthreads();
-    for (int k = 0; k < npart; ++k) {
-        if (!s_flag[k]) continue;
-        // last to arrive: add every contributor's partial tile, element by element, and finish it
-        const int b = part_block[k];
-        const int w_first = (b * G) / p.upw, w_last = (b * G + G - 1) / p.upw;
-        for (int el = threadIdx.x; el < MF * kThreads; el += kStreamThreads) {
-            v4i sum = (v4i){0, 0, 0, 0};
-            for (int w = w_first; w <= w_last; w += 4) {
-                v4i t[4];
+    finish_shared_blocks<MF, GROUP, OUT, kStreamThreads>(p, npart, part_block0, part_block1, m0, s_flag);
+}
+
+// ------------------------------------------------------------------------------------------
+// "rstream" kernel: the same work partition as the kernel above, but no staging through LDS at all.
+// Wave w of eight takes the w-th unit of each iteration (eight consecutive groups of one block) and, for that
+// group, ALL four 16-channel fragments of the block: the 4 x 1 KiB of packed weights and the 16*MF x 128 bytes
+// of activations go straight from memory into its registers (each lane loads exactly the 16-byte words its
+// MFMA operands consist of), one iteration ahead.  Nothing is shared between waves, so the loop has no
+// barriers, and an activation word is fetched once per four units instead of being read from LDS by every
+// wave that consumes it -- LDS bandwidth, not HBM, bounded the staged kernel.  The eight partial sums of a
+// block meet once per segment of the run, through LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int kRsThreads = 512;
+constexpr int kRsWaves = 8;
+
+template <int MF, bool GROUP, int OUT>
+__global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
+{
+    constexpr int kEl = MF * kThreads;                              // int4 elements of a 64-channel tile: (mf * 4 + f) * 64 + lane
+    constexpr int kRounds = (kEl + kRsThreads - 1) / kRsThreads;    // elements per thread after the reduction
+    __shared__ int4 red[kRsWaves][kEl];
+    __shared__ int s_flag[2];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wg = blockIdx.x;
+    const int m0 = blockIdx.y * (16 * MF);
+    const int G = p.G;
+    const int blocks = p.N / 64;
+    const int total = blocks * G;
+    const int u0 = min(total, wg * p.upw), u1 = min(total, u0 + p.upw);
+    if (u0 >= u1) return;                                  // whole workgroup: nothing to do
+    const int q = lane >> 4, ml = lane & 15;
+    const int nf_total = p.N / 16;
+
+    RunShape run = make_run(u0, u1, G, kRsWaves);
+    const int T = __builtin_amdgcn_readfirstlane(run.T);
+    auto iteration = [&](int it) __attribute__((always_inline)) {
+        IterInfo o = run_iteration(run, it);               // wave-uniform
+        o.block = __builtin_amdgcn_readfirstlane(o.block);
+        o.g = __builtin_amdgcn_readfirstlane(o.g);
+        o.n = __builtin_amdgcn_readfirstlane(o.n);
+        o.seg_end = __builtin_amdgcn_readfirstlane((int)o.seg_end) != 0;
+        o.complete = __builtin_amdgcn_readfirstlane((int)o.complete) != 0;
+        return o;
+    };
+
+    // lane (ml, q) holds, of every operand, row ml and the 16-byte k-chunk q
+    uint32_t a_off[MF];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int ww = min(w + x, w_last);
-                    const int which = (ww * p.upw) / G == b ? 0 : 1;   // first or second partial of that workgroup
-                    load_sc1_nowait(t[x], p.parts + ((size_t)(blockIdx.y * gridDim.x + ww) * 2 + which) * (MF * kThreads) + el);
+    for (int mf = 0; mf < MF; ++mf)                        // rows past M repeat the last one; never stored
+        a_off[mf] = (uint32_t)min(m0 + mf * 16 + ml, p.M - 1) * (uint32_t)p.K + (uint32_t)(q * 16);
+    const char* abase = reinterpret_cast<const char*>(p.qx);
+
+    struct Item { uint4 w[kNFrag]; uint32_t mt[kNFrag]; v4i a[MF][2]; };
+    auto load_item = [&](Item& item, const IterInfo& o) __attribute__((always_inline)) {
+        if (wave >= o.n) return;                           // no unit for this wave in that iteration
+        const int g = o.g + wave;
+        const int blk = o.block;
+#pragma unroll
+        for (int f = 0; f < kNFrag; ++f) {
+            const int nf = blk * kNFrag + f;
+            item.w[f] = p.codes[(size_t)((nf * G + g) << 6) + lane];
+            if (GROUP) item.mt[f] = p.meta[((size_t)g * nf_total + nf) * 16 + ml];
+        }
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                item.a[mf][ks] = *reinterpret_cast<const v4i*>(abase + (a_off[mf] + (uint32_t)(g * kGroup + ks * 64)));
+    };
+
+    v4i acc[kNFrag][MF];
+#pragma unroll
+    for (int f = 0; f < kNFrag; ++f)
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf) acc[f][mf] = (v4i){0, 0, 0, 0};
+    auto compute = [&](const Item& item) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int f = 0; f < kNFrag; ++f) {
+                uint32_t S = 0, B = 0;
+                if (GROUP) {
+                    S = __builtin_amdgcn_perm(item.mt[f], item.mt[f], 0x0c000c00u);  // s1 in both 16-bit lanes
+                    B = __builtin_amdgcn_perm(item.mt[f], item.mt[f], 0x01010101u);  // bias in all four bytes
                 }
-                wait_loads(t[0], t[1], t[2], t[3]);
+                const v4i w_op = dequant<GROUP>(ks ? item.w[f].z : item.w[f].x, ks ? item.w[f].w : item.w[f].y, S, B);
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    if (w + x <= w_last) sum += t[x];
+                for (int mf = 0; mf < MF; ++mf)
+                    acc[f][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w_op, item.a[mf][ks], acc[f][mf], 0, 0, 0);
             }
-            const int mf = el / kThreads, ft = (el % kThreads) >> 6, ln = el & 63;
-            const int m = m0 + mf * 16 + (ln & 15);
-            const int n0 = b * 64 + 16 * (ln >> 4) + 4 * ft;
-            if (m >= p.M) continue;
-            float sn[4];
-            int zn[4] = {0, 0, 0, 0};
+    };
+
+    // Partial tiles of the run (at most two: a first segment that starts inside a block, a last one that ends
+    // inside a block) stay in registers, spread over the threads, until the loop is over.
+    v4i part0[kRounds], part1[kRounds];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) sn[j] = OUT == OUT_FP16 ? __half2float(p.scales[n0 + j]) : 0.f;
-            if (!GROUP) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) zn[j] = p.zeros[n0 + j];
-            }
-            finish4<GROUP, OUT>(p, m, n0, sum, sn, zn, OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f,
-                                GROUP ? 0 : p.rowsum[m]);
+    for (int r = 0; r < kRounds; ++r) part0[r] = part1[r] = (v4i){0, 0, 0, 0};
+    bool has_part0 = false, has_part1 = false;
+    int npart = 0, part_block0 = 0, part_block1 = 0, seg_index = 0;   // (scalars: an indexed array would be moved to LDS)
+    int4* my_parts = p.parts + (size_t)(blockIdx.y * gridDim.x + wg) * 2 * kEl;
+
+    // One item ahead: the loads of the next iteration go out, then the current one is computed.  (Deeper
+    // register prefetch with a fixed number of loads per iteration was measured and is no faster: the loop is not
+    // bound by the bytes a wave has in flight.)
+    IterInfo cur_i = iteration(0);
+    Item cur;
+    load_item(cur, cur_i);
+    for (int it = 0; it < T; ++it) {
+        IterInfo nxt_i = cur_i;
+        Item nxt;                                          // (left unset when there is no next iteration: never used then)
+        if (it + 1 < T) {
+            nxt_i = iteration(it + 1);
+            load_item(nxt, nxt_i);
         }
+        if (wave < cur_i.n) compute(cur);
+        if (cur_i.seg_end) {
+            // ---- end of this run's share of a block: the eight waves' sums meet in LDS ----------------
+            const bool complete = cur_i.complete;
+            const int block_now = cur_i.block;
+            uint2 c_s[kRounds];
+            uint32_t c_z[kRounds];
+            float c_sx[kRounds];
+            int c_rs[kRounds];
+            if (complete) {                                // epilogue constants: in flight across the barrier
+#pragma unroll
+                for (int r = 0; r < kRounds; ++r) {
+                    const int el = min((int)threadIdx.x + r * kRsThreads, kEl - 1);
+                    const int mf = el >> 8, f = (el >> 6) & 3, ln = el & 63;
+                    const int m = min(m0 + mf * 16 + (ln & 15), p.M - 1);
+                    const int n0 = block_now * 64 + 16 * (ln >> 4) + 4 * f;
+                    c_s[r] = OUT == OUT_FP16 ? *reinterpret_cast<const uint2*>(p.scales + n0) : make_uint2(0, 0);
+                    c_z[r] = GROUP ? 0u : *reinterpret_cast<const uint32_t*>(p.zeros + n0);
+                    c_sx[r] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
+                    c_rs[r] = GROUP ? 0 : p.rowsum[m];
+                }
+            }
+#pragma unroll
+            for (int f = 0; f < kNFrag; ++f)
+#pragma unroll
+                for (int mf = 0; mf < MF; ++mf) {
+                    red[wave][(mf * kNFrag + f) * 64 + lane] = make_int4(acc[f][mf].x, acc[f][mf].y, acc[f][mf].z, acc[f][mf].w);
+                    acc[f][mf] = (v4i){0, 0, 0, 0};
+                }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r) {
+                const int el = (int)threadIdx.x + r * kRsThreads;
+                if (el >= kEl) continue;
+                v4i sum = (v4i){0, 0, 0, 0};
+#pragma unroll
+                for (int w = 0; w < kRsWaves; ++w) {
+                    const int4 o = red[w][el];
+                    sum += (v4i){o.x, o.y, o.z, o.w};
+                }
+                if (complete) {
+                    const int mf = el >> 8, f = (el >> 6) & 3, ln = el & 63;
+                    const int m = m0 + mf * 16 + (ln & 15);
+                    if (m < p.M) {
+                        const float sn[4] = {__half2float(__ushort_as_half((unsigned short)(c_s[r].x & 0xFFFFu))),
+                                             __half2float(__ushort_as_half((unsigned short)(c_s[r].x >> 16))),
+                                             __half2float(__ushort_as_half((unsigned short)(c_s[r].y & 0xFFFFu))),
+                                             __half2float(__ushort_as_half((unsigned short)(c_s[r].y >> 16)))};
+                        const int zn[4] = {(int)(c_z[r] & 0xFFu), (int)((c_z[r] >> 8) & 0xFFu), (int)((c_z[r] >> 16) & 0xFFu),
+                                           (int)(c_z[r] >> 24)};
+                        finish4<GROUP, OUT>(p, m, block_now * 64 + 16 * (ln >> 4) + 4 * f, sum, sn, zn, c_sx[r], c_rs[r]);
+                    }
+                } else if (seg_index == 0) {
+                    part0[r] = sum;
+                } else {
+                    part1[r] = sum;
+                }
+            }
+            if (!complete) {
+                if (seg_index == 0) has_part0 = true; else has_part1 = true;
+                if (npart == 0) part_block0 = block_now; else part_block1 = block_now;
+                ++npart;
+            }
+            ++seg_index;
+            __syncthreads();                               // `red` is free again
+        }
+        cur = nxt;
+        cur_i = nxt_i;
     }
+
+    // partial tiles -> workspace (write-through), then the hand-over
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int el = (int)threadIdx.x + r * kRsThreads;
+        if (el >= kEl) continue;
+        if (has_part0) store_through(my_parts + el, part0[r].x, part0[r].y, part0[r].z, part0[r].w);
+        if (has_part1) store_through(my_parts + kEl + el, part1[r].x, part1[r].y, part1[r].z, part1[r].w);
+    }
+    wait_vmcnt<0>();
+    if (npart == 0) return;
+    finish_shared_blocks<MF, GROUP, OUT, kRsThreads>(p, npart, part_block0, part_block1, m0, s_flag);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -968,8 +1275,15 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 template <int MF, bool GROUP>
 void launch_stream(const GemmDev& p, bool fp16, dim3 grid, hipStream_t s)
 {
-    if (fp16) stream_kernel<MF, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
-    else stream_kernel<MF, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+    // 64-token tiles: the LDS-staged kernel; smaller tiles: the register-streaming kernel (measured faster there:
+    // its activation traffic shrinks with the tile while the staged kernel's per-iteration barriers do not)
+    if constexpr (MF == 4) {
+        if (fp16) stream_kernel<MF, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else stream_kernel<MF, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+    } else {
+        if (fp16) rstream_kernel<MF, GROUP, OUT_FP16><<<grid, kRsThreads, 0, s>>>(p);
+        else rstream_kernel<MF, GROUP, OUT_I32><<<grid, kRsThreads, 0, s>>>(p);
+    }
 }
 
 template <bool GROUP, int CF, int WM>

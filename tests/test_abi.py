@@ -132,15 +132,16 @@ def test_run_walk_closed_form(tmp_path):
 using namespace qoq;
 int main() {
     long checked = 0;
+    for (int R = 1; R <= 8; R += (R == 2 ? 6 : 1))
     for (int G = 1; G <= 13; ++G)
         for (int u0 = 0; u0 < 4 * G + 3; ++u0)
             for (int U = 1; U <= 5 * G + 2; ++U) {
                 const int u1 = u0 + U;
-                RunShape r = make_run(u0, u1, G);
+                RunShape r = make_run(u0, u1, G, R);
                 // reference state machine
                 int block = u0 / G, g = u0 - block * G, left = (G - g) < U ? (G - g) : U, rem = U - left, seg_first = g, it = 0;
                 while (left > 0) {
-                    const int n = left < 2 ? left : 2;
+                    const int n = left < R ? left : R;
                     if (it >= r.T) { printf("too many iterations G=%d u0=%d U=%d\n", G, u0, U); return 1; }
                     IterInfo o = run_iteration(r, it);
                     const bool wrapped = g + n >= G;
