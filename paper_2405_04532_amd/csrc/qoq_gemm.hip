@@ -9,8 +9,8 @@
 //     all four bytes at once (no carries because the protective range keeps every byte in [1, 255]), and
 //     one XOR turns the +128 bias into two's complement.  The per-channel variant feeds the codes unchanged
 //     and folds the zero point into the epilogue through the token's row sum (Eq. 6).
-//   * Two kernels.
-//     "stream" (M <= 64 per tile, memory bound, v_mfma_i32_16x16x64_i8): a multi-stage pipeline of direct
+//   * Three kernels.
+//     "stream" (64-token tiles, memory bound, v_mfma_i32_16x16x64_i8): a multi-stage pipeline of direct
 //     global->LDS copies (the asynchronous-copy software pipeline of Section 5.2.4 in its gfx950 form) over
 //     a balanced, stream-k style partition of the work.
 //       - Work unit = one quantization group of one 64-channel block (4 KiB of packed weights).  The
@@ -18,9 +18,9 @@
 //         the layer shape; a run may start and end in the middle of a block.
 //       - HBM latency under load is about 1.5-2.5 us here, so some 50-100 KiB per CU must be in flight.
 //         Each of eight consumer waves (fragment f, group parity e) copies the units it will itself consume
-//         into a private 10-12 deep LDS ring: no barrier guards the weights.  Activations come from L2 and
+//         into a private 10 deep LDS ring: no barrier guards the weights.  Activations come from L2 and
 //         need far less lead, but a wave's outstanding copies retire in order, so a wave issuing both would
-//         stall its deep weight prefetch on every activation wait: two producer waves copy the activation
+//         stall its deep weight prefetch on every activation wait: four producer waves copy the activation
 //         slabs, level-2 metadata and channel scales a couple of iterations ahead; one barrier per iteration
 //         (two groups) publishes them.  Copies are issued from inline assembly and waited for with explicit
 //         s_waitcnt vmcnt(n): the compiler's own bookkeeping would wait for ALL outstanding copies before
@@ -29,6 +29,8 @@
 //         in the workspace: partial INT32 tiles are written through to memory, a per-block counter elects
 //         the last workgroup to arrive, which adds all partials (integer sums are exact and order
 //         independent) and runs the epilogue.
+//     "rstream" (16- and 32-token tiles): the same partition with nothing staged in LDS; every wave loads the
+//     operand words of its own units straight into registers (see the comment in front of it).
 //     "mma" (larger M, compute bound, v_mfma_i32_32x32x32_i8): large output tiles, one wave per SIMD, a
 //     hand software-pipelined main loop; see the comment in front of it.
 //   * Epilogue (Section 5.2.2): FP32 acc * (sx[m] * s[n]), one rounding to FP16.
@@ -102,7 +104,7 @@ __device__ inline v4i as_v4i(uint4 t) { return (v4i){(int)t.x, (int)t.y, (int)t.
 // relaxed device-scope atomic, and the last arriver reads the partials only after that atomic has returned.
 
 // ------------------------------------------------------------------------------------------
-// "stream" kernel: 16*MF <= 64 tokens; nine waves; grid = (workgroups, m-tiles).
+// "stream" kernel: 16*MF <= 64 tokens; twelve waves; grid = (workgroups, m-tiles).
 // Consumer wave c = 2*f + e handles fragment f of the current 64-channel block and, in each
 // iteration, the group of parity e of a pair of consecutive groups.
 // ------------------------------------------------------------------------------------------
