@@ -162,3 +162,27 @@ def layer_activations(family, layer, M, base_seed, device="cpu"):
     shapes = {"llama2_7b": LLAMA2_7B, "llama3_70b": LLAMA3_70B, "llama3_8b": LLAMA3_8B}[family]
     K, _ = shapes[layer]
     return make_activations(M, K, _layer_seed(base_seed, layer) + 7919 * M, device)
+
+
+# ---------------------------------------------------------------------------------------
+# Decode attention over a 4-bit KV cache: synthetic keys, values and queries.
+# ---------------------------------------------------------------------------------------
+KV4_DECODE = {"llama2_7b": dict(H=32, Hkv=32, D=128), "llama3_8b": dict(H=32, Hkv=8, D=128),
+              "llama3_70b": dict(H=64, Hkv=8, D=128)}
+
+
+def make_kv(B, Hkv, S, D, seed, device="cpu", key_outliers=2, gain=8.0):
+    """FP16 keys and values [B, Hkv, S, D] ~ N(0, 1).  In every KV head `key_outliers` seeded channels of
+    the keys are scaled by `gain` for all tokens (keys have a few fixed large channels, values do not)."""
+    k = _rows_normal(seed, 3, B * Hkv * S, D, device).view(B, Hkv, S, D)
+    v = _rows_normal(seed, 4, B * Hkv * S, D, device).view(B, Hkv, S, D)
+    for h in range(Hkv):
+        cols = pick_channels(seed, 200 + h, D, key_outliers, device)
+        if key_outliers > 0:
+            k[:, h, :, cols] = k[:, h, :, cols] * gain
+    return k.to(torch.float16), v.to(torch.float16)
+
+
+def make_queries(B, H, D, seed, device="cpu"):
+    """FP16 queries [B, H, D] ~ N(0, 1), one new token per sequence."""
+    return _rows_normal(seed, 5, B * H, D, device).view(B, H, D).to(torch.float16)
