@@ -158,6 +158,38 @@ int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N
                     void* out_fp16, int8_t* qx, void* sx_fp16, int32_t* rowsum,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- KV4 cache and decode attention (Sections 5.1 "KV Cache Management" and 5.3; Eq. 1-2; the attention
+ * equation of Section 3.1) ----------------------------------------------------------------------------
+ * The cache holds keys and values as 4-bit codes with one FP16 scale and one FP16 zero point per token and KV
+ * head (per-head, dynamic, asymmetric: Eq. 1 with q_min = 0, q_max = 15 on the range of that head's D values,
+ * widened to contain 0; s = fp16((max - min) / 15), 1 for an all-zero vector; z = floor(-min / s + 1/2);
+ * code = clamp(floor(x / s + z + 1/2), 0, 15); dequantized value (code - z) * s, Eq. 2).  It is an opaque device
+ * buffer of qoq_kv4_cache_bytes(B, Hkv, S_max, D) bytes, owned by the caller, organised in pages of 64 tokens
+ * per (sequence, KV head) with the scales and zeros stored behind the codes inside each page.  D must be 128.
+ *
+ * qoq_kv4_append: quantizes T new tokens per sequence and writes them at token positions
+ * positions[b] .. positions[b] + T - 1 of sequence b (tokens that would fall outside [0, S_max) are dropped).
+ *   k_fp16, v_fp16   [B, T, Hkv, D] FP16, device, read only
+ *   positions        [B] INT32, device
+ * qoq_kv4_attention_decode: one new query token per sequence,
+ *   out[b, h, :] = softmax_t( q[b, h, :] . K^[b, floor(h / r), t, :] / sqrt(D) ) V^[b, floor(h / r), t, :],
+ *   t < seq_lens[b], r = H / Hkv in {1, 2, 4, 8}; K^, V^ the dequantized cache.  Products take FP16 operands, sums
+ *   and the softmax are FP32, one rounding to FP16 at the end.  seq_lens[b] is clamped to [0, S_max]; an empty
+ *   sequence gives a zero row.
+ *   q_fp16 [B, H, D] FP16; seq_lens [B] INT32 device; out_fp16 [B, H, D] FP16 (written)
+ * qoq_kv4_unpack (tests): codes as one byte each [B, Hkv, S_max, D] and the FP16 scales / zeros [B, Hkv, S_max]
+ * of keys and values; positions never written hold whatever the buffer held.
+ * Errors: QOQ_ERR_SHAPE (D != 128, negative sizes, H not r * Hkv), QOQ_ERR_NULL, QOQ_ERR_ALIGN (16 bytes),
+ * QOQ_ERR_ARCH, QOQ_ERR_HIP.  Nothing is allocated; all work is enqueued on `stream`. */
+size_t qoq_kv4_cache_bytes(int64_t B, int64_t Hkv, int64_t S_max, int64_t D);
+int qoq_kv4_append(const void* k_fp16, const void* v_fp16, const int32_t* positions, int64_t B, int64_t T,
+                   int64_t Hkv, int64_t D, int64_t S_max, void* cache, void* stream);
+int qoq_kv4_attention_decode(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
+                             int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* stream);
+int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int64_t D, uint8_t* k_codes,
+                   void* k_scale_fp16, void* k_zero_fp16, uint8_t* v_codes, void* v_scale_fp16, void* v_zero_fp16,
+                   void* stream);
+
 /* Test/tuning hook: force the GEMM launch configuration instead of the built-in heuristic.
  * tile_m: 0 = auto; 16, 32, 64 = streaming kernel with that many tokens per tile; 128, 129, 130 =
  * compute-bound kernel with tiles of 256 x 256, 128 x 256, 256 x 128 (tokens x channels).

@@ -51,6 +51,15 @@ _SIGNATURES = {
                                        ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_set_gemm_config": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+    "qoq_kv4_cache_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]),
+    "qoq_kv4_append": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
+    "qoq_kv4_attention_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                                ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                ctypes.c_void_p, ctypes.c_void_p]),
+    "qoq_kv4_unpack": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_void_p]),
 }
 
 EXPORTS = tuple(_SIGNATURES)
@@ -263,3 +272,51 @@ def silu_mul_quant(gate_up, want_y=True, want_rowsum=True, want_tx=False):
     _check(lib().qoq_silu_mul_quant(_ptr(gate_up), M, K, _ptr(y), _ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(tx),
                                     _stream(gate_up.device)))
     return y, qx, sx, rowsum, tx
+
+
+# ---------------------------------------------------------------------------------------
+# KV4 cache and decode attention
+# ---------------------------------------------------------------------------------------
+def kv4_cache_bytes(B, Hkv, S_max, D=128):
+    return int(lib().qoq_kv4_cache_bytes(B, Hkv, S_max, D))
+
+
+def kv4_new_cache(B, Hkv, S_max, device, D=128):
+    """An empty (zero-filled) cache buffer for B sequences of up to S_max tokens."""
+    n = kv4_cache_bytes(B, Hkv, S_max, D)
+    if n == 0 and B > 0:
+        raise QoqError(2, "unsupported KV4 cache shape")
+    return torch.zeros(max(n, 16), dtype=torch.uint8, device=device)
+
+
+def kv4_append(cache, k, v, positions, S_max):
+    """Quantize k, v [B, T, Hkv, D] FP16 and write them at token positions positions[b] .. + T - 1."""
+    _dev(k, torch.float16, "k")
+    _dev(v, torch.float16, "v")
+    _dev(positions, torch.int32, "positions")
+    B, T, Hkv, D = k.shape
+    _check(lib().qoq_kv4_append(_ptr(k), _ptr(v), _ptr(positions), B, T, Hkv, D, S_max, _ptr(cache), _stream(k.device)))
+
+
+def kv4_attention_decode(q, cache, seq_lens, Hkv, S_max, out=None):
+    """out[b, h] = softmax(q[b, h] . K^ / sqrt(D)) V^ over the first seq_lens[b] tokens of the cache."""
+    _dev(q, torch.float16, "q")
+    _dev(seq_lens, torch.int32, "seq_lens")
+    B, H, D = q.shape
+    if out is None:
+        out = torch.empty((B, H, D), dtype=torch.float16, device=q.device)
+    _check(lib().qoq_kv4_attention_decode(_ptr(q), _ptr(cache), _ptr(seq_lens), B, H, Hkv, D, S_max, _ptr(out),
+                                          _stream(q.device)))
+    return out
+
+
+def kv4_unpack(cache, B, Hkv, S_max, D=128):
+    """(k_codes, k_s, k_z, v_codes, v_s, v_z): one byte per code, FP16 scales and zeros (tests)."""
+    dev = cache.device
+    kc = torch.empty((B, Hkv, S_max, D), dtype=torch.uint8, device=dev)
+    vc = torch.empty_like(kc)
+    ks = torch.empty((B, Hkv, S_max), dtype=torch.float16, device=dev)
+    kz, vs, vz = torch.empty_like(ks), torch.empty_like(ks), torch.empty_like(ks)
+    _check(lib().qoq_kv4_unpack(_ptr(cache), B, Hkv, S_max, D, _ptr(kc), _ptr(ks), _ptr(kz), _ptr(vc), _ptr(vs), _ptr(vz),
+                                _stream(dev)))
+    return kc, ks, kz, vc, vs, vz

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include "qoq_internal.h"
+#include "qoq_fp16.h"
 
 namespace qoq {
 namespace {
@@ -185,25 +186,6 @@ __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* _
 // second FFN projection).  The producer is evaluated in FP64 and rounded once to FP16 (the exact bit routine
 // below), which defines the tensor an unfused pipeline would hand to the quantizer; the codes are then decided
 // from that FP16 value exactly as in the stand-alone kernel.
-__device__ inline uint16_t double_to_half_rne(double d)   // finite d; exact round-to-nearest-even, integer arithmetic only
-{
-    const uint64_t bits = (uint64_t)__double_as_longlong(d);
-    const uint16_t sign = (uint16_t)((bits >> 48) & 0x8000u);
-    const int e = (int)((bits >> 52) & 0x7FF) - 1023;    // d = 1.m * 2^e (FP64 subnormals are far below FP16's range)
-    if (e < -25) return sign;                            // below half of the smallest FP16 subnormal (or zero)
-    if (e > 15) return sign | 0x7C00u;
-    const uint64_t mant = (bits & 0xFFFFFFFFFFFFFull) | (1ull << 52);   // 53 significant bits
-    // FP16 keeps 10 fraction bits for e >= -14, fewer below: drop `shift` low bits with round-half-to-even
-    const int shift = e >= -14 ? 42 : 42 + (-14 - e);    // 42 .. 53
-    const uint64_t kept = mant >> shift, rest = mant & ((1ull << shift) - 1), half = 1ull << (shift - 1);
-    const uint64_t rounded = kept + ((rest > half || (rest == half && (kept & 1))) ? 1 : 0);
-    // e >= -14: rounded in [1024, 2048]; the biased exponent is added on top of the hidden bit, so a carry to
-    // 2048 bumps the exponent by itself (and 65520 and above become infinity).  e < -14: rounded is the
-    // subnormal pattern (1024 = smallest normal).
-    const uint32_t h = e >= -14 ? (uint32_t)((e + 14) << 10) + (uint32_t)rounded : (uint32_t)rounded;
-    return sign | (uint16_t)(h > 0x7C00u ? 0x7C00u : h);
-}
-
 __device__ inline void unpack8(const uint4& v, double (&f)[8])
 {
     const __half* h = reinterpret_cast<const __half*>(&v);

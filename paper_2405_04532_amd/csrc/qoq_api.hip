@@ -207,6 +207,56 @@ int qoq_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K, void* y_f
                                       static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
 
+static bool kv4_shape_ok(int64_t B, int64_t Hkv, int64_t S_max, int64_t D)
+{
+    return D == 128 && B >= 0 && Hkv > 0 && S_max > 0 && B <= (1 << 20) && Hkv <= 1024 && S_max <= (1 << 24) &&
+           B * Hkv * ((S_max + 63) / 64) < (int64_t)1 << 40;
+}
+
+size_t qoq_kv4_cache_bytes(int64_t B, int64_t Hkv, int64_t S_max, int64_t D)
+{
+    if (!kv4_shape_ok(B, Hkv, S_max, D)) return 0;
+    return qoq::kv4_cache_bytes(B, Hkv, S_max);
+}
+
+int qoq_kv4_append(const void* k_fp16, const void* v_fp16, const int32_t* positions, int64_t B, int64_t T, int64_t Hkv,
+                   int64_t D, int64_t S_max, void* cache, void* stream)
+{
+    if (!kv4_shape_ok(B, Hkv, S_max, D) || T < 0 || T > S_max) return QOQ_ERR_SHAPE;
+    if (B == 0 || T == 0) return QOQ_OK;
+    if (!k_fp16 || !v_fp16 || !positions || !cache) return QOQ_ERR_NULL;
+    if (!aligned16(k_fp16) || !aligned16(v_fp16) || !aligned16(cache)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_kv4_append(k_fp16, v_fp16, positions, B, T, Hkv, S_max, static_cast<uint8_t*>(cache),
+                                  static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_kv4_attention_decode(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
+                             int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* stream)
+{
+    if (!kv4_shape_ok(B, Hkv, S_max, D) || H <= 0 || H % Hkv != 0) return QOQ_ERR_SHAPE;
+    const int64_t r = H / Hkv;
+    if (r != 1 && r != 2 && r != 4 && r != 8) return QOQ_ERR_SHAPE;
+    if (B == 0) return QOQ_OK;
+    if (!q_fp16 || !cache || !seq_lens || !out_fp16) return QOQ_ERR_NULL;
+    if (!aligned16(q_fp16) || !aligned16(cache) || !aligned16(out_fp16)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_kv4_decode(q_fp16, static_cast<const uint8_t*>(cache), seq_lens, B, H, Hkv, S_max, out_fp16,
+                                  static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int64_t D, uint8_t* k_codes, void* k_scale_fp16,
+                   void* k_zero_fp16, uint8_t* v_codes, void* v_scale_fp16, void* v_zero_fp16, void* stream)
+{
+    if (!kv4_shape_ok(B, Hkv, S_max, D)) return QOQ_ERR_SHAPE;
+    if (B == 0) return QOQ_OK;
+    if (!cache || !k_codes || !k_scale_fp16 || !k_zero_fp16 || !v_codes || !v_scale_fp16 || !v_zero_fp16) return QOQ_ERR_NULL;
+    if (!aligned16(cache)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_kv4_unpack(static_cast<const uint8_t*>(cache), B, Hkv, S_max, k_codes, k_scale_fp16, k_zero_fp16, v_codes,
+                                  v_scale_fp16, v_zero_fp16, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
 int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum, const void* packed, int64_t M,
                   int64_t N, int64_t K, int mode, void* out_fp16, void* workspace, size_t workspace_bytes,
                   void* stream)

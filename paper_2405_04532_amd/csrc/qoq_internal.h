@@ -46,6 +46,15 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k);
 hipError_t launch_zero(void* dst, size_t bytes, hipStream_t s);
 
+// KV4 cache (head dimension 128) and decode attention.
+size_t kv4_cache_bytes(int64_t B, int64_t Hkv, int64_t S_max);
+hipError_t launch_kv4_append(const void* k, const void* v, const int32_t* positions, int64_t B, int64_t T, int64_t Hkv,
+                             int64_t S_max, uint8_t* cache, hipStream_t s);
+hipError_t launch_kv4_unpack(const uint8_t* cache, int64_t B, int64_t Hkv, int64_t S_max, uint8_t* k_codes, void* k_s, void* k_z,
+                             uint8_t* v_codes, void* v_s, void* v_z, hipStream_t s);
+hipError_t launch_kv4_decode(const void* q, const uint8_t* cache, const int32_t* seq_lens, int64_t B, int64_t H, int64_t Hkv,
+                             int64_t S_max, void* out, hipStream_t s);
+
 // Launch configuration the library picks for a problem (also sizes the workspace).
 struct GemmTuning { int tile_m, split_k; };  // 0 = let the heuristic decide
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k);
