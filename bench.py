@@ -46,6 +46,10 @@ def main():
     ap.add_argument("--copies", type=int, default=8, help="independently packed layer sets rotated per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", type=str, default=None, help="also write a per-layer/per-M table to this file")
+    ap.add_argument("--attention", action="store_true",
+                    help="time the KV4 decode attention kernel instead (64 sequences x --seq tokens, Llama-2-7B heads)")
+    ap.add_argument("--seq", type=int, default=1024, help="--attention: tokens in every sequence's cache")
+    ap.add_argument("--family", type=str, default="llama2_7b", help="--attention: head configuration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -61,6 +65,9 @@ def main():
     api.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.attention:
+        print(json.dumps(attention_bench(args, api, wl, dev)))
+        return
     M = args.m
     layers = list(wl.LLAMA2_7B.items())          # name -> (K, N)
 
@@ -182,6 +189,90 @@ def main():
         sweep(args.sweep, api, wl, dev)
 
     print(json.dumps(result))
+
+
+def attention_bench(args, api, wl, dev):
+    """KV4 decode attention: one new token for each of 64 sequences with `--seq` cached tokens (the shape of the
+    paper's attention latency table, Section 5.3), heads of `--family`.  Four independently filled caches are
+    rotated so that every call reads its cache from HBM.  One step = one qoq_kv4_attention_decode call."""
+    import numpy as np
+    import torch
+
+    cfg = wl.KV4_DECODE[args.family]
+    B, S, H, Hkv, D = 64, args.seq, cfg["H"], cfg["Hkv"], cfg["D"]
+    k, v = wl.make_kv(B, Hkv, S, D, 7, dev)
+    q = wl.make_queries(B, H, D, 7, dev)
+    kt, vt = k.permute(0, 2, 1, 3).contiguous(), v.permute(0, 2, 1, 3).contiguous()
+    zero = torch.zeros(B, dtype=torch.int32, device=dev)
+    n_caches = 4
+    caches = []
+    for _ in range(n_caches):
+        c = api.kv4_new_cache(B, Hkv, S, dev)
+        api.kv4_append(c, kt, vt, zero, S)
+        caches.append(c)
+    del kt, vt
+    seq = torch.full((B,), S, dtype=torch.int32, device=dev)
+    out = torch.empty((B, H, D), dtype=torch.float16, device=dev)
+    L = api.lib()
+
+    def call(i, s):
+        rc = L.qoq_kv4_attention_decode(q.data_ptr(), caches[i % n_caches].data_ptr(), seq.data_ptr(), B, H, Hkv, D, S,
+                                        out.data_ptr(), s)
+        if rc != 0:
+            raise RuntimeError(api.status_string(rc))
+
+    sp = torch.cuda.current_stream().cuda_stream
+    for i in range(args.warmup):
+        call(i, sp)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cs = torch.cuda.current_stream().cuda_stream
+        for i in range(n_caches):
+            call(i, cs)
+    graph.replay()
+    torch.cuda.synchronize()
+    steps = (args.steps // n_caches) * n_caches
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps // n_caches):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    # bytes one call must move: codes and (scale, zero) pairs of keys and values of every cached token, q, out
+    byts = B * Hkv * S * (2 * (D // 2) + 2 * 4) + 2 * B * H * D * 2
+    gbs = byts / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "KV4 decode attention time per call (64 sequences x %d cached tokens)" % S,
+        "value": round(ms, 5), "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "%s_kv4_decode_b64_s%d" % (args.family, S), "B": B, "S": S, "H": H, "Hkv": Hkv, "D": D,
+                   "caches_rotated": n_caches, "step": "1 x qoq_kv4_attention_decode, launches replayed from a HIP graph",
+                   "paper_context": "0.28 ms on A100 for 64 x 1024 (its heads are not stated); another machine, not a target"},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "kv4_decode_kernel", "avg_launch_us": round(ms * 1e3, 3), "algorithmic_bytes_per_launch": byts},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import kv4
+        picks = [(b, h) for b in range(0, B, 8) for h in range(0, H, 8)]
+        t0 = time.perf_counter()
+        done = 0
+        for b, h in picks:
+            hk = h // (H // Hkv)
+            kc, ks, kz = kv4.kv4_quantize(k[b:b + 1, hk:hk + 1].cpu().numpy())
+            vc, vs, vz = kv4.kv4_quantize(v[b:b + 1, hk:hk + 1].cpu().numpy())
+            t1 = time.perf_counter()
+            kv4.attention_decode(q[b:b + 1, h:h + 1].cpu().numpy(), kc, ks, kz, vc, vs, vz, np.array([S]))
+            done += 1
+            if time.perf_counter() - t0 > 12.0:
+                break
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(dt / done * B * H * 1e3, 3), "unit": "ms", "cores": 1, "kind": "oracle",
+                                  "sample": "%d of %d (sequence, head) pairs incl. their cache quantization, scaled to all pairs (%.1f s)"
+                                            % (done, B * H, dt)}
+    return result
 
 
 def cpu_baseline(M, xs, wl, budget_s=12.0):
