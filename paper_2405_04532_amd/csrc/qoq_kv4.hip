@@ -2,7 +2,8 @@
 // re-designed for CDNA4).
 //
 // Cache.  Keys and values are quantized when they are written: per token and KV head, Eq. 1 with 4 bits on the
-// range of that head's 128 values widened to contain 0, FP16 scale s and integer zero z (stored as FP16).  A
+// range of that head's 128 values widened to contain 0, FP16 scale s and integer zero z (stored as the FP16
+// number -(1024 + z), the form the decode kernel consumes).  A
 // page holds 64 consecutive tokens of one (sequence, KV head): 4 KiB of key codes, their 64 (s, z) pairs, 4 KiB
 // of value codes, their 64 pairs -- the parameters sit directly behind the codes they belong to, in the same
 // page.  The pages of a (sequence, head) are contiguous.
@@ -13,25 +14,31 @@
 //   then gives the exact integers (code - z) as FP16.  The odd nibbles need no shift: (x & 0x00F000F0) |
 //   0x64006400 is (1024 + 16a, 1024 + 16b), and one packed multiply-add, * 1/16 - (64 + z), is exact too.
 //   Two vector operations per pair of elements, plus one shift per dword.
-//   value codes: tokens are stored in pairs (2t, 2t+1), 128 bytes per pair: dword i holds elements 4i .. 4i+3
-//   of token 2t in its low half (element 4i+j in bits 4j..) and of token 2t+1 in its high half, so the same
-//   unpacking yields pairs (token 2t, token 2t+1) of ONE element: the weighted sum over tokens then runs on
-//   v_dot2_f32_f16 against the pair of softmax weights, two tokens per instruction.  A token still owns whole
-//   16-bit words, so appending one token is 32 plain 2-byte stores.
+//   value codes: stored tile by tile (16 tokens x 128 elements = 1 KiB) in the order the matrix instruction that
+//   forms P.V wants its operand: lane l = 16 kb + r of a wave owns the 16 bytes at 16 l; its dword 2u + h holds, for
+//   the four elements d = 4 (r + 16 u) + j (nibble j), token 4 kb + 2h in the low half and token 4 kb + 2h + 1 in the
+//   high half.  The same unpacking then yields FP16 pairs (token, next token) of one element, and two such pairs are
+//   the four k-values of an MFMA operand row.  A token still owns whole 16-bit words (32 of them), so appending a
+//   token is 32 plain 2-byte stores.
 //
-// Decode kernel.  One workgroup of four waves per (sequence, KV head); all R = H / Hkv query heads that share
-// the KV head are handled together, so the cache is read once.  Every wave streams chunks of the sequence;
-// inside a wave a token is spread over 128 / E lanes (E = 32, 16 or 8 elements per lane, fewer when more query
-// heads need registers), so a wave load covers 64 * E / 128 whole tokens = 1 KiB of contiguous cache.
-//   score = (log2 e / sqrt(D)) * s_K * sum_d q_d (code_d - z_K)      v_dot2_f32_f16: FP16 products, FP32 sums
-//   online softmax in base 2 per lane group (no communication between tokens inside the loop)
-//   acc_d += dot2((code_d - z_V) of tokens 2t, 2t+1; FP16(p * s_V) of the same two tokens)   FP32 accumulators
-// The paper moves the products of its kernel from FP32 to FP16 to lift the compute roof of its GPU; here the
-// multiplications take FP16 operands and the sums stay FP32, which the dot instructions give for free.  The partial (max, sum, acc) of all lane groups and waves meet in LDS at the end.
+// Decode kernel.  One workgroup of four waves per (sequence, KV head); every wave streams chunks of the sequence,
+// 16-token tiles at a time, and both products run on v_mfma_f32_16x16x16_f16 (FP16 operands, FP32 sums):
+//   S[token][head]  = sum_d (code - z_K)[token][d] * q[head][d]     A = unpacked keys, B = the queries of the up
+//                                                                    to 16 heads that share the KV head (GQA
+//                                                                    costs nothing extra), 8 MFMAs per tile
+//   score = S * s_K[token] * log2(e) / sqrt(D); online softmax in base 2
+//   O[d][head]     += sum_token (code - z_V)[token][d] * (p * s_V)[token][head]    8 MFMAs per tile
+// The output layout of the first product (a lane holds 4 tokens of one head) is exactly the operand layout of the
+// second, so the softmax runs in place and nothing moves between lanes except the running maximum.  The paper's
+// kernel computes on scalar cores and fights their compute roof (Section 5.3: FP16 instead of FP32 arithmetic,
+// two-operation dequantization); here the two-operation dequantization is kept and the multiply-adds go to the
+// matrix cores, which leaves the vector pipe with the unpacking and the softmax only.
 // The scale/zero words of a chunk are loaded together with its codes, one chunk ahead of the arithmetic (the
-// prefetch of the dequantization parameters of Section 5.3).
+// prefetch of the dequantization parameters of Section 5.3).  Partial (max, sum, acc) of the four waves meet in LDS.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "qoq_fp16.h"
 #include "qoq_internal.h"
@@ -47,6 +54,14 @@ constexpr int kCodeBytes = kPageTokens * kD / 2;          // 4096
 constexpr int kParamBytes = kPageTokens * 4;              // 256
 constexpr int kHalfPage = kCodeBytes + kParamBytes;       // keys (or values) of a page
 constexpr int kPageBytes = 2 * kHalfPage;                 // 8704
+
+// byte offset, inside the value codes of a page, of the 16-bit word of token `tin` (0..63) and elements 4 q4 .. 4 q4 + 3
+__device__ __forceinline__ int v_word_offset(int tin, int q4)
+{
+    const int tile = tin >> 4, kb = (tin >> 2) & 3, h = (tin >> 1) & 1, half = tin & 1;
+    const int r = q4 & 15, u = q4 >> 4;
+    return tile * 1024 + (kb * 16 + r) * 16 + (2 * u + h) * 4 + half * 2;
+}
 
 __device__ __forceinline__ float wave_min(float v) { for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64)); return v; }
 __device__ __forceinline__ float wave_max(float v) { for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64)); return v; }
@@ -91,16 +106,16 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const __half* __restric
         word |= __shfl_xor(word, 2, 64);
         if (j == 0) reinterpret_cast<uint32_t*>(page + tin * (kD / 2))[lane >> 2] = word;
     } else {
-        // values: 16-bit word i = lanes 2i, 2i+1 (elements 4i .. 4i+3), in the half of dword i that belongs to this
-        // token of its pair
+        // values: 16-bit word i = lanes 2i, 2i+1 (elements 4i .. 4i+3)
         const int j = (lane & 1) * 2;
         uint32_t word = (c0 << (4 * j)) | (c1 << (4 * j + 4));
         word |= __shfl_xor(word, 1, 64);
-        if ((lane & 1) == 0)
-            reinterpret_cast<uint16_t*>(page + (tin >> 1) * kD)[(lane >> 1) * 2 + (tin & 1)] = (uint16_t)word;
+        if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(page + v_word_offset(tin, lane >> 1)) = (uint16_t)word;
     }
     if (lane == 0) {
-        const uint16_t z_bits = __half_as_ushort(__float2half_rn((float)zf));    // integer 0..15: exact
+        // the zero point is stored as the FP16 number -(1024 + z) (an exact integer), the constant the decode
+        // kernel adds to its unpacked codes
+        const uint16_t z_bits = __half_as_ushort(__float2half_rn(-1024.0f - (float)zf));
         reinterpret_cast<uint32_t*>(page + kCodeBytes)[tin] = (uint32_t)s_bits | ((uint32_t)z_bits << 16);
     }
 }
@@ -127,10 +142,9 @@ __global__ __launch_bounds__(256) void kv4_unpack_kernel(const uint8_t* __restri
             dst[2 * j + 1] = (uint8_t)((word >> (16 + 4 * j)) & 0xFu);
         }
     } else {
-        const uint16_t* pair = reinterpret_cast<const uint16_t*>(page + (tin >> 1) * kD);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {                     // elements 8w + 4i .. + 3 sit in 16-bit word 2w + i of this token
-            const uint32_t half = pair[(2 * w + i) * 2 + (tin & 1)];
+        for (int i = 0; i < 2; ++i) {                     // elements 8w + 4i .. + 3 sit in one 16-bit word
+            const uint32_t half = *reinterpret_cast<const uint16_t*>(page + v_word_offset(tin, 2 * w + i));
 #pragma unroll
             for (int j = 0; j < 4; ++j) dst[4 * i + j] = (uint8_t)((half >> (4 * j)) & 0xFu);
         }
@@ -138,7 +152,7 @@ __global__ __launch_bounds__(256) void kv4_unpack_kernel(const uint8_t* __restri
     if (w == 0) {
         const uint32_t prm = reinterpret_cast<const uint32_t*>(page + kCodeBytes)[tin];
         (which ? v_s : k_s)[bht] = __ushort_as_half((unsigned short)(prm & 0xFFFFu));
-        (which ? v_z : k_z)[bht] = __ushort_as_half((unsigned short)(prm >> 16));
+        (which ? v_z : k_z)[bht] = __float2half_rn(-1024.0f - __half2float(__ushort_as_half((unsigned short)(prm >> 16))));
     }
 }
 
@@ -146,7 +160,7 @@ __global__ __launch_bounds__(256) void kv4_unpack_kernel(const uint8_t* __restri
 // Decode attention.
 // ------------------------------------------------------------------------------------------
 // the four FP16 pairs of a code dword, minus the zero point: out[j] = (nibble j of the low half, of the high half)
-// c = -(1024 + z), c16 = -(64 + z), per half
+// c = -(1024 + z), c16 = -(64 + z) = c + 960, per half
 // (x & mask) | bits in one instruction.  All three sources are vector registers: with the two constants in scalar
 // registers the instruction would exceed its one-scalar-operand limit and the compiler splits it in two.
 __device__ __forceinline__ h2 and_or(uint32_t x, uint32_t mask, uint32_t bits)
@@ -165,154 +179,151 @@ __device__ __forceinline__ void unpack4(uint32_t word, h2 c, h2 c16, h2 (&out)[4
     out[3] = and_or(hi, 0x00F000F0u, 0x64006400u) * sixteenth + c16;
 }
 
-__device__ __forceinline__ h2 pack_rne(float a, float b) { return (h2){(_Float16)a, (_Float16)b}; }
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ h4 join(h2 a, h2 b) { return __builtin_shufflevector(a, b, 0, 1, 2, 3); }
+__device__ __forceinline__ _Float16 half_bits(uint32_t v) { return __builtin_bit_cast(_Float16, (unsigned short)v); }
 
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = 4;
-constexpr int kNT = 4;                                   // tokens (two pairs) per lane and chunk
+constexpr int kMaxRatio = 16;                            // query heads per KV head: the columns of one MFMA
 
-// E elements per lane: a token (pair) is spread over 128 / E lanes.
-template <int R, int E>
-__global__ __launch_bounds__(kDecodeThreads) void kv4_decode_kernel(const __half* __restrict__ q, const uint8_t* __restrict__ cache,
-                                                                    const int32_t* __restrict__ seq_lens, int64_t Hkv,
+// NTL tiles of 16 tokens per chunk.
+template <int NTL>
+__global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void kv4_decode_kernel(const __half* __restrict__ q, const uint8_t* __restrict__ cache,
+                                                                    const int32_t* __restrict__ seq_lens, int64_t Hkv, int R,
                                                                     int64_t S_max, __half* __restrict__ out)
 {
-    constexpr int LPT = kD / E;                          // lanes per token
-    constexpr int TPW = 64 / LPT;                        // lane groups = tokens per wave load of keys
-    constexpr int CH = kNT * TPW;                        // tokens per chunk (divides the page)
-    constexpr int WK = E / 8;                            // key dwords per lane and token
-    constexpr int WV = E / 4;                            // value dwords per lane and token pair
-    constexpr int NP = kDecodeWaves * TPW;               // partial results per query head
-    static_assert(E == 32 || E == 16 || E == 8, "elements per lane");
-    __shared__ float s_acc[NP][R][kD];
-    __shared__ float s_m[NP][R], s_l[NP][R];
+    constexpr int CH = 16 * NTL;                         // tokens per chunk (divides the page)
+    __shared__ float s_acc[kDecodeWaves][kMaxRatio][kD];
+    __shared__ float s_m[kDecodeWaves][kMaxRatio], s_l[kDecodeWaves][kMaxRatio];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tl = lane / LPT, p = lane % LPT;
+    const int r16 = lane & 15, kb = lane >> 4;           // operand row (token / element slot / head) and k-block
     const int64_t bh = blockIdx.x;                       // b * Hkv + hk
     const int64_t b = bh / Hkv, hk = bh % Hkv;
     const int64_t n_pages = (S_max + kPageTokens - 1) / kPageTokens;
     const int L = (int)min((int64_t)max(seq_lens[b], 0), S_max);
     const uint8_t* stream = cache + bh * n_pages * kPageBytes;
-    __half* out_bh = out + (b * Hkv * R + hk * R) * kD;
+    __half* out_bh = out + (b * Hkv + hk) * R * kD;
     if (L == 0) {                                        // empty cache: zero rows
         for (int x = threadIdx.x; x < R * kD; x += kDecodeThreads) out_bh[x] = __float2half_rn(0.f);
         return;
     }
 
-    // this lane's slice of every query head sharing the KV head
-    h2 qv[R][E / 2];
+    // B operand of S = K q^T: column r16 = query head, k-block kb = elements 32 kb .. 32 kb + 31 (heads >= R: zero)
+    h2 qv[16];
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(q + ((b * Hkv + hk) * R + min(r16, R - 1)) * kD + kb * 32);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(q + (b * Hkv * R + hk * R + r) * kD + p * E);
-#pragma unroll
-        for (int e = 0; e < E / 2; ++e) qv[r][e] = __builtin_bit_cast(h2, src[e]);
+        for (int e = 0; e < 16; ++e) qv[e] = __builtin_bit_cast(h2, r16 < R ? src[e] : 0u);
     }
 
-    // A lane group handles two token pairs per chunk: pairs tl and tl + TPW of the chunk's 2 * TPW pairs.
-    struct Chunk { uint32_t kc[kNT][WK], vc[2][WV], kp[kNT], vp[kNT]; };
+    struct Chunk {
+        uint4 kc[NTL];      // keys: token r16 of the tile, elements 32 kb ..
+        uint4 vc[NTL];      // values: this lane's 16 bytes of the tile
+        uint32_t kz[NTL];   // (s, z) of token r16 (zero point for unpacking)
+        uint4 ks[NTL];      // (s, z) of tokens 4 kb .. 4 kb + 3 (scales of the scores this lane receives)
+        uint4 vp[NTL];      // (s, z) of tokens 4 kb .. 4 kb + 3 of the values
+    };
     auto load_chunk = [&](Chunk& c, int chunk) __attribute__((always_inline)) {
 #pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-            const int t0 = chunk * CH + 2 * (tl + pr * TPW);   // < n_pages * 64: inside the allocation even past L
+        for (int tt = 0; tt < NTL; ++tt) {
+            const int t0 = chunk * CH + tt * 16;         // < n_pages * 64: inside the allocation even past L
             const uint8_t* page = stream + (int64_t)(t0 / kPageTokens) * kPageBytes;
-            const int tin = t0 % kPageTokens;            // even
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint32_t* kw = reinterpret_cast<const uint32_t*>(page + (tin + u) * (kD / 2) + p * (E / 2));
-#pragma unroll
-                for (int w = 0; w < WK; ++w) c.kc[2 * pr + u][w] = kw[w];
-                c.kp[2 * pr + u] = reinterpret_cast<const uint32_t*>(page + kCodeBytes)[tin + u];
-                c.vp[2 * pr + u] = reinterpret_cast<const uint32_t*>(page + kHalfPage + kCodeBytes)[tin + u];
-            }
-            const uint32_t* vw = reinterpret_cast<const uint32_t*>(page + kHalfPage + (tin >> 1) * kD + p * E);
-#pragma unroll
-            for (int w = 0; w < WV; ++w) c.vc[pr][w] = vw[w];
+            const int tin = t0 % kPageTokens;
+            c.kc[tt] = *reinterpret_cast<const uint4*>(page + (tin + r16) * (kD / 2) + kb * 16);
+            c.kz[tt] = reinterpret_cast<const uint32_t*>(page + kCodeBytes)[tin + r16];
+            c.ks[tt] = *reinterpret_cast<const uint4*>(page + kCodeBytes + (tin + 4 * kb) * 4);
+            c.vc[tt] = *reinterpret_cast<const uint4*>(page + kHalfPage + (tin >> 4) * 1024 + lane * 16);
+            c.vp[tt] = *reinterpret_cast<const uint4*>(page + kHalfPage + kCodeBytes + (tin + 4 * kb) * 4);
         }
     };
 
-    float m[R], l[R], acc[R][E];
+    float m = -1e30f, l = 0.f;                           // of head r16, over the tokens this lane has seen
+    f4 acc[8];                                           // acc[4u + j][x]: element d = 16 kb + 4x + 64u + j of head r16
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        m[r] = -1e30f; l[r] = 0.f;
-#pragma unroll
-        for (int e = 0; e < E; ++e) acc[r][e] = 0.f;
-    }
+    for (int i = 0; i < 8; ++i) acc[i] = (f4){0.f, 0.f, 0.f, 0.f};
     const float kScale = 1.4426950408889634f * 0.08838834764831845f;      // log2(e) / sqrt(128)
     const int n_chunks = (L + CH - 1) / CH;
 
-    // One chunk of arithmetic.  `chunk` may lie past the end of the sequence (then every token is masked).
-    auto process = [&](const Chunk& cur, int chunk) __attribute__((always_inline)) {
-        float sc[R][kNT], vscale[kNT];
-        _Float16 vzero[kNT];
-        bool valid[kNT];
+    const h2 k960 = {(_Float16)960.0f, (_Float16)960.0f};
+    // One chunk of arithmetic.  MASKED: the chunk reaches past the end of the sequence (possibly entirely); the
+    // parameters of tokens past the end are whatever the cache holds and must not enter the arithmetic.
+    auto process_as = [&](const Chunk& cur, int chunk, auto masked_tag) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        f4 sc[NTL];
+        float m_new = m;
 #pragma unroll
-        for (int i = 0; i < kNT; ++i) {
-            valid[i] = chunk * CH + 2 * (tl + (i >> 1) * TPW) + (i & 1) < L;
-            // parameters of tokens past the end are whatever the cache holds: never let them into the arithmetic
-            const uint32_t kp = valid[i] ? cur.kp[i] : 0u, vp = valid[i] ? cur.vp[i] : 0u;
-            const float ks = __half2float(__ushort_as_half((unsigned short)(kp & 0xFFFFu)));
-            const _Float16 kz = __builtin_bit_cast(_Float16, (unsigned short)(kp >> 16));
-            const h2 c = {(_Float16)(-1024.0f) - kz, (_Float16)(-1024.0f) - kz};
-            const h2 c16 = {(_Float16)(-64.0f) - kz, (_Float16)(-64.0f) - kz};
-            vscale[i] = __half2float(__ushort_as_half((unsigned short)(vp & 0xFFFFu)));
-            vzero[i] = __builtin_bit_cast(_Float16, (unsigned short)(vp >> 16));
-            float dot[R];
+        for (int tt = 0; tt < NTL; ++tt) {
+            const int t0 = chunk * CH + tt * 16;
+            uint32_t kz = cur.kz[tt];
+            if (MASKED) kz = t0 + r16 < L ? kz : 0xE4000000u;               // -(1024 + 0)
+            const h2 c = __builtin_bit_cast(h2, __builtin_amdgcn_perm(kz, kz, 0x07060706u));   // high half in both halves
+            const h2 c16 = c + k960;
+            const uint32_t kw[4] = {cur.kc[tt].x, cur.kc[tt].y, cur.kc[tt].z, cur.kc[tt].w};
+            f4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < R; ++r) dot[r] = 0.f;
-#pragma unroll
-            for (int w = 0; w < WK; ++w) {
+            for (int w = 0; w < 4; ++w) {
                 h2 kh[4];
-                unpack4(cur.kc[i][w], c, c16, kh);       // kh[j] = elements 8w + 2j, 8w + 2j + 1
+                unpack4(kw[w], c, c16, kh);              // kh[j] = elements 8w + 2j, 8w + 2j + 1 of this lane's 32
+                d = __builtin_amdgcn_mfma_f32_16x16x16f16(join(kh[0], kh[1]), join(qv[4 * w], qv[4 * w + 1]), d, 0, 0, 0);
+                d = __builtin_amdgcn_mfma_f32_16x16x16f16(join(kh[2], kh[3]), join(qv[4 * w + 2], qv[4 * w + 3]), d, 0, 0, 0);
+            }
+            const uint32_t sw[4] = {cur.ks[tt].x, cur.ks[tt].y, cur.ks[tt].z, cur.ks[tt].w};
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {                // d[x] = token 4 kb + x of the tile, head r16
+                const float ks = (float)half_bits(sw[x]);
+                sc[tt][x] = d[x] * (ks * kScale);
+                if (MASKED) sc[tt][x] = t0 + 4 * kb + x < L ? sc[tt][x] : -1e30f;
+                m_new = fmaxf(m_new, sc[tt][x]);
+            }
+        }
+        m_new = fmaxf(m_new, __shfl_xor(m_new, 16, 64));  // the four k-blocks of a head agree on the maximum
+        m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));
+        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {                  // rare once a few chunks have been seen
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            m = m_new;
+            l *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] *= alpha;
+        }
+#pragma unroll
+        for (int tt = 0; tt < NTL; ++tt) {
+            const int t0 = chunk * CH + tt * 16;
+            uint32_t pw[4] = {cur.vp[tt].x, cur.vp[tt].y, cur.vp[tt].z, cur.vp[tt].w};
+            float wf[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                if (MASKED) pw[x] = t0 + 4 * kb + x < L ? pw[x] : 0xE4000000u;   // scale 0, zero point 0
+                // a masked score is -1e30: its weight underflows to 0 unless nothing valid has been seen yet
+                // (then m is -1e30 too), which the zero scale takes care of
+                const float pr = __builtin_amdgcn_exp2f(sc[tt][x] - m);
+                l += MASKED ? (t0 + 4 * kb + x < L ? pr : 0.f) : pr;
+                wf[x] = pr * (float)half_bits(pw[x]);
+            }
+            const h4 bw = {(_Float16)wf[0], (_Float16)wf[1], (_Float16)wf[2], (_Float16)wf[3]};   // B: tokens 4 kb .., head r16
+            const uint32_t vw[4] = {cur.vc[tt].x, cur.vc[tt].y, cur.vc[tt].z, cur.vc[tt].w};
+            h2 vh[2][2][4];                              // [u][h][j]: (token 4 kb + 2h, + 1) of element 4 (r16 + 16 u) + j
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const h2 c = __builtin_bit_cast(h2, __builtin_amdgcn_perm(pw[2 * h + 1], pw[2 * h], 0x07060302u));
+                const h2 c16 = c + k960;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) unpack4(vw[2 * u + h], c, c16, vh[u][h]);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int r = 0; r < R; ++r) dot[r] = __builtin_amdgcn_fdot2(kh[j], qv[r][w * 4 + j], dot[r], false);
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-#pragma unroll
-                for (int o = 1; o < LPT; o <<= 1) dot[r] += __shfl_xor(dot[r], o, 64);
-                sc[r][i] = dot[r] * (ks * kScale);
-            }
+                    acc[4 * u + j] = __builtin_amdgcn_mfma_f32_16x16x16f16(join(vh[u][0][j], vh[u][1][j]), bw, acc[4 * u + j], 0, 0, 0);
         }
-        h2 wgt[R][2];                                    // FP16 weights (p * s_V) of the two tokens of each pair
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            float m_new = m[r];
-#pragma unroll
-            for (int i = 0; i < kNT; ++i) m_new = valid[i] ? fmaxf(m_new, sc[r][i]) : m_new;
-            const float alpha = exp2f(m[r] - m_new);
-            m[r] = m_new;
-            l[r] *= alpha;
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc[r][e] *= alpha;
-            float wf[kNT];
-#pragma unroll
-            for (int i = 0; i < kNT; ++i) {
-                const float pr = valid[i] ? exp2f(sc[r][i] - m_new) : 0.f;
-                l[r] += pr;
-                wf[i] = pr * vscale[i];
-            }
-            wgt[r][0] = pack_rne(wf[0], wf[1]);
-            wgt[r][1] = pack_rne(wf[2], wf[3]);
-        }
-#pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-            const h2 c = {(_Float16)(-1024.0f) - vzero[2 * pr], (_Float16)(-1024.0f) - vzero[2 * pr + 1]};
-            const h2 c16 = {(_Float16)(-64.0f) - vzero[2 * pr], (_Float16)(-64.0f) - vzero[2 * pr + 1]};
-#pragma unroll
-            for (int w = 0; w < WV; ++w) {
-                h2 vh[4];
-                unpack4(cur.vc[pr][w], c, c16, vh);      // vh[j] = element 4w + j of the pair's two tokens
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-                        acc[r][w * 4 + j] = __builtin_amdgcn_fdot2(vh[j], wgt[r][pr], acc[r][w * 4 + j], false);
-            }
-        }
+    };
+    auto process = [&](const Chunk& cur, int chunk) __attribute__((always_inline)) {
+        if (chunk * CH + CH <= L) process_as(cur, chunk, std::false_type{});
+        else process_as(cur, chunk, std::true_type{});
     };
 
     // Wave w takes chunks w, w + 4, ...; all waves run the same number of iterations (a wave without a chunk in
@@ -325,36 +336,43 @@ __global__ __launch_bounds__(kDecodeThreads) void kv4_decode_kernel(const __half
     Chunk A, Bf;
     fetch(A, 0);
     int it = 0;
+    // Only a wave's last chunk can reach past the end of the sequence: every earlier one lies before the final chunk.
     for (; it + 2 < n_iter; it += 2) {
         fetch(Bf, it + 1);
-        process(A, chunk_of(it));
+        process_as(A, chunk_of(it), std::false_type{});
         fetch(A, it + 2);
-        process(Bf, chunk_of(it + 1));
+        process_as(Bf, chunk_of(it + 1), std::false_type{});
     }
     if (it + 2 == n_iter) {
         fetch(Bf, it + 1);
-        process(A, chunk_of(it));
+        process_as(A, chunk_of(it), std::false_type{});
         process(Bf, chunk_of(it + 1));
     } else {
         process(A, chunk_of(it));
     }
 
-    // ---- partial results of all lane groups and waves meet in LDS -------------------------------
-    const int slot = wave * TPW + tl;
+    // ---- the four waves' partial results meet in LDS --------------------------------------------
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (r16 < R) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int e = 0; e < E; ++e) s_acc[slot][r][p * E + e] = acc[r][e];
-        if (p == 0) { s_m[slot][r] = m[r]; s_l[slot][r] = l[r]; }
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) s_acc[wave][r16][16 * kb + 4 * x + 64 * u + j] = acc[4 * u + j][x];
+        if (kb == 0) { s_m[wave][r16] = m; s_l[wave][r16] = l; }
     }
     __syncthreads();
     for (int x = threadIdx.x; x < R * kD; x += kDecodeThreads) {
         const int r = x / kD, d = x % kD;
         float mm = -1e30f;
-        for (int i = 0; i < NP; ++i) mm = fmaxf(mm, s_m[i][r]);
+#pragma unroll
+        for (int i = 0; i < kDecodeWaves; ++i) mm = fmaxf(mm, s_m[i][r]);
         float num = 0.f, den = 0.f;
-        for (int i = 0; i < NP; ++i) {
-            const float f = exp2f(s_m[i][r] - mm);
+#pragma unroll
+        for (int i = 0; i < kDecodeWaves; ++i) {
+            const float f = __builtin_amdgcn_exp2f(s_m[i][r] - mm);
             num = fmaf(s_acc[i][r][d], f, num);
             den = fmaf(s_l[i][r], f, den);
         }
@@ -398,13 +416,9 @@ hipError_t launch_kv4_decode(const void* q, const uint8_t* cache, const int32_t*
     const dim3 grid((unsigned)(B * Hkv));
     const __half* qh = static_cast<const __half*>(q);
     __half* oh = static_cast<__half*>(out);
-    switch (H / Hkv) {
-        case 1: kv4_decode_kernel<1, 32><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, S_max, oh); break;
-        case 2: kv4_decode_kernel<2, 16><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, S_max, oh); break;
-        case 4: kv4_decode_kernel<4, 8><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, S_max, oh); break;
-        case 8: kv4_decode_kernel<8, 8><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, S_max, oh); break;
-        default: return hipErrorInvalidValue;
-    }
+    const int R = (int)(H / Hkv);
+    if (R < 1 || R > kMaxRatio) return hipErrorInvalidValue;
+    kv4_decode_kernel<2><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, R, S_max, oh);
     return hipGetLastError();
 }
 
