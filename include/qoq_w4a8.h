@@ -173,13 +173,14 @@ int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N
  *   positions        [B] INT32, device
  * qoq_kv4_attention_decode: one new query token per sequence,
  *   out[b, h, :] = softmax_t( q[b, h, :] . K^[b, floor(h / r), t, :] / sqrt(D) ) V^[b, floor(h / r), t, :],
- *   t < seq_lens[b], r = H / Hkv in {1, 2, 4, 8}; K^, V^ the dequantized cache.  Products take FP16 operands, sums
- *   and the softmax are FP32, one rounding to FP16 at the end.  seq_lens[b] is clamped to [0, S_max]; an empty
+ *   t < seq_lens[b], r = H / Hkv an integer in 1 .. 16; K^, V^ the dequantized cache.  Products take FP16 operands
+ *   (the softmax weight times the value scale is rounded to FP16 for that), sums and the softmax are FP32, one
+ *   rounding to FP16 at the end.  seq_lens[b] is clamped to [0, S_max]; an empty
  *   sequence gives a zero row.
  *   q_fp16 [B, H, D] FP16; seq_lens [B] INT32 device; out_fp16 [B, H, D] FP16 (written)
  * qoq_kv4_unpack (tests): codes as one byte each [B, Hkv, S_max, D] and the FP16 scales / zeros [B, Hkv, S_max]
  * of keys and values; positions never written hold whatever the buffer held.
- * Errors: QOQ_ERR_SHAPE (D != 128, negative sizes, H not r * Hkv), QOQ_ERR_NULL, QOQ_ERR_ALIGN (16 bytes),
+ * Errors: QOQ_ERR_SHAPE (D != 128, negative sizes, H not a multiple of Hkv or more than 16 times Hkv), QOQ_ERR_NULL, QOQ_ERR_ALIGN (16 bytes),
  * QOQ_ERR_ARCH, QOQ_ERR_HIP.  Nothing is allocated; all work is enqueued on `stream`. */
 size_t qoq_kv4_cache_bytes(int64_t B, int64_t Hkv, int64_t S_max, int64_t D);
 int qoq_kv4_append(const void* k_fp16, const void* v_fp16, const int32_t* positions, int64_t B, int64_t T,

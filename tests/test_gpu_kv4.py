@@ -1,10 +1,13 @@
 """GPU parity of the KV4 cache quantizer and the decode attention kernel against the CPU oracle, through the C ABI.
 
-Codes, scales and zero points must be bit-exact.  The attention output is floating point: products take FP16
-operands exactly, sums and the softmax run in FP32 and the result is rounded once to FP16, so
-    |gpu - ref| <= 1e-3 * |ref| + 1e-4 * max|V^|
-(one FP16 rounding is 4.9e-4 relative; FP32 accumulation over a few thousand tokens and the hardware exp2 stay two
-orders of magnitude below the second term)."""
+Codes, scales and zero points must be bit-exact.  The attention output is floating point: the integer codes enter the
+products exactly, the softmax weight of a token (times its value scale) is rounded to FP16 before the second
+product, sums and the softmax run in FP32 and the result is rounded once to FP16, so
+    |gpu - ref| <= 1e-3 * |ref| + 1e-3 * max|V^|
+The first term is the final rounding (4.9e-4 relative) with margin.  The second bounds the effect of the FP16
+weights: each weight carries an independent relative error of at most 2^-11 = 4.9e-4, so the weighted average moves
+by at most 4.9e-4 * sum_t p_t |v_t| <= 4.9e-4 * max|V^|, again with margin (FP32 accumulation and the hardware
+exp2 are two orders of magnitude below)."""
 import numpy as np
 import pytest
 import torch
@@ -104,14 +107,18 @@ def _attention_case(B, H, Hkv, S_max, lens, seed):
     got = out.cpu().numpy().astype(np.float64)
     v_hat = kv4.kv4_dequantize(o[3], o[4], o[5])
     vmax = np.abs(v_hat).max(axis=(2, 3))                       # [B, Hkv]
-    tol = 1e-3 * np.abs(ref) + 1e-4 * np.repeat(vmax, H // Hkv, axis=1)[:, :, None]
+    tol = 1e-3 * np.abs(ref) + 1e-3 * np.repeat(vmax, H // Hkv, axis=1)[:, :, None]
     assert np.isfinite(got).all()
     bad = np.abs(got - ref) > tol
     assert not bad.any(), (int(bad.sum()), float(np.abs(got - ref).max()))
+    # the bound above is a worst case; the roundings are independent, so the typical error is far smaller
+    live = np.array(lens) > 0
+    rms = np.sqrt(np.mean((got[live] - ref[live]) ** 2))
+    assert rms <= 2e-4 * vmax[live].mean(), float(rms)
     return got, ref
 
 
-@pytest.mark.parametrize("H,Hkv", [(4, 4), (4, 2), (8, 2), (8, 1)])
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (4, 2), (8, 2), (8, 1), (6, 2), (16, 1)])
 def test_attention_ragged_lengths(H, Hkv):
     """Lengths around chunk and page boundaries, one token, none; every ratio of query to KV heads."""
     lens = [0, 1, 3, 15, 16, 17, 63, 64, 65, 130, 200]
@@ -156,7 +163,7 @@ def test_attention_full_size_sampled():
         vc, vs, vz = kv4.kv4_quantize(vb)
         ref = kv4.attention_decode(q[b:b + 1, h:h + 1].cpu().numpy(), kc, ks, kz, vc, vs, vz, lens[b:b + 1])[0, 0]
         got = out[b, h].cpu().numpy().astype(np.float64)
-        tol = 1e-3 * np.abs(ref) + 1e-4 * np.abs(kv4.kv4_dequantize(vc, vs, vz)).max()
+        tol = 1e-3 * np.abs(ref) + 1e-3 * np.abs(kv4.kv4_dequantize(vc, vs, vz)).max()
         assert np.all(np.abs(got - ref) <= tol), (b, h, float(np.abs(got - ref).max()))
 
 
@@ -169,7 +176,7 @@ def test_kv4_argument_validation():
     args = lambda H, Hkv, D: (q.data_ptr(), cache.data_ptr(), seq.data_ptr(), 1, H, Hkv, D, 64, out.data_ptr(), None)
     assert L.qoq_kv4_attention_decode(*args(4, 4, 64)) == 2          # head dimension
     assert L.qoq_kv4_attention_decode(*args(4, 3, 128)) == 2         # H not a multiple of Hkv
-    assert L.qoq_kv4_attention_decode(*args(48, 4, 128)) == 2        # ratio 12 not supported
+    assert L.qoq_kv4_attention_decode(*args(68, 4, 128)) == 2        # ratio 17: more than one matrix tile of heads
     assert L.qoq_kv4_attention_decode(None, cache.data_ptr(), seq.data_ptr(), 1, 4, 4, 128, 64, out.data_ptr(), None) == 1
     assert L.qoq_kv4_attention_decode(q.data_ptr() + 2, cache.data_ptr(), seq.data_ptr(), 1, 4, 4, 128, 64, out.data_ptr(), None) == 3
     assert api.kv4_cache_bytes(1, 4, 64, 64) == 0
