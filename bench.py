@@ -12,6 +12,7 @@ as they do when a whole model's layers stream through.
 Prints ONE JSON line: effective TOPS (2*M*K*N summed over the layers / step time), the HBM
 roofline of the GEMM launch, and the CPU oracle timed on the host cores as a baseline.
 `--sweep FILE` additionally writes per-layer, per-M timings of every configuration family.
+`--attention` times the KV4 decode attention kernel instead (its own JSON line, same fields).
 """
 import argparse
 import json
@@ -251,7 +252,9 @@ def attention_bench(args, api, wl, dev):
                    "caches_rotated": n_caches, "step": "1 x qoq_kv4_attention_decode, launches replayed from a HIP graph",
                    "paper_context": "0.28 ms on A100 for 64 x 1024 (its heads are not stated); another machine, not a target"},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     # from the counter runs summarised in profiles/kv4_decode_attention_llama2_7b_b64_s1024.txt
+                     "traffic": 286.52e6 if (S == 1024 and args.family == "llama2_7b") else None,
                      "kernel": "kv4_decode_kernel", "avg_launch_us": round(ms * 1e3, 3), "algorithmic_bytes_per_launch": byts},
     }
     if not args.no_cpu_baseline:

@@ -228,17 +228,24 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
         uint4 ks[NTL];      // (s, z) of tokens 4 kb .. 4 kb + 3 (scales of the scores this lane receives)
         uint4 vp[NTL];      // (s, z) of tokens 4 kb .. 4 kb + 3 of the values
     };
+    // Every address is a wave-uniform tile base plus a lane offset that never changes: the five loads of a tile
+    // cost no vector address arithmetic.
+    const uint32_t off_kc = (uint32_t)(r16 * (kD / 2) + kb * 16), off_kz = (uint32_t)(kCodeBytes + r16 * 4);
+    const uint32_t off_ks = (uint32_t)(kCodeBytes + kb * 16), off_vc = (uint32_t)(kHalfPage + lane * 16);
+    const uint32_t off_vp = (uint32_t)(kHalfPage + kCodeBytes + kb * 16);
     auto load_chunk = [&](Chunk& c, int chunk) __attribute__((always_inline)) {
 #pragma unroll
         for (int tt = 0; tt < NTL; ++tt) {
-            const int t0 = chunk * CH + tt * 16;         // < n_pages * 64: inside the allocation even past L
+            const int t0 = __builtin_amdgcn_readfirstlane(chunk * CH + tt * 16);   // < n_pages * 64: inside the allocation
             const uint8_t* page = stream + (int64_t)(t0 / kPageTokens) * kPageBytes;
-            const int tin = t0 % kPageTokens;
-            c.kc[tt] = *reinterpret_cast<const uint4*>(page + (tin + r16) * (kD / 2) + kb * 16);
-            c.kz[tt] = reinterpret_cast<const uint32_t*>(page + kCodeBytes)[tin + r16];
-            c.ks[tt] = *reinterpret_cast<const uint4*>(page + kCodeBytes + (tin + 4 * kb) * 4);
-            c.vc[tt] = *reinterpret_cast<const uint4*>(page + kHalfPage + (tin >> 4) * 1024 + lane * 16);
-            c.vp[tt] = *reinterpret_cast<const uint4*>(page + kHalfPage + kCodeBytes + (tin + 4 * kb) * 4);
+            const int tin = t0 % kPageTokens;            // first token of the tile inside its page (a multiple of 16)
+            const uint8_t* codes = page + tin * (kD / 2);          // key codes of the tile; its value codes lie 4352 further
+            const uint8_t* prm = page + tin * 4;                   // (s, z) words of the tile
+            c.kc[tt] = *reinterpret_cast<const uint4*>(codes + off_kc);
+            c.kz[tt] = *reinterpret_cast<const uint32_t*>(prm + off_kz);
+            c.ks[tt] = *reinterpret_cast<const uint4*>(prm + off_ks);
+            c.vc[tt] = *reinterpret_cast<const uint4*>(codes + off_vc);
+            c.vp[tt] = *reinterpret_cast<const uint4*>(prm + off_vp);
         }
     };
 
