@@ -158,6 +158,29 @@ int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N
                     void* out_fp16, int8_t* qx, void* sx_fp16, int32_t* rowsum,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Data-free offline transforms (Section 4.3: "Activation-Aware Channel Reordering", "Block Input Module
+ * Rotation") ------------------------------------------------------------------------------------------
+ * Reordering: the salience of input channel k is max_m |X[m, k]| over calibration tokens; channels are sorted by
+ * decreasing salience (ties by channel index) so that a quantization group holds channels of similar salience.
+ * Weights are permuted once (gather, then qoq_pack_weights); at run time the activations are permuted inside the
+ * quantizer.  X W^T is unchanged.
+ *   qoq_channel_absmax     x_fp16 [M, K] device -> absmax [K] FP32 device (overwritten).  K % 8 == 0.
+ *   qoq_channel_order_host salience [K] FP32 HOST -> perm [K] INT32 HOST: new channel j = old channel perm[j].
+ *   qoq_gather_channels    dst[r, j] = src[r, perm[j]], FP16 [rows, K] device, perm [K] INT32 device, not in place.
+ *   qoq_quant_act_per_token_reordered   qoq_quant_act_per_token of x[:, perm] in one pass (K <= 32768).
+ * perm entries outside [0, K) are clamped (a kernel cannot report them).
+ * Rotation: dst = src (I (x) H_block) / sqrt(block), H the Sylvester Hadamard matrix, block a power of two
+ * <= 8192 dividing K; the exact product (FP64 sums of FP16 numbers) rounded once to FP16.  Applied to the
+ * activations of a block input and to the weights [N, K] of its input modules alike, it leaves X W^T unchanged.
+ *   qoq_hadamard_rotate    src_fp16, dst_fp16 [rows, K] FP16 device (may coincide), rows <= 65535.
+ * Errors as above (QOQ_ERR_SHAPE, QOQ_ERR_NULL, QOQ_ERR_ALIGN, QOQ_ERR_ARCH, QOQ_ERR_HIP). */
+int qoq_channel_absmax(const void* x_fp16, int64_t M, int64_t K, float* absmax, void* stream);
+int qoq_channel_order_host(const float* salience_host, int64_t K, int32_t* perm_host);
+int qoq_gather_channels(const void* src_fp16, const int32_t* perm, int64_t rows, int64_t K, void* dst_fp16, void* stream);
+int qoq_quant_act_per_token_reordered(const void* x_fp16, const int32_t* perm, int64_t M, int64_t K, int8_t* qx,
+                                      void* sx_fp16, int32_t* rowsum, float* tx, void* stream);
+int qoq_hadamard_rotate(const void* src_fp16, int64_t rows, int64_t K, int64_t block, void* dst_fp16, void* stream);
+
 /* ---- KV4 cache and decode attention (Sections 5.1 "KV Cache Management" and 5.3; Eq. 1-2; the attention
  * equation of Section 3.1) ----------------------------------------------------------------------------
  * The cache holds keys and values as 4-bit codes with one FP16 scale and one FP16 zero point per token and KV

@@ -51,6 +51,15 @@ _SIGNATURES = {
                                        ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_set_gemm_config": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+    "qoq_channel_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
+    "qoq_channel_order_host": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
+    "qoq_gather_channels": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                           ctypes.c_void_p]),
+    "qoq_quant_act_per_token_reordered": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                         ctypes.c_void_p]),
+    "qoq_hadamard_rotate": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                           ctypes.c_void_p]),
     "qoq_kv4_cache_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]),
     "qoq_kv4_append": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
@@ -320,3 +329,55 @@ def kv4_unpack(cache, B, Hkv, S_max, D=128):
     _check(lib().qoq_kv4_unpack(_ptr(cache), B, Hkv, S_max, D, _ptr(kc), _ptr(ks), _ptr(kz), _ptr(vc), _ptr(vs), _ptr(vz),
                                 _stream(dev)))
     return kc, ks, kz, vc, vs, vz
+
+
+# ---------------------------------------------------------------------------------------
+# Data-free offline transforms: channel reordering, Hadamard rotation
+# ---------------------------------------------------------------------------------------
+def channel_absmax(x):
+    """max over tokens of |x| per input channel: FP16 [M, K] -> FP32 [K]."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    out = torch.empty(K, dtype=torch.float32, device=x.device)
+    _check(lib().qoq_channel_absmax(_ptr(x), M, K, _ptr(out), _stream(x.device)))
+    return out
+
+
+def channel_order(salience):
+    """Permutation (INT32, on the device of `salience`): most salient channel first; sorted on the host."""
+    host = salience.detach().to("cpu", torch.float32).contiguous()
+    perm = torch.empty(host.numel(), dtype=torch.int32)
+    _check(lib().qoq_channel_order_host(host.data_ptr(), host.numel(), perm.data_ptr()))
+    return perm.to(salience.device)
+
+
+def gather_channels(src, perm):
+    _dev(src, torch.float16, "src")
+    _dev(perm, torch.int32, "perm")
+    rows, K = src.shape
+    dst = torch.empty_like(src)
+    _check(lib().qoq_gather_channels(_ptr(src), _ptr(perm), rows, K, _ptr(dst), _stream(src.device)))
+    return dst
+
+
+def quant_act_per_token_reordered(x, perm, want_rowsum=True, want_tx=False):
+    """quant_act_per_token of x[:, perm] in one pass."""
+    _dev(x, torch.float16, "x")
+    _dev(perm, torch.int32, "perm")
+    M, K = x.shape
+    _, qx, sx, rowsum, tx = _quant_outputs(M, K, x.device, False, want_rowsum, want_tx)
+    _check(lib().qoq_quant_act_per_token_reordered(_ptr(x), _ptr(perm), M, K, _ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(tx),
+                                                   _stream(x.device)))
+    return qx, sx, rowsum, tx
+
+
+def hadamard_rotate(src, block=None, out=None):
+    """src (I (x) H_block) / sqrt(block), rounded once to FP16; block defaults to the largest power of two dividing K."""
+    _dev(src, torch.float16, "src")
+    rows, K = src.shape
+    if block is None:
+        block = min(K & -K, 8192)
+    if out is None:
+        out = torch.empty_like(src)
+    _check(lib().qoq_hadamard_rotate(_ptr(src), rows, K, block, _ptr(out), _stream(src.device)))
+    return out

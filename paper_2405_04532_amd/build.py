@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqoq_w4a8.so")
 PROBE = os.path.join(HERE, "mfma_ceiling")          # stand-alone matrix-core ceiling probe (measurement aid)
-SOURCES = ["qoq_api.hip", "qoq_pack.hip", "qoq_act.hip", "qoq_gemm.hip", "qoq_kv4.hip"]
+SOURCES = ["qoq_api.hip", "qoq_pack.hip", "qoq_act.hip", "qoq_gemm.hip", "qoq_kv4.hip", "qoq_transforms.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions off (they have produced wrong results on these machines)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -181,6 +181,35 @@ __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* _
     quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
 }
 
+// The same with the input channels taken in a new order (activation-aware channel reordering, Section 4.3):
+// qx[m, j] = quantize(x[m, perm[j]]).  The gather is fused into the quantizer's single read of the row; the
+// per-token scale does not depend on the order.  Indices are clamped to the row.
+__global__ __launch_bounds__(kWide) void act_quant_reordered_kernel(const __half* __restrict__ x, const int32_t* __restrict__ perm,
+                                                                    int64_t K, int8_t* __restrict__ qx, __half* __restrict__ sx,
+                                                                    int32_t* __restrict__ rowsum, float* __restrict__ tx)
+{
+    __shared__ float s_f[kWide / 64];
+    __shared__ int s_i[kWide / 64];
+    const int64_t m = blockIdx.x;
+    const unsigned short* row = reinterpret_cast<const unsigned short*>(x + m * K);
+    const int chunks = (int)(K / 8);
+    uint4 v[kCache];
+#pragma unroll
+    for (int i = 0; i < kCache; ++i) {
+        const int c = (int)threadIdx.x + i * kWide;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (c < chunks) {
+            const int4 p0 = reinterpret_cast<const int4*>(perm)[2 * c], p1 = reinterpret_cast<const int4*>(perm)[2 * c + 1];
+            const int idx[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                w[j >> 1] |= (uint32_t)row[min(max(idx[j], 0), (int)K - 1)] << (16 * (j & 1));
+        }
+        v[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
+}
+
 // ---- producers with the quantization fused in (Section 5.1: the activations are quantized inside the
 // normalisation in front of the QKV / first FFN projection and inside the activation function in front of the
 // second FFN projection).  The producer is evaluated in FP64 and rounded once to FP16 (the exact bit routine
@@ -296,6 +325,16 @@ hipError_t launch_act_quant(const void* x_fp16, int64_t M, int64_t K, int8_t* qx
     }
     act_quant_kernel<<<dim3((unsigned)M), kThreads, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx,
                                                            static_cast<__half*>(sx), rowsum, tx);
+    return hipGetLastError();
+}
+
+hipError_t launch_act_quant_reordered(const void* x_fp16, const int32_t* perm, int64_t M, int64_t K, int8_t* qx, void* sx,
+                                      int32_t* rowsum, float* tx, hipStream_t s)
+{
+    if (M == 0) return hipSuccess;
+    if (K > kMaxCachedK) return hipErrorInvalidValue;
+    act_quant_reordered_kernel<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), perm, K, qx,
+                                                                  static_cast<__half*>(sx), rowsum, tx);
     return hipGetLastError();
 }
 

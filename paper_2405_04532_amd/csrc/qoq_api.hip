@@ -207,6 +207,59 @@ int qoq_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K, void* y_f
                                       static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
 
+int qoq_channel_absmax(const void* x_fp16, int64_t M, int64_t K, float* absmax, void* stream)
+{
+    if (M < 0 || M > (1 << 24) || K <= 0 || (K % 8) != 0 || K > (1 << 24)) return QOQ_ERR_SHAPE;
+    if (!absmax || (!x_fp16 && M > 0)) return QOQ_ERR_NULL;
+    if (!aligned16(x_fp16) || !aligned16(absmax)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_channel_absmax(x_fp16, M, K, absmax, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_channel_order_host(const float* salience_host, int64_t K, int32_t* perm_host)
+{
+    if (K <= 0 || K > (1 << 24)) return QOQ_ERR_SHAPE;
+    if (!salience_host || !perm_host) return QOQ_ERR_NULL;
+    qoq::channel_order_host(salience_host, K, perm_host);
+    return QOQ_OK;
+}
+
+int qoq_gather_channels(const void* src_fp16, const int32_t* perm, int64_t rows, int64_t K, void* dst_fp16, void* stream)
+{
+    if (rows < 0 || rows > (1 << 24) || K <= 0 || (K % 8) != 0 || K > (1 << 24)) return QOQ_ERR_SHAPE;
+    if (rows == 0) return QOQ_OK;
+    if (!src_fp16 || !perm || !dst_fp16) return QOQ_ERR_NULL;
+    if (src_fp16 == dst_fp16) return QOQ_ERR_SHAPE;        // not in place
+    if (!aligned16(src_fp16) || !aligned16(dst_fp16) || !aligned16(perm)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_gather_channels(src_fp16, perm, rows, K, dst_fp16, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_quant_act_per_token_reordered(const void* x_fp16, const int32_t* perm, int64_t M, int64_t K, int8_t* qx, void* sx_fp16,
+                                      int32_t* rowsum, float* tx, void* stream)
+{
+    if (M < 0 || M > (1 << 24) || K <= 0 || (K % qoq::kGroup) != 0 || K > qoq::fused_quant_max_k()) return QOQ_ERR_SHAPE;
+    if (M == 0) return QOQ_OK;
+    if (!x_fp16 || !perm || !qx || !sx_fp16) return QOQ_ERR_NULL;
+    if (!aligned16(x_fp16) || !aligned16(qx) || !aligned16(perm)) return QOQ_ERR_ALIGN;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_act_quant_reordered(x_fp16, perm, M, K, qx, sx_fp16, rowsum, tx, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_hadamard_rotate(const void* src_fp16, int64_t rows, int64_t K, int64_t block, void* dst_fp16, void* stream)
+{
+    if (rows < 0 || rows > 65535 || K <= 0 || K > (1 << 24) || block < 1 || block > qoq::hadamard_max_block() ||
+        (block & (block - 1)) != 0 || (K % block) != 0)
+        return QOQ_ERR_SHAPE;
+    if (rows == 0) return QOQ_OK;
+    if (!src_fp16 || !dst_fp16) return QOQ_ERR_NULL;
+    if (!arch_ok()) return QOQ_ERR_ARCH;
+    return qoq::launch_hadamard(src_fp16, rows, K, block, dst_fp16, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK
+                                                                                                                    : QOQ_ERR_HIP;
+}
+
 static bool kv4_shape_ok(int64_t B, int64_t Hkv, int64_t S_max, int64_t D)
 {
     return D == 128 && B >= 0 && Hkv > 0 && S_max > 0 && B <= (1 << 20) && Hkv <= 1024 && S_max <= (1 << 24) &&

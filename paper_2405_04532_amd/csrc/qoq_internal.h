@@ -46,6 +46,15 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k);
 hipError_t launch_zero(void* dst, size_t bytes, hipStream_t s);
 
+// Data-free offline transforms (channel reordering, Hadamard rotation).
+hipError_t launch_act_quant_reordered(const void* x_fp16, const int32_t* perm, int64_t M, int64_t K, int8_t* qx, void* sx,
+                                      int32_t* rowsum, float* tx, hipStream_t s);
+hipError_t launch_channel_absmax(const void* x, int64_t M, int64_t K, float* absmax, hipStream_t s);
+hipError_t launch_gather_channels(const void* src, const int32_t* perm, int64_t rows, int64_t K, void* dst, hipStream_t s);
+hipError_t launch_hadamard(const void* src, int64_t rows, int64_t K, int64_t block, void* dst, hipStream_t s);
+int hadamard_max_block();
+void channel_order_host(const float* salience, int64_t K, int32_t* perm);
+
 // KV4 cache (head dimension 128) and decode attention.
 size_t kv4_cache_bytes(int64_t B, int64_t Hkv, int64_t S_max);
 hipError_t launch_kv4_append(const void* k, const void* v, const int32_t* positions, int64_t B, int64_t T, int64_t Hkv,
