@@ -51,6 +51,8 @@ def main():
                     help="time the KV4 decode attention kernel instead (64 sequences x --seq tokens, Llama-2-7B heads)")
     ap.add_argument("--seq", type=int, default=1024, help="--attention: tokens in every sequence's cache")
     ap.add_argument("--family", type=str, default="llama2_7b", help="--attention: head configuration")
+    ap.add_argument("--ablation", action="store_true",
+                    help="dequantization-overhead ablation of the GEMM main loop and timings of the offline transforms")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -68,6 +70,9 @@ def main():
     torch.cuda.set_device(0)
     if args.attention:
         print(json.dumps(attention_bench(args, api, wl, dev)))
+        return
+    if args.ablation:
+        print(json.dumps(ablation_bench(args, api, wl, dev)))
         return
     M = args.m
     layers = list(wl.LLAMA2_7B.items())          # name -> (K, N)
@@ -276,6 +281,74 @@ def attention_bench(args, api, wl, dev):
                                   "sample": "%d of %d (sequence, head) pairs incl. their cache quantization, scaled to all pairs (%.1f s)"
                                             % (done, B * H, dt)}
     return result
+
+
+def ablation_bench(args, api, wl, dev):
+    """(1) What the level-2 dequantization costs in the main loop (the paper's dequantization-overhead ablation,
+    Section 6.4): the same layers and M through the g128 kernels (unpack + multiply-add + sign flip per operand) and
+    through the per-channel kernels (unpack only; the zero point moves to the epilogue) -- the difference is the
+    overhead.  (2) Run-time cost of the channel reordering (gather fused into the activation quantizer) and the
+    speed of the offline Hadamard rotation."""
+    import torch
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(reps):
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps          # us
+
+    M = args.m if args.m != 64 else 4096
+    rows = {}
+    tot = [0.0, 0.0]
+    for name, (K, N) in wl.LLAMA2_7B.items():
+        w = wl.layer_weights("llama2_7b", name, 1, dev)
+        x = wl.layer_activations("llama2_7b", name, M, 1, dev)
+        qx, sx, rowsum, _ = api.quant_act_per_token(x)
+        out = torch.empty((M, N), dtype=torch.float16, device=dev)
+        us = []
+        for mode in (0, 1):
+            blob = api.pack_weights(w, mode)
+            ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, mode), dev)
+            us.append(timed(lambda: api.w4a8_gemm(qx, sx, blob, N, mode, rowsum=rowsum, out=out, workspace=ws), 10))
+            del blob
+        rows[name] = {"g128_us": round(us[0], 2), "per_channel_us": round(us[1], 2), "overhead": round(us[0] / us[1] - 1, 4)}
+        tot[0] += us[0]; tot[1] += us[1]
+        del w, x
+    overhead = tot[0] / tot[1] - 1
+    # transforms
+    K, N = wl.LLAMA2_7B["gate_up"]
+    tr = {}
+    for m in (64, 4096):
+        x = wl.layer_activations("llama2_7b", "gate_up", m, 1, dev)
+        perm = api.channel_order(api.channel_absmax(x))
+        L = api.lib()
+        qx = torch.empty((m, K), dtype=torch.int8, device=dev); sx = torch.empty(m, dtype=torch.float16, device=dev)
+        s = torch.cuda.current_stream
+        plain = timed(lambda: L.qoq_quant_act_per_token(x.data_ptr(), m, K, qx.data_ptr(), sx.data_ptr(), None, None, s().cuda_stream), 20)
+        reord = timed(lambda: L.qoq_quant_act_per_token_reordered(x.data_ptr(), perm.data_ptr(), m, K, qx.data_ptr(), sx.data_ptr(), None, None, s().cuda_stream), 20)
+        tr["act_quant_m%d" % m] = {"plain_us": round(plain, 2), "reordered_us": round(reord, 2)}
+    w = wl.layer_weights("llama2_7b", "gate_up", 1, dev)
+    out = torch.empty_like(w)
+    us = timed(lambda: api.hadamard_rotate(w, K, out=out), 5)
+    tr["hadamard_rotate_%dx%d" % (N, K)] = {"us": round(us, 1), "gbs": round(4.0 * N * K / us / 1e3, 1)}
+    return {"metric": "level-2 dequantization overhead of the W4A8 g128 main loop (Llama-2-7B layers, M=%d)" % M,
+            "value": round(100.0 * overhead, 2), "unit": "%", "n_gpus": 1, "steps": 10, "warmup": 3,
+            "ms_per_step": round(tot[0] * 1e-3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+            "dtype": "int8", "data": "synthetic",
+            "config": {"workload": "llama2_7b_dequant_ablation_m%d" % M, "M": M,
+                       "ablation": "g128 kernels vs per-channel kernels (no level-2 multiply-add in the loop), GEMM launches only"},
+            "layers": rows, "transforms": tr}
 
 
 def cpu_baseline(M, xs, wl, budget_s=12.0):
