@@ -148,6 +148,10 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
             qrow[c] = make_uint2(packed[0], packed[1]);
         }
     }
+    if (!rowsum && !tx) {                          // group mode needs neither sum: no second reduction
+        if (threadIdx.x == 0) sx[m] = sxh;
+        return;
+    }
     for (int o = 32; o > 0; o >>= 1) {
         isum += __shfl_xor(isum, o, 64);
         fsum += __shfl_xor(fsum, o, 64);

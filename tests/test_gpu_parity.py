@@ -369,3 +369,12 @@ def test_fused_producers_reject_long_rows(api):
     with pytest.raises(api.QoqError) as e:
         api.rmsnorm_quant(x, g, 1e-5)
     assert e.value.status == 2
+
+
+def test_act_quant_without_token_sums(api):
+    """Group mode asks for neither row sums nor token sums: codes and scales are the same as with them."""
+    x = wl.make_activations(37, 4096, 77, DEV)
+    qx0, sx0, _, _ = api.quant_act_per_token(x, want_rowsum=True, want_tx=True)
+    qx1, sx1, rs1, tx1 = api.quant_act_per_token(x, want_rowsum=False, want_tx=False)
+    assert rs1 is None and tx1 is None
+    assert torch.equal(qx0, qx1) and torch.equal(sx0, sx1)
