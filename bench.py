@@ -56,7 +56,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(see DESIGN.md for how the path would shard)", file=sys.stderr)
+              "(column-parallel layers would split N, row-parallel ones K on group boundaries with an exact INT32 "
+              "reduce-scatter; none of that is built)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
