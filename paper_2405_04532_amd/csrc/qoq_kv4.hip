@@ -63,60 +63,101 @@ __device__ __forceinline__ int v_word_offset(int tin, int q4)
     return tile * 1024 + (kb * 16 + r) * 16 + (2 * u + h) * 4 + half * 2;
 }
 
-__device__ __forceinline__ float wave_min(float v) { for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64)); return v; }
-__device__ __forceinline__ float wave_max(float v) { for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64)); return v; }
-
 // ------------------------------------------------------------------------------------------
-// Append: one wave per (sequence, token, KV head, key|value) vector of 128 FP16 values; lane l holds elements
-// 2l, 2l+1.  Every decision is taken as the reference definition takes it: s = FP16((hi - lo) / 15) by one exact
-// rounding of the FP64 quotient, z and the codes by floor(t + 1/2) of FP64 quotients (a quotient of two FP16
-// values that is not exactly a half-integer is many orders of magnitude further from it than FP64's error).
+// Append: one wave per (sequence, KV head, aligned quad of token positions); 16 lanes per token, lane w of a token
+// holds its elements 8w .. 8w+7 (one 16-byte load), keys first, then values.  A quad of tokens is 4 x 64
+// contiguous bytes of key codes and ONE contiguous 256-byte block of value codes (the value layout groups the
+// four tokens of an operand k-block), which a complete quad assembles in LDS and writes with 16-byte stores; a
+// quad that this call covers only in part (a decode step appends a single token) writes its own 2-byte words.
+// Every decision is taken as the reference definition takes it: s = FP16((hi - lo) / 15) by one exact rounding
+// of the FP64 quotient, z and the codes by floor(t + 1/2) decided exactly from FP32 quotients (below).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void kv4_append_kernel(const __half* __restrict__ k, const __half* __restrict__ v,
                                                          const int32_t* __restrict__ positions, int64_t B, int64_t T,
-                                                         int64_t Hkv, int64_t S_max, uint8_t* __restrict__ cache)
+                                                         int64_t Hkv, int64_t S_max, int64_t quads, uint8_t* __restrict__ cache)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t vec = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);     // ((b * T + t) * Hkv + h) * 2 + which
-    if (vec >= B * T * Hkv * 2) return;
-    const int which = (int)(vec & 1);
-    const int64_t bth = vec >> 1;
-    const int64_t h = bth % Hkv, bt = bth / Hkv, t = bt % T, b = bt / T;
-    const int64_t pos = (int64_t)positions[b] + t;
-    if (pos < 0 || pos >= S_max) return;                                   // outside the cache: not written
-    const __half* src = (which ? v : k) + bth * kD;
-    const uint32_t raw = reinterpret_cast<const uint32_t*>(src)[lane];
-    const float x0 = __half2float(__ushort_as_half((unsigned short)(raw & 0xFFFFu)));
-    const float x1 = __half2float(__ushort_as_half((unsigned short)(raw >> 16)));
-    const float lo = fminf(wave_min(fminf(x0, x1)), 0.f), hi = fmaxf(wave_max(fmaxf(x0, x1)), 0.f);
-    uint16_t s_bits = double_to_half_rne(((double)hi - (double)lo) / 15.0);
-    if ((s_bits & 0x7FFFu) == 0) s_bits = 0x3C00u;                         // all-zero vector: s = 1
-    const double s = (double)__half2float(__ushort_as_half(s_bits));
-    const double zf = fmin(fmax(floor(-(double)lo / s + 0.5), 0.0), 15.0);
-    const uint32_t c0 = (uint32_t)fmin(fmax(floor((double)x0 / s + zf + 0.5), 0.0), 15.0);
-    const uint32_t c1 = (uint32_t)fmin(fmax(floor((double)x1 / s + zf + 0.5), 0.0), 15.0);
+    __shared__ uint4 s_block[4][16];                                       // per wave: the value codes of its quad
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 4, w = lane & 15;                                // token of the quad, 16-byte chunk of its row
+    const int64_t item = (int64_t)blockIdx.x * 4 + wave;                   // (b * Hkv + h) * quads + j
+    if (item >= B * Hkv * quads) return;
+    const int64_t j = item % quads, bh = item / quads, h = bh % Hkv, b = bh / Hkv;
+    const int64_t p0 = positions[b];
+    const int64_t pos = ((p0 >> 2) + j) * 4 + g;                           // floor(p0 / 4) also for negative p0
+    const int64_t t = pos - p0;
+    const bool valid = t >= 0 && t < T && pos >= 0 && pos < S_max;         // outside the call or the cache: not written
+    const bool whole = __builtin_amdgcn_ballot_w64(valid) == ~0ull;
+    if (__builtin_amdgcn_ballot_w64(valid) == 0) return;
     const int64_t n_pages = (S_max + kPageTokens - 1) / kPageTokens;
-    uint8_t* page = cache + ((b * Hkv + h) * n_pages + pos / kPageTokens) * kPageBytes + which * kHalfPage;
-    const int tin = (int)(pos % kPageTokens);
-    if (which == 0) {
-        // keys: dword w = lanes 4w .. 4w+3; lane 4w+j contributes pair j
-        const int j = lane & 3;
-        uint32_t word = (c0 << (4 * j)) | (c1 << (16 + 4 * j));
-        word |= __shfl_xor(word, 1, 64);
-        word |= __shfl_xor(word, 2, 64);
-        if (j == 0) reinterpret_cast<uint32_t*>(page + tin * (kD / 2))[lane >> 2] = word;
-    } else {
-        // values: 16-bit word i = lanes 2i, 2i+1 (elements 4i .. 4i+3)
-        const int j = (lane & 1) * 2;
-        uint32_t word = (c0 << (4 * j)) | (c1 << (4 * j + 4));
-        word |= __shfl_xor(word, 1, 64);
-        if ((lane & 1) == 0) *reinterpret_cast<uint16_t*>(page + v_word_offset(tin, lane >> 1)) = (uint16_t)word;
-    }
-    if (lane == 0) {
-        // the zero point is stored as the FP16 number -(1024 + z) (an exact integer), the constant the decode
-        // kernel adds to its unpacked codes
-        const uint16_t z_bits = __half_as_ushort(__float2half_rn(-1024.0f - (float)zf));
-        reinterpret_cast<uint32_t*>(page + kCodeBytes)[tin] = (uint32_t)s_bits | ((uint32_t)z_bits << 16);
+    const int64_t pos_c = valid ? pos : 0;
+    uint8_t* page = cache + (bh * n_pages + pos_c / kPageTokens) * kPageBytes;
+    const int tin = (int)(pos_c % kPageTokens);
+    const int64_t row = ((b * T + (valid ? t : 0)) * Hkv + h) * kD;
+
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        const uint4 raw = reinterpret_cast<const uint4*>((which ? v : k) + row)[w];
+        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            x[e] = __half2float(__ushort_as_half((unsigned short)(rw[e >> 1] >> (16 * (e & 1)))));
+        float lo = 0.f, hi = 0.f;                                          // the range is widened to contain 0
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            lo = fminf(lo, __shfl_xor(lo, o, 64));
+            hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+        }
+        uint16_t s_bits = double_to_half_rne(((double)hi - (double)lo) / 15.0);
+        if ((s_bits & 0x7FFFu) == 0) s_bits = 0x3C00u;                     // all-zero vector: s = 1
+        // floor(x / s + 1/2) from the correctly rounded FP32 quotient q of two FP16 numbers: its integer part and
+        // the comparison of its fractional part with 1/2 are both exact, and q lies on the same side of every
+        // half-integer as x / s does (an exact tie is representable and divides exactly; otherwise x / s is at
+        // least 2^-22 from a half-integer below 1 and 2^-12 above, at least four times FP32's rounding error
+        // there).  The integer zero point is added afterwards, in integers.
+        const float sc = __half2float(__ushort_as_half(s_bits));
+        auto round_half_up = [](float q) { const float f = floorf(q); return (int)f + (q - f >= 0.5f ? 1 : 0); };
+        const int zi = min(max(round_half_up(-lo / sc), 0), 15);
+        uint32_t c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c[e] = (uint32_t)min(max(round_half_up(x[e] / sc) + zi, 0), 15);
+        if (which == 0) {
+            // keys: dword w = elements 8w .. 8w+7, element 8w+2j in nibble j of the low half, 8w+2j+1 of the high half
+            uint32_t word = 0;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) word |= (c[2 * jj] << (4 * jj)) | (c[2 * jj + 1] << (16 + 4 * jj));
+            if (valid) reinterpret_cast<uint32_t*>(page + tin * (kD / 2))[w] = word;
+        } else {
+            // values: 16-bit words of element quads 2w (elements 8w .. 8w+3) and 2w+1
+            const uint32_t h0 = c[0] | (c[1] << 4) | (c[2] << 8) | (c[3] << 12);
+            const uint32_t h1 = c[4] | (c[5] << 4) | (c[6] << 8) | (c[7] << 12);
+            if (whole) {
+                // inside the quad's 256-byte block: chunk r = q4 % 16, dword 2 (q4 / 16) + (g >> 1), half g & 1
+                uint16_t* blk = reinterpret_cast<uint16_t*>(&s_block[wave][0]);
+                const int q4a = 2 * w, q4b = 2 * w + 1;
+                blk[(q4a & 15) * 8 + (2 * (q4a >> 4) + (g >> 1)) * 2 + (g & 1)] = (uint16_t)h0;
+                blk[(q4b & 15) * 8 + (2 * (q4b >> 4) + (g >> 1)) * 2 + (g & 1)] = (uint16_t)h1;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // the wave's own LDS writes, then its reads
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                if (lane < 16) {
+                    const int tin0 = tin & ~3;                             // lanes 0..15 are token 0 of the quad: tin % 4 == 0
+                    uint8_t* dst = page + kHalfPage + (tin0 >> 4) * 1024 + (((tin0 >> 2) & 3) * 16 + lane) * 16;
+                    *reinterpret_cast<uint4*>(dst) = s_block[wave][lane];
+                }
+            } else if (valid) {
+                *reinterpret_cast<uint16_t*>(page + kHalfPage + v_word_offset(tin, 2 * w)) = (uint16_t)h0;
+                *reinterpret_cast<uint16_t*>(page + kHalfPage + v_word_offset(tin, 2 * w + 1)) = (uint16_t)h1;
+            }
+        }
+        if (valid && w == 0) {
+            // the zero point is stored as the FP16 number -(1024 + z) (an exact integer), the constant the decode
+            // kernel adds to its unpacked codes
+            const uint16_t z_bits = __half_as_ushort(__float2half_rn(-1024.0f - (float)zi));
+            reinterpret_cast<uint32_t*>(page + which * kHalfPage + kCodeBytes)[tin] = (uint32_t)s_bits | ((uint32_t)z_bits << 16);
+        }
     }
 }
 
@@ -398,10 +439,11 @@ size_t kv4_cache_bytes(int64_t B, int64_t Hkv, int64_t S_max)
 hipError_t launch_kv4_append(const void* k, const void* v, const int32_t* positions, int64_t B, int64_t T, int64_t Hkv,
                              int64_t S_max, uint8_t* cache, hipStream_t s)
 {
-    const int64_t vecs = B * T * Hkv * 2;
-    if (vecs == 0) return hipSuccess;
-    kv4_append_kernel<<<(unsigned)((vecs + 3) / 4), 256, 0, s>>>(static_cast<const __half*>(k), static_cast<const __half*>(v), positions,
-                                                                  B, T, Hkv, S_max, cache);
+    if (B * T * Hkv == 0) return hipSuccess;
+    const int64_t quads = (T + 3) / 4 + 1;        // aligned quads of positions a run of T tokens can touch
+    const int64_t items = B * Hkv * quads;
+    kv4_append_kernel<<<(unsigned)((items + 3) / 4), 256, 0, s>>>(static_cast<const __half*>(k), static_cast<const __half*>(v), positions,
+                                                                   B, T, Hkv, S_max, quads, cache);
     return hipGetLastError();
 }
 

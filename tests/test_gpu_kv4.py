@@ -181,3 +181,18 @@ def test_kv4_argument_validation():
     assert L.qoq_kv4_attention_decode(q.data_ptr() + 2, cache.data_ptr(), seq.data_ptr(), 1, 4, 4, 128, 64, out.data_ptr(), None) == 3
     assert api.kv4_cache_bytes(1, 4, 64, 64) == 0
     assert api.kv4_cache_bytes(2, 4, 65) == 2 * 4 * 2 * 8704
+
+
+def test_append_many_vectors_bit_exact():
+    """Sixteen million elements (131072 key and value vectors), all codes, scales and zeros compared; half of the
+    vectors are scaled to magnitudes between 1e-3 and 1e3 so that many exponents of x / s occur."""
+    B, Hkv, S, D = 8, 8, 1024, 128
+    k, v = wl.make_kv(B, Hkv, S, D, 53, DEV)
+    gain = torch.pow(10.0, torch.linspace(-3, 3, S, device=DEV)).to(torch.float16)
+    v = (v.float() * gain[None, None, :, None].float()).to(torch.float16)
+    k[:, :, ::2] = (k[:, :, ::2].float() * gain[None, None, ::2, None].float()).to(torch.float16)
+    cache = api.kv4_new_cache(B, Hkv, S, DEV)
+    api.kv4_append(cache, k.permute(0, 2, 1, 3).contiguous(), v.permute(0, 2, 1, 3).contiguous(),
+                   torch.zeros(B, dtype=torch.int32, device=DEV), S)
+    torch.cuda.synchronize()
+    _check_cache(cache, B, Hkv, S, k.cpu().numpy(), v.cpu().numpy(), np.ones((B, S), dtype=bool))
