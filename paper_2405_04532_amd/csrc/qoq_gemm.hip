@@ -1379,13 +1379,22 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
     }
     if (tile_m <= 64) {
         const int64_t units = (N / 64) * G;
-        // one workgroup per CU; when the number of 64-channel blocks already fills most of the
-        // chip, one workgroup per block avoids the cross-workgroup reduction altogether
         const int64_t blocks = N / 64;
-        int64_t nwg = forced.split_k > 0 ? forced.split_k : (blocks >= 160 && blocks <= 256 ? blocks : 256);
         const int64_t max_wg = (units + 1) / 2;   // at least one full iteration (two units) each
+        int64_t nwg = forced.split_k > 0 ? forced.split_k : 256;   // one workgroup per CU, equal shares of the units
         if (nwg > max_wg) nwg = max_wg;
         if (nwg < 1) nwg = 1;
+        if (forced.split_k <= 0) {
+            // Alternative: whole blocks per workgroup (k of them), fewer workgroups but no partial tiles and no
+            // hand-over at the end, which costs about as much as 12 iterations of the LDS-staged kernel (3 of the
+            // register-streaming one).  Taken when its longer loop is cheaper than that.
+            const int64_t per_it = tile_m == 64 ? 2 : 8, slack = tile_m == 64 ? 12 : 2;
+            const int64_t it_auto = ((units + nwg - 1) / nwg + per_it - 1) / per_it;
+            const int64_t k = (blocks + 255) / 256;
+            const int64_t nwg_whole = (blocks + k - 1) / k;
+            const int64_t it_whole = k * ((G + per_it - 1) / per_it);
+            if ((units + nwg_whole - 1) / nwg_whole == k * G && it_whole <= it_auto + slack) nwg = nwg_whole;
+        }
         const int64_t upw = (units + nwg - 1) / nwg;
         split_k = (int)((units + upw - 1) / upw);
         return;
