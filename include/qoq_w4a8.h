@@ -210,6 +210,18 @@ int qoq_kv4_append(const void* k_fp16, const void* v_fp16, const int32_t* positi
                    int64_t Hkv, int64_t D, int64_t S_max, void* cache, void* stream);
 int qoq_kv4_attention_decode(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
                              int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* stream);
+/* The same attention with the sequence cut into ranges that separate workgroups process (a second, small launch
+ * adds them up): for problems with few (sequence, KV head) pairs -- grouped-query models at small batch -- whose
+ * single-pass launch leaves most of the chip idle.  The result obeys the same definition; the sums are formed in a
+ * different order.
+ *   workspace   device scratch of at least qoq_kv4_attention_workspace_bytes(...) bytes, 16-byte aligned, contents
+ *               irrelevant on entry and exit; two calls that overlap in time need separate workspaces.
+ * qoq_kv4_attention_workspace_bytes returns 0 when the library would not split this problem; the call then runs the
+ * single pass (workspace may be NULL).  A workspace that is too small: QOQ_ERR_WORKSPACE. */
+size_t qoq_kv4_attention_workspace_bytes(int64_t B, int64_t H, int64_t Hkv, int64_t D, int64_t S_max);
+int qoq_kv4_attention_decode_split(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
+                                   int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* workspace,
+                                   size_t workspace_bytes, void* stream);
 int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int64_t D, uint8_t* k_codes,
                    void* k_scale_fp16, void* k_zero_fp16, uint8_t* v_codes, void* v_scale_fp16, void* v_zero_fp16,
                    void* stream);

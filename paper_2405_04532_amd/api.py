@@ -66,6 +66,11 @@ _SIGNATURES = {
     "qoq_kv4_attention_decode": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                                 ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                                 ctypes.c_void_p, ctypes.c_void_p]),
+    "qoq_kv4_attention_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                            ctypes.c_int64]),
+    "qoq_kv4_attention_decode_split": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_kv4_unpack": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_void_p]),
@@ -307,15 +312,25 @@ def kv4_append(cache, k, v, positions, S_max):
     _check(lib().qoq_kv4_append(_ptr(k), _ptr(v), _ptr(positions), B, T, Hkv, D, S_max, _ptr(cache), _stream(k.device)))
 
 
-def kv4_attention_decode(q, cache, seq_lens, Hkv, S_max, out=None):
-    """out[b, h] = softmax(q[b, h] . K^ / sqrt(D)) V^ over the first seq_lens[b] tokens of the cache."""
+def kv4_attention_workspace_bytes(B, H, Hkv, S_max, D=128):
+    return int(lib().qoq_kv4_attention_workspace_bytes(B, H, Hkv, D, S_max))
+
+
+def kv4_attention_decode(q, cache, seq_lens, Hkv, S_max, out=None, workspace=None):
+    """out[b, h] = softmax(q[b, h] . K^ / sqrt(D)) V^ over the first seq_lens[b] tokens of the cache.
+    With a `workspace` (uint8 tensor of kv4_attention_workspace_bytes) the library may split long sequences
+    over several workgroups."""
     _dev(q, torch.float16, "q")
     _dev(seq_lens, torch.int32, "seq_lens")
     B, H, D = q.shape
     if out is None:
         out = torch.empty((B, H, D), dtype=torch.float16, device=q.device)
-    _check(lib().qoq_kv4_attention_decode(_ptr(q), _ptr(cache), _ptr(seq_lens), B, H, Hkv, D, S_max, _ptr(out),
-                                          _stream(q.device)))
+    if workspace is None:
+        _check(lib().qoq_kv4_attention_decode(_ptr(q), _ptr(cache), _ptr(seq_lens), B, H, Hkv, D, S_max, _ptr(out),
+                                              _stream(q.device)))
+    else:
+        _check(lib().qoq_kv4_attention_decode_split(_ptr(q), _ptr(cache), _ptr(seq_lens), B, H, Hkv, D, S_max, _ptr(out),
+                                                    _ptr(workspace), workspace.numel(), _stream(q.device)))
     return out
 
 

@@ -284,17 +284,37 @@ int qoq_kv4_append(const void* k_fp16, const void* v_fp16, const int32_t* positi
                                   static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
 
-int qoq_kv4_attention_decode(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
-                             int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* stream)
+static int kv4_decode_common(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H, int64_t Hkv,
+                             int64_t D, int64_t S_max, void* out_fp16, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!kv4_shape_ok(B, Hkv, S_max, D) || H <= 0 || H % Hkv != 0) return QOQ_ERR_SHAPE;
     if (H / Hkv > 16) return QOQ_ERR_SHAPE;     // the query heads of a KV head are the columns of one matrix instruction
     if (B == 0) return QOQ_OK;
     if (!q_fp16 || !cache || !seq_lens || !out_fp16) return QOQ_ERR_NULL;
-    if (!aligned16(q_fp16) || !aligned16(cache) || !aligned16(out_fp16)) return QOQ_ERR_ALIGN;
+    if (!aligned16(q_fp16) || !aligned16(cache) || !aligned16(out_fp16) || !aligned16(workspace)) return QOQ_ERR_ALIGN;
+    if (workspace && workspace_bytes < qoq::kv4_decode_workspace_bytes(B, H, Hkv, S_max)) return QOQ_ERR_WORKSPACE;
     if (!arch_ok()) return QOQ_ERR_ARCH;
-    return qoq::launch_kv4_decode(q_fp16, static_cast<const uint8_t*>(cache), seq_lens, B, H, Hkv, S_max, out_fp16,
-                                  static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+    return qoq::launch_kv4_decode(q_fp16, static_cast<const uint8_t*>(cache), seq_lens, B, H, Hkv, S_max, out_fp16, workspace,
+                                  workspace_bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
+}
+
+int qoq_kv4_attention_decode(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
+                             int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* stream)
+{
+    return kv4_decode_common(q_fp16, cache, seq_lens, B, H, Hkv, D, S_max, out_fp16, nullptr, 0, stream);
+}
+
+size_t qoq_kv4_attention_workspace_bytes(int64_t B, int64_t H, int64_t Hkv, int64_t D, int64_t S_max)
+{
+    if (!kv4_shape_ok(B, Hkv, S_max, D) || H <= 0 || H % Hkv != 0 || H / Hkv > 16) return 0;
+    return qoq::kv4_decode_workspace_bytes(B, H, Hkv, S_max);
+}
+
+int qoq_kv4_attention_decode_split(const void* q_fp16, const void* cache, const int32_t* seq_lens, int64_t B, int64_t H,
+                                   int64_t Hkv, int64_t D, int64_t S_max, void* out_fp16, void* workspace,
+                                   size_t workspace_bytes, void* stream)
+{
+    return kv4_decode_common(q_fp16, cache, seq_lens, B, H, Hkv, D, S_max, out_fp16, workspace, workspace_bytes, stream);
 }
 
 int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int64_t D, uint8_t* k_codes, void* k_scale_fp16,

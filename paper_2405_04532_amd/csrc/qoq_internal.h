@@ -62,7 +62,8 @@ hipError_t launch_kv4_append(const void* k, const void* v, const int32_t* positi
 hipError_t launch_kv4_unpack(const uint8_t* cache, int64_t B, int64_t Hkv, int64_t S_max, uint8_t* k_codes, void* k_s, void* k_z,
                              uint8_t* v_codes, void* v_s, void* v_z, hipStream_t s);
 hipError_t launch_kv4_decode(const void* q, const uint8_t* cache, const int32_t* seq_lens, int64_t B, int64_t H, int64_t Hkv,
-                             int64_t S_max, void* out, hipStream_t s);
+                             int64_t S_max, void* out, void* workspace, size_t workspace_bytes, hipStream_t s);
+size_t kv4_decode_workspace_bytes(int64_t B, int64_t H, int64_t Hkv, int64_t S_max);
 
 // Launch configuration the library picks for a problem (also sizes the workspace).
 struct GemmTuning { int tile_m, split_k; };  // 0 = let the heuristic decide

@@ -38,6 +38,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "qoq_fp16.h"
@@ -230,11 +231,15 @@ constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = 4;
 constexpr int kMaxRatio = 16;                            // query heads per KV head: the columns of one MFMA
 
-// NTL tiles of 16 tokens per chunk.
-template <int NTL>
+constexpr int kPartial = kD + 2;                         // floats per (split, head): 128 sums, the maximum, the weight sum
+
+// NTL tiles of 16 tokens per chunk.  SPLIT: the sequence is cut into gridDim.y contiguous ranges of chunks, one
+// workgroup each, whose (unnormalised sums, maximum, weight sum) go to the workspace for kv4_combine_kernel; used
+// when there are too few (sequence, KV head) pairs to fill the chip (grouped-query models).
+template <int NTL, bool SPLIT>
 __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void kv4_decode_kernel(const __half* __restrict__ q, const uint8_t* __restrict__ cache,
                                                                     const int32_t* __restrict__ seq_lens, int64_t Hkv, int R,
-                                                                    int64_t S_max, __half* __restrict__ out)
+                                                                    int64_t S_max, __half* __restrict__ out, float* __restrict__ ws)
 {
     constexpr int CH = 16 * NTL;                         // tokens per chunk (divides the page)
     __shared__ float s_acc[kDecodeWaves][kMaxRatio][kD];
@@ -246,11 +251,21 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
     const int64_t bh = blockIdx.x;                       // b * Hkv + hk
     const int64_t b = bh / Hkv, hk = bh % Hkv;
     const int64_t n_pages = (S_max + kPageTokens - 1) / kPageTokens;
-    const int L = (int)min((int64_t)max(seq_lens[b], 0), S_max);
+    const int L_seq = (int)min((int64_t)max(seq_lens[b], 0), S_max);
     const uint8_t* stream = cache + bh * n_pages * kPageBytes;
     __half* out_bh = out + (b * Hkv + hk) * R * kD;
-    if (L == 0) {                                        // empty cache: zero rows
-        for (int x = threadIdx.x; x < R * kD; x += kDecodeThreads) out_bh[x] = __float2half_rn(0.f);
+    float* ws_bh = SPLIT ? ws + ((size_t)bh * gridDim.y + blockIdx.y) * R * kPartial : nullptr;
+    // this workgroup's range of chunks [c0, c1) and the length it masks against
+    const int chunks_seq = (L_seq + CH - 1) / CH;
+    const int per_split = SPLIT ? (chunks_seq + (int)gridDim.y - 1) / (int)gridDim.y : chunks_seq;
+    const int c0 = SPLIT ? min(chunks_seq, (int)blockIdx.y * per_split) : 0;
+    const int c1 = SPLIT ? min(chunks_seq, c0 + per_split) : chunks_seq;
+    const int L = min(L_seq, c1 * CH);
+    if (c0 >= c1) {                                      // nothing to attend to: zero rows / an empty partial result
+        for (int x = threadIdx.x; x < R * (SPLIT ? kPartial : kD); x += kDecodeThreads) {
+            if (SPLIT) ws_bh[x] = x % kPartial == kD ? -1e30f : 0.f;
+            else out_bh[x] = __float2half_rn(0.f);
+        }
         return;
     }
 
@@ -295,7 +310,7 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = (f4){0.f, 0.f, 0.f, 0.f};
     const float kScale = 1.4426950408889634f * 0.08838834764831845f;      // log2(e) / sqrt(128)
-    const int n_chunks = (L + CH - 1) / CH;
+    const int n_chunks = c1;                             // chunk indices past the range are clamped to its last chunk
 
     const h2 k960 = {(_Float16)960.0f, (_Float16)960.0f};
     // One chunk of arithmetic.  MASKED: the chunk reaches past the end of the sequence (possibly entirely); the
@@ -378,8 +393,8 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
     // the last one re-reads the final chunk, masked).  Two buffers alternate, and every path through the loop
     // issues a fixed number of loads, so the compiler's wait counts are exact: while a chunk is computed the next
     // one stays in flight.  (With loads under a condition it waits for everything outstanding.)
-    const int n_iter = (n_chunks + kDecodeWaves - 1) / kDecodeWaves;
-    auto chunk_of = [&](int it) __attribute__((always_inline)) { return it * kDecodeWaves + wave; };
+    const int n_iter = (c1 - c0 + kDecodeWaves - 1) / kDecodeWaves;
+    auto chunk_of = [&](int it) __attribute__((always_inline)) { return c0 + it * kDecodeWaves + wave; };
     auto fetch = [&](Chunk& c, int it) __attribute__((always_inline)) { load_chunk(c, min(chunk_of(it), n_chunks - 1)); };
     Chunk A, Bf;
     fetch(A, 0);
@@ -424,8 +439,30 @@ __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(
             num = fmaf(s_acc[i][r][d], f, num);
             den = fmaf(s_l[i][r], f, den);
         }
-        out_bh[r * kD + d] = __float2half_rn(num / den);
+        if (SPLIT) {
+            ws_bh[r * kPartial + d] = num;
+            if (d == 0) { ws_bh[r * kPartial + kD] = mm; ws_bh[r * kPartial + kD + 1] = den; }
+        } else {
+            out_bh[r * kD + d] = __float2half_rn(num / den);
+        }
     }
+}
+
+// Second pass of the split variant: one workgroup of 128 threads per (sequence, query head).
+__global__ __launch_bounds__(kD) void kv4_combine_kernel(const float* __restrict__ ws, int NS, int R, __half* __restrict__ out)
+{
+    const int64_t bh = blockIdx.x / R;                   // (sequence, KV head)
+    const int r = (int)(blockIdx.x % R), d = threadIdx.x;
+    const float* part = ws + (size_t)bh * NS * R * kPartial + (size_t)r * kPartial;
+    float mm = -1e30f;
+    for (int s = 0; s < NS; ++s) mm = fmaxf(mm, part[(size_t)s * R * kPartial + kD]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < NS; ++s) {
+        const float f = __builtin_amdgcn_exp2f(part[(size_t)s * R * kPartial + kD] - mm);
+        num = fmaf(part[(size_t)s * R * kPartial + d], f, num);
+        den = fmaf(part[(size_t)s * R * kPartial + kD + 1], f, den);
+    }
+    out[(size_t)blockIdx.x * kD + d] = __float2half_rn(den > 0.f ? num / den : 0.f);
 }
 
 }  // namespace
@@ -458,16 +495,44 @@ hipError_t launch_kv4_unpack(const uint8_t* cache, int64_t B, int64_t Hkv, int64
     return hipGetLastError();
 }
 
+// Number of sequence ranges the split variant would use for this problem (1 = single pass).  Cutting the sequence pays only
+// while the (sequence, KV head) pairs alone leave compute units idle: measured at 8 KV heads, 1 x 8192 tokens goes from 51 to
+// 15 us with 8 ranges and 8 x 2048 from 16 to 11 us with 4, while at 64 sequences (512 pairs) every cut is slower than none
+// (18.6 us whole, 22.2 in 2 ranges, 25.5 in 4): each range repeats the set-up and adds a second launch that merges them.
+constexpr int64_t kDecodeFill = 256;
+int kv4_decode_splits(int64_t B, int64_t Hkv, int64_t S_max)
+{
+    const int64_t pairs = B * Hkv;
+    if (pairs <= 0) return 1;
+    int64_t ns = kDecodeFill / pairs;                    // about one workgroup per compute unit
+    ns = std::min<int64_t>(ns, 8);
+    ns = std::min<int64_t>(ns, S_max / 512);             // ranges of at least 512 tokens
+    return (int)std::max<int64_t>(ns, 1);
+}
+
+size_t kv4_decode_workspace_bytes(int64_t B, int64_t H, int64_t Hkv, int64_t S_max)
+{
+    const int ns = kv4_decode_splits(B, Hkv, S_max);
+    return ns <= 1 ? 0 : (size_t)(B * H) * ns * kPartial * sizeof(float);
+}
+
 hipError_t launch_kv4_decode(const void* q, const uint8_t* cache, const int32_t* seq_lens, int64_t B, int64_t H, int64_t Hkv,
-                             int64_t S_max, void* out, hipStream_t s)
+                             int64_t S_max, void* out, void* workspace, size_t workspace_bytes, hipStream_t s)
 {
     if (B == 0) return hipSuccess;
-    const dim3 grid((unsigned)(B * Hkv));
     const __half* qh = static_cast<const __half*>(q);
     __half* oh = static_cast<__half*>(out);
     const int R = (int)(H / Hkv);
     if (R < 1 || R > kMaxRatio) return hipErrorInvalidValue;
-    kv4_decode_kernel<2><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, R, S_max, oh);
+    const int ns = kv4_decode_splits(B, Hkv, S_max);
+    if (workspace && ns > 1 && workspace_bytes >= kv4_decode_workspace_bytes(B, H, Hkv, S_max)) {
+        float* ws = static_cast<float*>(workspace);
+        const dim3 grid((unsigned)(B * Hkv), (unsigned)ns);
+        kv4_decode_kernel<2, true><<<grid, kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, R, S_max, oh, ws);
+        kv4_combine_kernel<<<(unsigned)(B * H), kD, 0, s>>>(ws, ns, R, oh);
+        return hipGetLastError();
+    }
+    kv4_decode_kernel<2, false><<<dim3((unsigned)(B * Hkv)), kDecodeThreads, 0, s>>>(qh, cache, seq_lens, Hkv, R, S_max, oh, nullptr);
     return hipGetLastError();
 }
 

@@ -92,7 +92,7 @@ def test_append_outside_the_cache_is_dropped():
     assert cache.numel() == before.numel()
 
 
-def _attention_case(B, H, Hkv, S_max, lens, seed):
+def _attention_case(B, H, Hkv, S_max, lens, seed, split=False):
     D = 128
     k, v = wl.make_kv(B, Hkv, S_max, D, seed, DEV)
     q = wl.make_queries(B, H, D, seed, DEV)
@@ -100,7 +100,12 @@ def _attention_case(B, H, Hkv, S_max, lens, seed):
     api.kv4_append(cache, k.permute(0, 2, 1, 3).contiguous(), v.permute(0, 2, 1, 3).contiguous(),
                    torch.zeros(B, dtype=torch.int32, device=DEV), S_max)
     seq = torch.tensor(lens, dtype=torch.int32, device=DEV)
-    out = api.kv4_attention_decode(q, cache, seq, Hkv, S_max)
+    ws = None
+    if split:
+        nbytes = api.kv4_attention_workspace_bytes(B, H, Hkv, S_max)
+        assert nbytes > 0, "this shape was meant to exercise the split variant"
+        ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=DEV)     # contents on entry are irrelevant (NaN here)
+    out = api.kv4_attention_decode(q, cache, seq, Hkv, S_max, workspace=ws)
     torch.cuda.synchronize()
     o = _check_cache(cache, B, Hkv, S_max, k.cpu().numpy(), v.cpu().numpy(), np.ones((B, S_max), dtype=bool))
     ref = kv4.attention_decode(q.cpu().numpy(), *o, np.array(lens))
@@ -124,6 +129,32 @@ def test_attention_ragged_lengths(H, Hkv):
     lens = [0, 1, 3, 15, 16, 17, 63, 64, 65, 130, 200]
     got, ref = _attention_case(len(lens), H, Hkv, 200, lens, 40 + H + Hkv)
     assert not got[0].any()                                     # empty sequence: zero rows
+
+
+@pytest.mark.parametrize("H,Hkv", [(4, 1), (8, 2), (6, 6)])
+def test_attention_split_over_workgroups(H, Hkv):
+    """Few (sequence, KV head) pairs and long caches: the sequence is cut into ranges; lengths that leave ranges
+    empty, partly filled, and exactly filled."""
+    lens = [0, 1, 31, 32, 33, 127, 128, 129, 500, 1000, 1023, 1024]
+    _attention_case(len(lens), H, Hkv, 1024, lens, 70 + H)
+    got, ref = _attention_case(len(lens), H, Hkv, 1024, lens, 70 + H, split=True)
+    assert not got[0].any()
+    # the two variants compute the same sums in a different order
+    k, v = wl.make_kv(2, Hkv, 2000, 128, 71, DEV)
+    q = wl.make_queries(2, H, 128, 71, DEV)
+    cache = api.kv4_new_cache(2, Hkv, 2000, DEV)
+    api.kv4_append(cache, k.permute(0, 2, 1, 3).contiguous(), v.permute(0, 2, 1, 3).contiguous(),
+                   torch.zeros(2, dtype=torch.int32, device=DEV), 2000)
+    seq = torch.tensor([2000, 777], dtype=torch.int32, device=DEV)
+    ws = torch.zeros(api.kv4_attention_workspace_bytes(2, H, Hkv, 2000), dtype=torch.uint8, device=DEV)
+    a = api.kv4_attention_decode(q, cache, seq, Hkv, 2000).float()
+    b = api.kv4_attention_decode(q, cache, seq, Hkv, 2000, workspace=ws).float()
+    assert torch.allclose(a, b, rtol=2e-3, atol=2e-3)
+    # a workspace that is too small is refused
+    L = api.lib()
+    out = torch.empty_like(q)
+    assert L.qoq_kv4_attention_decode_split(q.data_ptr(), cache.data_ptr(), seq.data_ptr(), 2, H, Hkv, 128, 2000, out.data_ptr(),
+                                            ws.data_ptr(), 16, None) == 4
 
 
 def test_attention_long_sequence_many_pages():
