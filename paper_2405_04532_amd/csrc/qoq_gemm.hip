@@ -367,8 +367,11 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     // consumers run separate, tight loops that meet at the same barriers: with one loop for both roles every
     // wave branched around the other role's code, and the producers' ten copies plus that branching set
     // the pace of the whole workgroup (measured with s_memtime probes).
-    constexpr int kWRing = MF == 4 ? 10 : 12;
-    constexpr int kARing = 3;
+    // Ring depths: three slots are the minimum of the scheme (one read, one landing, one in flight).  Depths of
+    // 3 to 10 weight units per wave were measured to stream equally fast (the loop is not limited by bytes in
+    // flight), and a deep ring only lengthens the burst of copies that must land before the first iteration.
+    constexpr int kWRing = 4;
+    constexpr int kARing = 4;
     constexpr int kABlocks = 2 * MF;                                  // 1 KiB blocks (m-fragment, k-step) per group
     constexpr int kAHalf = kABlocks / 2;                              // activation blocks per producer wave
     static_assert(kWRing - 2 < 64 && (kARing - 2) * (kAHalf + 1) < 64, "vmcnt range");
