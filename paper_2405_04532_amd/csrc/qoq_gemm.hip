@@ -847,6 +847,9 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 //     CF = 4, waves 2 x 2 : 256 tokens x 256 channels  (large problems: fewest bytes per MFMA)
 //     CF = 2, waves 1 x 4 : 128 tokens x 256 channels  (few tokens)
 //     CF = 2, waves 2 x 2 : 256 tokens x 128 channels  (few channels)
+//     CF = 3, waves 2 x 2 : 256 tokens x 192 channels  (tile counts that fill the CUs where 256 x 256 leaves a
+//                           quarter idle, e.g. N = 12288).  A wave's three 32-row fragments are then every second
+//                           one of the tile's six, so that both waves see the same half of every 64-channel block.
 // With one wave per SIMD nothing but that wave's own instruction stream keeps the matrix pipe busy, so the
 // main loop is software pipelined by hand into "chunks" of one MFMA (32 cycles) plus what fits in its
 // shadow: a quarter of the dequantization of a LATER weight operand (one operand = 4 dwords, reused by the
@@ -877,7 +880,9 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     constexpr int kACopies = kABlocks / 4, kWCopies = kUnits / 4;     // per wave
     constexpr int NB = 2 * CF;                      // blocks (k32-step jj, channel fragment cf) per half-stage
     constexpr int NC = 4 * NB;                      // chunks per half-stage
-    constexpr int BAR = CF == 4 ? 16 : 4;           // chunk in front of which the half-stage's barrier sits
+    constexpr int BAR = CF == 4 ? 16 : CF == 3 ? 12 : 4;   // chunk in front of which the half-stage's barrier sits
+    constexpr int kFragStep = (CF & 1) ? WN : 1;    // distance, in 32-row fragments, between a wave's fragments
+    static_assert(!(CF & 1) || WN == 2, "an odd CF interleaves the fragments of two waves");
     __shared__ __attribute__((aligned(16))) char aring[kASlots * kASlotBytes];
     __shared__ __attribute__((aligned(16))) char wring[kWSlots * kWSlotBytes];
     __shared__ __attribute__((aligned(16))) char mring[kWSlots * kMSlotBytes];
@@ -927,7 +932,10 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         }
     }
     const uint32_t w_voff = (uint32_t)lane * 16u;
-    const uint32_t m_voff = (uint32_t)(lane & (kWCopies * 8 - 1)) * 4u;   // 32 B of metadata per unit
+    // metadata: 32 B per unit; lane l copies dword l % 8 of the wave's unit l / 8 (units past N repeat the last one,
+    // lanes past the wave's units repeat its last dword)
+    const int m_lane = min(lane, kWCopies * 8 - 1);
+    const uint32_t m_voff = (uint32_t)min(nf_base + wave * kWCopies + (m_lane >> 3), nf_total - 1) * 32u + (uint32_t)(m_lane & 7) * 4u;
     const uint32_t a_dst = (uint32_t)(uintptr_t)&aring[0] + (uint32_t)(wave * kACopies) * 1024u;
     const uint32_t w_dst = (uint32_t)(uintptr_t)&wring[0] + (uint32_t)(wave * kWCopies) * 1024u;
     const uint32_t m_dst = (uint32_t)(uintptr_t)&mring[0] + (uint32_t)wave * 256u;
@@ -936,7 +944,7 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 #pragma unroll
     for (int u = 0; u < kWCopies; ++u)   // units past N repeat the last one; their results are never stored
         wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * kWCopies + u, nf_total - 1) * G * 1024;
-    const char* mrow = reinterpret_cast<const char*>(p.meta) + (size_t)min(nf_base + wave * kWCopies, nf_total - kWCopies) * 32;
+    const char* mrow = reinterpret_cast<const char*>(p.meta);
     const size_t m_g_stride = (size_t)nf_total * 32;
     int ca = 2 * g_first, cw = g_first;   // next half-stage / group to copy; past the end of the slice the last one is copied again into a free slab
     const int ca_last = 2 * (g_first + Gs) - 1, cw_last = g_first + Gs - 1;
@@ -992,6 +1000,7 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
 
     // ---- compute role ---------------------------------------------------------------------------
     const int wm = wave / WN, wn = wave % WN;            // 128-token part, (32 * CF)-channel part of the tile
+    const int frag0 = (CF & 1) ? wn : wn * CF;           // first 32-row fragment of the wave inside the tile
     const int r32 = lane & 31, kb2 = lane >> 5;
     v16i acc[CF][4];                                     // [channel fragment][token fragment]
 #pragma unroll
@@ -1011,14 +1020,14 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     for (int jj = 0; jj < 2; ++jj) {
         a_rd[jj] = (uint32_t)((wm * 8 + (r32 >> 4)) * 1024 + (4 * arow + (((2 * jj + kb2) & 3) ^ ah)) * 16);
         //   weights, channel fragment cf (+ cf * 2048; 32 rows = units 2cf, 2cf+1), both halves in one lane word:
-        //   unit wn*2*CF + 2cf + r32/16, lane word ((2jj + kb2) % 4) * 16 + r32 % 16
-        w_rd[jj] = (uint32_t)((wn * 2 * CF + (r32 >> 4)) * 1024 + ((((2 * jj + kb2) & 3) * 16) + (r32 & 15)) * 16);
+        //   unit 2 * (frag0 + cf * kFragStep) + r32/16, lane word ((2jj + kb2) % 4) * 16 + r32 % 16
+        w_rd[jj] = (uint32_t)((2 * frag0 + (r32 >> 4)) * 1024 + ((((2 * jj + kb2) & 3) * 16) + (r32 & 15)) * 16);
     }
-    //   metadata of unit u = wn*2*CF + 2cf + r32/16: in the 256 B of copying wave u / kWCopies, 32 B per unit
+    //   metadata of that unit u: in the 256 B of copying wave u / kWCopies, 32 B per unit
     uint32_t m_rd[CF];
 #pragma unroll
     for (int cf = 0; cf < CF; ++cf) {
-        const int u = wn * 2 * CF + 2 * cf + (r32 >> 4);
+        const int u = 2 * (frag0 + cf * kFragStep) + (r32 >> 4);
         m_rd[cf] = (uint32_t)((u / kWCopies) * 256 + ((u % kWCopies) * 16 + (r32 & 15)) * 2);
     }
 
@@ -1026,7 +1035,7 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         return as_v4i(*reinterpret_cast<const uint4*>(aring + slab + a_rd[jj] + tf * 2048));
     };
     auto lds_w = [&](uint32_t slab, int blk) {           // lane word (both halves) of block blk = (jj, cf)
-        return *reinterpret_cast<const uint4*>(wring + slab + w_rd[blk / CF] + (blk % CF) * 2048);
+        return *reinterpret_cast<const uint4*>(wring + slab + w_rd[blk / CF] + (blk % CF) * (2048 * kFragStep));
     };
     auto lds_m = [&](uint32_t slab, int cf) {
         return (uint32_t)*reinterpret_cast<const uint16_t*>(mring + slab + m_rd[cf]);
@@ -1137,6 +1146,26 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                             B[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x01010101u);
                         }
                     }
+                } else if (CF == 3) {
+                    // 24 chunks, barrier in front of chunk 12.  Lane words: 3..5 of this group during blocks 0..2 of
+                    // the first half-stage, 0..2 of the next group during blocks 3..5 of the second (each register is
+                    // free by then: block b's second half is dequantized one block ahead).  Activations of the next
+                    // half-stage in the eight chunks after the barrier (a0 is last used in block 2).  Level-2 constants
+                    // of the next group: S[cf] is last used in chunk 4 * (cf + 2) + 1 and next in chunk 4 * cf + 19.
+                    if (tf == 0) {
+                        if (s == 0 && b < 3) rq[b + 3] = lds_w(w_this, b + 3);
+                        if (s == 1 && b >= 3) rq[b - 3] = lds_w(w_next, b - 3);
+                    }
+                    if (c >= 12 && c <= 15) a0[c - 12] = lds_a(a_nxt, 0, c - 12);
+                    if (c >= 16 && c <= 19) a1[1 - s][c - 16] = lds_a(a_nxt, 1, c - 16);
+                    if (GROUP && s == 1) {
+                        if (b == 3 && tf < 3) mt[tf] = lds_m(m_nxt, tf);
+                        const int pc = c == 16 ? 0 : c == 18 ? 1 : c == 20 ? 2 : -1;
+                        if (pc >= 0) {
+                            S[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x0c000c00u);
+                            B[pc] = __builtin_amdgcn_perm(mt[pc], mt[pc], 0x01010101u);
+                        }
+                    }
                 } else {
                     if (s == 1) {                        // lane words of the next group, each once its register is free
                         const int e = c == 4 ? 0 : c == 5 ? 1 : c == 8 ? 2 : c == 12 ? 3 : -1;
@@ -1221,6 +1250,62 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     // i.e. logical channels 64*(cf/2) + 32*(v4%2) + 16*hb + 8*(cf%2) + 4*(v4/2) + v%4 of the wave's 32*CF: for fixed
     // (cf/2, v4%2) the four pieces (cf%2, v4/2) are 16 consecutive channels = one 32-byte row segment per token.
     const int hb = kb2;
+    if constexpr (CF & 1) {
+        // Interleaved fragments: the wave's fragment cf is half `wn` of the tile's 64-channel block cf, so for fixed
+        // (cf, v4 % 2) the two pieces v4 / 2 are 8 consecutive channels = one 16-byte row segment per token.
+#pragma unroll
+        for (int cf = 0; cf < CF; ++cf) {
+#pragma unroll
+            for (int vl = 0; vl < 2; ++vl) {
+                const int nl = 64 * cf + 32 * vl + 16 * hb + 8 * wn;   // first of the 8 channels, inside the tile
+                const int n8 = n_base + nl;
+                if (n8 >= p.N) continue;                 // N % 16 == 0: an 8-channel segment is all in or all out
+                float sn[8];
+                int zn[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) { sn[x] = OUT == OUT_FP16 ? __half2float(e_sn[nl + x]) : 0.f; zn[x] = GROUP ? 0 : (int)e_zn[nl + x]; }
+#pragma unroll
+                for (int tf = 0; tf < 4; ++tf) {
+                    const int ml = wm * 128 + tf * 32 + r32;
+                    const int m = m_base + ml;
+                    if (m >= p.M) continue;
+                    const float sxm = OUT == OUT_FP16 ? __half2float(e_sx[ml]) : 0.f;
+                    const int rs = GROUP ? 0 : e_rs[ml];
+                    const bool token_sum = !GROUP && OUT == OUT_FP16 && p.token_sum;   // Eq. 7 form, rs = bits of t_X
+                    const float txm = __int_as_float(rs);
+                    int t[8];
+#pragma unroll
+                    for (int piece = 0; piece < 2; ++piece) {
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            t[4 * piece + x] = acc[cf][tf][4 * (2 * piece + vl) + x];
+                            if (!GROUP && !token_sum) t[4 * piece + x] -= zn[4 * piece + x] * rs;
+                        }
+                    }
+                    if constexpr (OUT == OUT_I32) {
+                        int4* dst = reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n8);
+                        dst[0] = make_int4(t[0], t[1], t[2], t[3]);
+                        dst[1] = make_int4(t[4], t[5], t[6], t[7]);
+                    } else {
+                        uint32_t h[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            float ra = (float)t[2 * j] * (sxm * sn[2 * j]), rb = (float)t[2 * j + 1] * (sxm * sn[2 * j + 1]);
+                            if (token_sum) {
+                                ra -= txm * ((float)zn[2 * j] * sn[2 * j]);
+                                rb -= txm * ((float)zn[2 * j + 1] * sn[2 * j + 1]);
+                            }
+                            const __half lo = __float2half_rn(ra);
+                            const __half hi = __float2half_rn(rb);
+                            h[j] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
+                        }
+                        *reinterpret_cast<uint4*>(p.out16 + (size_t)m * p.N + n8) = make_uint4(h[0], h[1], h[2], h[3]);
+                    }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int ch = 0; ch < CF / 2; ++ch) {
 #pragma unroll
@@ -1301,7 +1386,8 @@ void launch_mma(const GemmDev& p, bool fp16, hipStream_t s)
 }
 
 // tile_m selects the kernel and its shape: 16 / 32 / 64 = streaming kernel with that many tokens per tile;
-// 128 = compute-bound kernel, 256 tokens x 256 channels; 129 = 128 tokens x 256 channels; 130 = 256 x 128.
+// 128 = compute-bound kernel, 256 tokens x 256 channels; 129 = 128 tokens x 256 channels; 130 = 256 x 128;
+// 131 = 256 x 192.
 template <bool GROUP>
 void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
@@ -1314,6 +1400,8 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
         launch_mma<GROUP, 2, 1>(p, fp16, s);
     } else if (tile_m == 130) {
         launch_mma<GROUP, 2, 2>(p, fp16, s);
+    } else if (tile_m == 131) {
+        launch_mma<GROUP, 3, 2>(p, fp16, s);
     } else {
         launch_mma<GROUP, 4, 2>(p, fp16, s);
     }
@@ -1322,13 +1410,13 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 }  // namespace
 
 // ---- launch configuration --------------------------------------------------------------------------
-// tile_m: 16 / 32 / 64 = streaming kernel with that many tokens per tile; 128 / 129 / 130 = compute-bound kernel
-// with 256 x 256, 128 x 256, 256 x 128 (tokens x channels) tiles.  split_k: streaming kernel = number of
+// tile_m: 16 / 32 / 64 = streaming kernel with that many tokens per tile; 128 / 129 / 130 / 131 = compute-bound
+// kernel with 256 x 256, 128 x 256, 256 x 128, 256 x 192 (tokens x channels) tiles.  split_k: streaming kernel = number of
 // workgroups the unit stream is dealt to (per token tile); compute-bound kernel = k-slices per tile.
 static void mma_tile_shape(int tile_m, int64_t& tm, int64_t& tn)
 {
     tm = tile_m == 129 ? 128 : 256;
-    tn = tile_m == 130 ? 128 : 256;
+    tn = tile_m == 130 ? 128 : tile_m == 131 ? 192 : 256;
 }
 static int64_t mma_tiles(int64_t M, int64_t N, int tile_m)
 {
@@ -1349,16 +1437,20 @@ static int mma_split(int64_t M, int64_t N, int64_t G, int tile_m, int forced_spl
     const int64_t gps = (G + S - 1) / S;
     return (int)((G + gps - 1) / gps);
 }
-// Cost model fitted to measurements on MI355X, in microseconds: a workgroup needs about 8 us of prologue and
-// epilogue plus 1.15 us per group with 256 x 256 tiles (0.72 us with the half-size tiles); workgroups run in
-// rounds of one per CU; a split adds about 30 us (14 us) for the hand-over.
+// Cost model fitted to measurements on MI355X (all four shapes on the Llama-2-7B and Llama-3-70B layers at
+// M = 512 ... 4096, within 5%), in microseconds: workgroups run in rounds of one per CU; a workgroup needs about
+// 8 us of prologue and epilogue plus, per group, a time that grows with the share of the CUs that are busy (the
+// clock drops as more matrix cores run): light-load time x (1 + 0.45 load^2); a split adds the hand-over.
 static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 {
     S = mma_split(M, N, G, tile_m, 0);
     const int64_t wgs = mma_tiles(M, N, tile_m) * S;
-    const double per_group = tile_m == 128 ? 1.15 : 0.72;
-    return (double)((wgs + 255) / 256) * (8.0 + per_group * (double)((G + S - 1) / S)) +
-           (S > 1 ? (tile_m == 128 ? 30.0 : 14.0) : 0.0);
+    const int64_t rounds = (wgs + 255) / 256;
+    const double load = (double)wgs / (double)(rounds * 256);
+    const double light = tile_m == 128 ? 1.18 : tile_m == 131 ? 0.92 : tile_m == 130 ? 0.64 : 0.62;
+    const double per_group = light * (1.0 + 0.45 * load * load);
+    return (double)rounds * (8.0 + per_group * (double)((G + S - 1) / S)) +
+           (S > 1 ? (tile_m == 128 ? 30.0 : tile_m == 131 ? 22.0 : 14.0) : 0.0);
 }
 
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
@@ -1366,18 +1458,18 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
     const int64_t G = K / kGroup;
     tile_m = forced.tile_m ? forced.tile_m : (M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128);
     if (!forced.tile_m && M > 64) {
-        // Cheapest of the three tile shapes of the compute-bound kernel and, for a few hundred tokens, the
+        // Cheapest of the four tile shapes of the compute-bound kernel and, for a few hundred tokens, the
         // streaming kernel run once per 64-token tile (it re-reads the weights but spreads K over the whole
-        // chip): streaming ~ 6 + m_tiles * max(7, weight MB / 2.3) microseconds.
+        // chip): streaming ~ 4 + m_tiles * max(7.5, weight MB / 2.6) microseconds.
         int S;
         double best = mma_cost(M, N, G, 128, S);
-        for (int cand = 129; cand <= 130; ++cand) {
+        for (int cand = 129; cand <= 131; ++cand) {
             const double c = mma_cost(M, N, G, cand, S);
-            if (c < 0.95 * best) { best = c; tile_m = cand; }
+            if (c < 0.98 * best) { best = c; tile_m = cand; }
         }
         const double m_tiles = (double)((M + 63) / 64);
         const double w_mb = (double)K * (double)N / 2.0e6;
-        const double est_stream = 6.0 + m_tiles * (w_mb / 2.3 > 7.0 ? w_mb / 2.3 : 7.0);
+        const double est_stream = 4.0 + m_tiles * (w_mb / 2.6 > 7.5 ? w_mb / 2.6 : 7.5);
         if (est_stream < 0.9 * best) tile_m = 64;
     }
     if (tile_m <= 64) {

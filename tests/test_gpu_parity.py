@@ -147,7 +147,8 @@ def test_group_ragged_m(api, M):
 
 
 @pytest.mark.parametrize("tile_m,split_k", [(16, 1), (32, 1), (64, 1), (128, 1), (16, 3), (64, 5), (128, 2), (32, 9),
-                                            (64, 2), (128, 9), (129, 1), (130, 1), (129, 3), (130, 2), (129, 9), (130, 4)])
+                                            (64, 2), (128, 9), (129, 1), (130, 1), (129, 3), (130, 2), (129, 9), (130, 4),
+                                            (131, 1), (131, 2), (131, 5)])
 def test_group_forced_variants(api, tile_m, split_k):
     run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
 
@@ -163,7 +164,7 @@ def test_group_several_tiles_all_axes(api):
     run_group_case(api, 300, 1088, 2048, seed=11)
 
 
-@pytest.mark.parametrize("tile_m,split_k", [(128, 1), (129, 1), (130, 1), (129, 2), (130, 3)])
+@pytest.mark.parametrize("tile_m,split_k", [(128, 1), (129, 1), (130, 1), (129, 2), (130, 3), (131, 1), (131, 2)])
 def test_group_compute_kernel_shapes_ragged(api, tile_m, split_k):
     """Every tile shape of the compute-bound kernel on a problem ragged in tokens and channels (M % 128 != 0,
     N % 128 != 0) with several tiles on both axes and, with a split, odd slice lengths (17 groups)."""
@@ -212,7 +213,7 @@ def test_per_channel_gemm(api, M, N, K):
     ref = ogemm.forward_per_channel(_np(w), _np(x))
     blob = api.pack_weights(w, api.QOQ_PER_CHANNEL)
     qx, sx, rowsum, _ = api.quant_act_per_token(x)
-    for tile_m, split_k in [(0, 0), (32, 3), (128, 1), (129, 1), (130, 1), (129, 2), (128, 3)]:
+    for tile_m, split_k in [(0, 0), (32, 3), (128, 1), (129, 1), (130, 1), (131, 1), (129, 2), (128, 3), (131, 3)]:
         api.set_gemm_config(tile_m, split_k)
         try:
             acc = api.w4a8_gemm_i32(qx, blob, N, api.QOQ_PER_CHANNEL, rowsum=rowsum)
@@ -289,7 +290,8 @@ def test_linear_equals_quant_then_gemm(api, M, N, K, mode):
 
 # ---------------------------------------------------------------------------- token-sum form of the per-channel epilogue
 @pytest.mark.parametrize("M,N,K,cfg", [(16, 256, 256, (0, 0)), (64, 512, 4096, (0, 0)), (70, 192, 640, (32, 3)),
-                                       (200, 448, 1152, (128, 1)), (200, 448, 1152, (129, 2)), (300, 320, 2048, (130, 1))])
+                                       (200, 448, 1152, (128, 1)), (200, 448, 1152, (129, 2)), (300, 320, 2048, (130, 1)),
+                                       (300, 320, 2048, (131, 1)), (200, 448, 1152, (131, 2)), (257, 256, 640, (131, 1))])
 def test_per_channel_token_sum_epilogue(api, M, N, K, cfg):
     """out = acc * sx * sw - t_X * (z * sw) with t_X summed over the unquantized activations (Section 5.2.2),
     against the oracle's FP64 form.  Tolerance: the stated 1e-3 relative on the result plus the FP32 rounding
