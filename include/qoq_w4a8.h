@@ -233,6 +233,10 @@ int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int
  * streaming kernel the number of workgroups the stream of work units is dealt to.  Process-wide;
  * returns QOQ_ERR_SHAPE for values outside the set.  Workspace sizes depend on it. */
 int qoq_set_gemm_config(int tile_m, int split_k);
+/* The configuration a GEMM call of this shape would run with (host only, no device work): tile_m as above;
+ * split_k = k-slices per tile (compute-bound kernel) or workgroups per token tile (streaming kernels).
+ * QOQ_ERR_SHAPE for shapes the GEMM refuses, QOQ_ERR_NULL for null outputs. */
+int qoq_query_gemm_config(int64_t M, int64_t N, int64_t K, int mode, int* tile_m, int* split_k);
 
 #ifdef __cplusplus
 }

@@ -51,6 +51,8 @@ _SIGNATURES = {
                                        ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "qoq_set_gemm_config": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+    "qoq_query_gemm_config": (ctypes.c_int, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                             ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "qoq_channel_absmax": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
     "qoq_channel_order_host": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
     "qoq_gather_channels": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
@@ -133,6 +135,13 @@ def gemm_workspace_bytes(M, N, K, mode=QOQ_GROUP128):
 
 def set_gemm_config(tile_m=0, split_k=0):
     _check(lib().qoq_set_gemm_config(tile_m, split_k))
+
+
+def query_gemm_config(M, N, K, mode=QOQ_GROUP128):
+    """(tile_m, split_k) a GEMM call of this shape would run with (host only)."""
+    t, k = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().qoq_query_gemm_config(M, N, K, mode, ctypes.byref(t), ctypes.byref(k)))
+    return t.value, k.value
 
 
 def pack_weights(w, mode=QOQ_GROUP128, out=None):

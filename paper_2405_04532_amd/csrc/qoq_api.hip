@@ -135,6 +135,14 @@ int qoq_set_gemm_config(int tile_m, int split_k)
     return QOQ_OK;
 }
 
+int qoq_query_gemm_config(int64_t M, int64_t N, int64_t K, int mode, int* tile_m, int* split_k)
+{
+    if (!tile_m || !split_k) return QOQ_ERR_NULL;
+    if (!qoq::shape_ok(N, K, mode) || M <= 0) return QOQ_ERR_SHAPE;
+    qoq::pick_gemm_config(M, N, K, forced(), *tile_m, *split_k);
+    return QOQ_OK;
+}
+
 int qoq_pack_weights(const void* w_fp16_dev, int64_t N, int64_t K, int mode, void* packed_dev, void* stream)
 {
     if (check_shape(N, K, mode) != QOQ_OK) return QOQ_ERR_SHAPE;

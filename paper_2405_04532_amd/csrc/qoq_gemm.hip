@@ -1453,43 +1453,78 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
            (S > 1 ? (tile_m == 128 ? 30.0 : tile_m == 131 ? 22.0 : 14.0) : 0.0);
 }
 
+// Streaming kernels: partition and cost of running `tile`-token tiles, in microseconds (fitted to measurements of the
+// Llama-2-7B layers at 16 ... 128 tokens: about 4.3 us of launch, set-up and first loads, then 1.0 / 1.25 / 0.49 us
+// per iteration of eight / eight / two (block, group) units for 16 / 32 / 64-token tiles, 0.8 us (0.3 us) per further
+// block of a workgroup, and 3 us (7.8 us for the LDS-staged kernel) for the hand-over when blocks are shared).  All token tiles of a launch
+// together get one workgroup per CU: with few blocks (N small) it is faster to cut the tokens into more, smaller
+// tiles that run side by side, each re-reading the weights through L2, than to leave most CUs idle.  Per token tile
+// the units are dealt either in equal contiguous shares (blocks shared, hand-over) or as whole blocks (k per
+// workgroup, no partial tiles), whichever is estimated cheaper.
+struct StreamPlan { int64_t nwg; double cost; };
+static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t forced_nwg)
+{
+    const int64_t blocks = N / 64, units = blocks * G, m_tiles = (M + tile - 1) / tile;
+    const int64_t per_it = tile == 64 ? 2 : 8;
+    const double t_it = tile == 64 ? 0.49 : tile == 32 ? 1.25 : 1.0, handover = tile == 64 ? 7.8 : 3.0, fixed = 4.3;
+    const double weight_mb = (double)N * (double)G * (double)kGroup / 2.0e6;
+    const int64_t max_wg = (units + 1) / 2;              // at least one full iteration of the staged kernel each
+    // cost of dealing the units of every token tile to n workgroups
+    auto cost_of = [&](int64_t n, int64_t& n_eff) {
+        const int64_t upw = (units + n - 1) / n;
+        n_eff = (units + upw - 1) / upw;
+        const int64_t rounds = (m_tiles * n_eff + 255) / 256;
+        // every token tile reads all the weights (~4.5 TB/s from memory); tiles that run side by side on the same
+        // XCD (workgroup ids a multiple of 8 apart) find in its L2 what the 32 MB of L2 can hold of them
+        const double miss = std::min(1.0, weight_mb / 32.0);
+        const double reads = (n_eff % 8 == 0 && rounds == 1) ? 1.0 + miss * (double)(m_tiles - 1) : (double)m_tiles;
+        // every further block of a workgroup's run ends in an exchange of partial sums and an epilogue
+        const double loop = (double)rounds * ((double)((upw + per_it - 1) / per_it) * t_it +
+                                              (double)((upw + G - 1) / G - 1) * (tile == 64 ? 0.3 : 0.8));
+        return fixed + std::max(loop, weight_mb * reads / 4.5) + (upw % G ? handover : 0.0);
+    };
+    StreamPlan best{1, 0.0};
+    if (forced_nwg > 0) {
+        best.cost = cost_of(std::max<int64_t>(1, std::min(forced_nwg, max_wg)), best.nwg);
+        return best;
+    }
+    bool first = true;
+    for (const int64_t budget : {(int64_t)256, std::max<int64_t>(1, 256 / m_tiles)}) {
+        const int64_t k = (blocks + budget - 1) / budget;
+        for (const int64_t n : {std::min(budget, max_wg), (blocks + k - 1) / k}) {   // equal shares; whole blocks
+            StreamPlan c;
+            c.cost = cost_of(std::max<int64_t>(1, std::min(n, max_wg)), c.nwg);
+            if (first || c.cost < best.cost) { best = c; first = false; }
+        }
+    }
+    return best;
+}
+
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
-    tile_m = forced.tile_m ? forced.tile_m : (M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128);
+    const int natural = M <= 16 ? 16 : M <= 32 ? 32 : 64;   // smallest streaming tile that holds min(M, 64) tokens
+    int stream_tile = natural;
+    StreamPlan plan = stream_plan(M, N, G, natural, 0);
+    for (int t = natural / 2; t >= 16; t /= 2) {             // smaller tiles, more of them: must be clearly cheaper
+        const StreamPlan c = stream_plan(M, N, G, t, 0);
+        if (c.cost < 0.97 * plan.cost) { plan = c; stream_tile = t; }
+    }
+    tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
     if (!forced.tile_m && M > 64) {
-        // Cheapest of the four tile shapes of the compute-bound kernel and, for a few hundred tokens, the
-        // streaming kernel run once per 64-token tile (it re-reads the weights but spreads K over the whole
-        // chip): streaming ~ 4 + m_tiles * max(7.5, weight MB / 2.6) microseconds.
+        // Cheapest of the four tile shapes of the compute-bound kernel or, for a few hundred tokens, the streaming
+        // kernels (they re-read the weights once per token tile but spread K over the whole chip).
         int S;
         double best = mma_cost(M, N, G, 128, S);
         for (int cand = 129; cand <= 131; ++cand) {
             const double c = mma_cost(M, N, G, cand, S);
             if (c < 0.98 * best) { best = c; tile_m = cand; }
         }
-        const double m_tiles = (double)((M + 63) / 64);
-        const double w_mb = (double)K * (double)N / 2.0e6;
-        const double est_stream = 4.0 + m_tiles * (w_mb / 2.6 > 7.5 ? w_mb / 2.6 : 7.5);
-        if (est_stream < 0.9 * best) tile_m = 64;
+        if (plan.cost < 0.9 * best) tile_m = stream_tile;
     }
     if (tile_m <= 64) {
         const int64_t units = (N / 64) * G;
-        const int64_t blocks = N / 64;
-        const int64_t max_wg = (units + 1) / 2;   // at least one full iteration (two units) each
-        int64_t nwg = forced.split_k > 0 ? forced.split_k : 256;   // one workgroup per CU, equal shares of the units
-        if (nwg > max_wg) nwg = max_wg;
-        if (nwg < 1) nwg = 1;
-        if (forced.split_k <= 0) {
-            // Alternative: whole blocks per workgroup (k of them), fewer workgroups but no partial tiles and no
-            // hand-over at the end, which costs about as much as 12 iterations of the LDS-staged kernel (3 of the
-            // register-streaming one).  Taken when its longer loop is cheaper than that.
-            const int64_t per_it = tile_m == 64 ? 2 : 8, slack = tile_m == 64 ? 12 : 2;
-            const int64_t it_auto = ((units + nwg - 1) / nwg + per_it - 1) / per_it;
-            const int64_t k = (blocks + 255) / 256;
-            const int64_t nwg_whole = (blocks + k - 1) / k;
-            const int64_t it_whole = k * ((G + per_it - 1) / per_it);
-            if ((units + nwg_whole - 1) / nwg_whole == k * G && it_whole <= it_auto + slack) nwg = nwg_whole;
-        }
+        const int64_t nwg = (tile_m == stream_tile && forced.split_k <= 0) ? plan.nwg : stream_plan(M, N, G, tile_m, forced.split_k).nwg;
         const int64_t upw = (units + nwg - 1) / nwg;
         split_k = (int)((units + upw - 1) / upw);
         return;

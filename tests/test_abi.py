@@ -81,6 +81,36 @@ def test_argument_validation_without_gpu(api):
     assert L.qoq_gemm_workspace_prepare(None, 0, None) == 0
 
 
+def test_launch_plan_host_logic(api):
+    """The host-side choice of kernel, tile and partition (no device work): always a runnable configuration (a streaming
+    partition gives every workgroup at least two units and a token tile at most one workgroup per CU), narrow layers cut the tokens into
+    smaller tiles that run side by side, wide layers keep the 64-token tile, forced values are honoured."""
+    L = api.lib()
+    t, k = ctypes.c_int(0), ctypes.c_int(0)
+    assert L.qoq_query_gemm_config(4, 100, 256, 0, ctypes.byref(t), ctypes.byref(k)) == 2
+    assert L.qoq_query_gemm_config(4, 256, 256, 0, None, ctypes.byref(k)) == 1
+    for N in (64, 256, 4096, 12288, 22016, 57344):
+        for K in (128, 1152, 4096, 11008, 28672):
+            for M in (1, 7, 16, 17, 32, 33, 64, 65, 100, 128, 200, 256, 512, 1024, 4096):
+                tile, split = api.query_gemm_config(M, N, K)
+                assert tile in (16, 32, 64, 128, 129, 130, 131) and split >= 1, (M, N, K, tile, split)
+                units = (N // 64) * (K // 128)
+                if tile <= 64:
+                    assert split <= min(256, max(1, (units + 1) // 2)), (M, N, K, tile, split)
+                else:
+                    assert M > 64 and split <= K // 128
+                assert api.gemm_workspace_bytes(M, N, K) % 16 == 0
+    assert api.query_gemm_config(64, 4096, 4096) == (16, 64)        # 64 blocks: four 16-token tiles x 64 workgroups
+    assert api.query_gemm_config(64, 12288, 4096) == (64, 192)      # one block per workgroup already
+    assert api.query_gemm_config(64, 22016, 4096) == (64, 172)      # two whole blocks per workgroup
+    assert api.query_gemm_config(1024, 12288, 4096)[0] == 131       # 256 tiles of 256 x 192
+    api.set_gemm_config(32, 5)
+    try:
+        assert api.query_gemm_config(200, 4096, 4096) == (32, 5)
+    finally:
+        api.set_gemm_config(0, 0)
+
+
 def test_layout_is_a_bijection(tmp_path):
     """Host logic of the packed layout: (n, k) -> (byte, nibble) is one-to-one and onto."""
     src = tmp_path / "t.cpp"

@@ -153,6 +153,15 @@ def test_group_forced_variants(api, tile_m, split_k):
     run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
 
 
+@pytest.mark.parametrize("M,N,K,tile_m", [(1, 256, 128, 0), (40, 64, 128, 0), (64, 256, 128, 0), (150, 256, 128, 0), (64, 320, 256, 0),
+                                          (40, 256, 128, 16), (40, 256, 128, 32), (40, 256, 128, 64), (200, 256, 128, 129),
+                                          (64, 4096, 512, 0), (48, 1024, 640, 0), (100, 512, 384, 0)])
+def test_group_one_or_few_groups(api, M, N, K, tile_m):
+    """K of one to five groups (runs of a single unit, odd group counts) and the token-tile splitting the library
+    chooses for layers of few blocks."""
+    run_group_case(api, M, N, K, seed=3 + M + K, tile_m=tile_m)
+
+
 @pytest.mark.parametrize("M,tile_m,split_k", [(256, 64, 0), (256, 64, 8), (200, 32, 6), (320, 64, 12)])
 def test_group_streaming_kernel_many_token_tiles(api, M, tile_m, split_k):
     """The M <= 64 kernel forced onto several token tiles, with runs that end exactly at a block end and
