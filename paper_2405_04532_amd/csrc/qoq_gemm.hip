@@ -843,7 +843,7 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 // ------------------------------------------------------------------------------------------
 // "mma" kernel (compute bound, M > 64).  Four waves per workgroup, exactly one per SIMD; a wave owns
 // 128 tokens x (32 * CF) channels in 4 x CF accumulator tiles of v_mfma_i32_32x32x32_i8 (CF = 4: 256
-// accumulator registers per lane).  Three workgroup shapes share the code:
+// accumulator registers per lane).  Four workgroup shapes share the code:
 //     CF = 4, waves 2 x 2 : 256 tokens x 256 channels  (large problems: fewest bytes per MFMA)
 //     CF = 2, waves 1 x 4 : 128 tokens x 256 channels  (few tokens)
 //     CF = 2, waves 2 x 2 : 256 tokens x 128 channels  (few channels)

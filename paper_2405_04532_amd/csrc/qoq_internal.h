@@ -37,7 +37,7 @@ struct GemmArgs {
     void* out_fp16;          // [M, N] FP16, or null
     int32_t* out_i32;        // [M, N] INT32, or null
     void* workspace;         // split-k counters and partial tiles when split_k > 1
-    int tile_m;              // 16, 32, 64 (streaming kernel) or 128, 129, 130 (compute-bound kernel, three tile shapes)
+    int tile_m;              // 16, 32, 64 (streaming kernels) or 128 ... 131 (compute-bound kernel, four tile shapes)
     int split_k;             // compute-bound kernel: k-slices per tile; streaming kernel: workgroups sharing the unit stream
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
