@@ -841,6 +841,182 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 }
 
 // ------------------------------------------------------------------------------------------
+// Pair-streaming kernel (64-token tiles, group mode, wide layers).  Same copy scheme as the LDS-staged kernel, but a
+// workgroup works on TWO adjacent 64-channel blocks in lockstep and the consumer waves are cut differently: wave
+// (fp, e) takes fragments 2fp and 2fp + 1 of the pair's eight and, in every iteration, the group of parity e.  The
+// two activation slabs an iteration stages serve both blocks (half the activation bytes through the vector cache
+// per byte of weights, half the barriers), and a wave reads a slab from LDS once for two fragments (80 KiB of LDS
+// reads per 16 KiB of weights instead of 144): the two limits of the single-block loop move together.  At the end
+// of a pair the parity-1 waves hand their sums to the parity-0 waves through LDS, which run the epilogue.
+// Workgroups own whole pairs (p.upw of them, all K): no partial tiles, no workspace.  The host picks this kernel
+// only where whole pairs still fill the chip (N / 128 of the order of the CU count or more).
+// ------------------------------------------------------------------------------------------
+template <int OUT>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void pstream_kernel(GemmDev p)
+{
+    constexpr int MF = 4;
+    constexpr int kRing = 3;
+    constexpr int kABlocks = 2 * MF;                   // 1 KiB blocks (m-fragment, k-step) per group
+    constexpr int kAHalf = kABlocks / 2;
+    __shared__ uint4 wring[8][kRing][2][64];           // per consumer wave: the units of its two fragments
+    __shared__ uint4 aring[kRing][2][kABlocks * 64];   // activation slabs of the iteration's two groups
+    __shared__ uint4 mring[kRing][2][16];              // level-2 metadata: 8 fragments x 16 rows x uint16 per group
+    __shared__ uint4 sring[kRing][16];                 // the pair's 128 FP16 scales
+    __shared__ int4 red[4][2 * MF * 64];               // sums of the parity-1 waves at the end of a pair
+    __shared__ float sx_lds[16 * MF];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool producer = wave >= 8;
+    const int pk = wave & 1, ph = (wave >> 1) & 1;     // producer: group of the iteration, half of its activation blocks
+    const int e = wave & 1, fp = (wave & 7) >> 1;      // consumer: group parity, fragment pair
+    const int m0 = blockIdx.y * (16 * MF);
+    const int G = p.G;
+    const int pairs = p.N / 128;
+    const int sb0 = min(pairs, (int)blockIdx.x * p.upw), sb1 = min(pairs, sb0 + p.upw);
+    if (sb0 >= sb1) return;
+    const int q = lane >> 4, ml = lane & 15;
+    const int itpb = (G + 1) / 2;                      // iterations per pair
+    const int T = (sb1 - sb0) * itpb;
+
+    v4i acc[2][MF];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf) acc[i][mf] = (v4i){0, 0, 0, 0};
+
+    // ---- copies ---------------------------------------------------------------------------
+    uint32_t a_voff[kAHalf];
+    {
+        const int r = lane >> 2, c = lane & 3;
+        const int h = ((r >> 1) ^ (r >> 2)) & 3;
+#pragma unroll
+        for (int j = 0; j < kAHalf; ++j) {
+            const int b = ph * kAHalf + j;
+            const int row = min(m0 + (b >> 1) * 16 + r, p.M - 1);   // rows past M repeat the last one; never stored
+            a_voff[j] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((b & 1) * 64 + (c ^ h) * 16);
+        }
+    }
+    const uint32_t lane4 = (uint32_t)lane * 4u, lane16 = (uint32_t)lane * 16u;
+    const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0][0] + (uint32_t)(wave & 7) * (kRing * 2048);
+    const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)(pk * kABlocks + ph * kAHalf) * 1024u;
+    const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * 256;
+    const uint32_t sring_addr = (uint32_t)(uintptr_t)&sring[0][0];
+    constexpr uint32_t kASlot = 2 * kABlocks * 1024;
+    const char* abase = reinterpret_cast<const char*>(p.qx);
+    const char* sbase = reinterpret_cast<const char*>(p.scales);
+    const char* codes_base = reinterpret_cast<const char*>(p.codes);
+    const char* meta_base = reinterpret_cast<const char*>(p.meta);
+    const uint32_t m_g_stride = (uint32_t)(p.N / 16) * 32u;
+
+    // The copy front runs kRing - 1 iterations ahead of the iteration being consumed; past the end of the run it
+    // stays on the last iteration (every iteration issues the same number of copies, and a repeated copy reads
+    // valid memory into a slot nobody reads any more).
+    int csb = sb0, cg = 0, cleft = T;                  // pair, first group, iterations left at the copy front
+    auto issue = [&](int slot) __attribute__((always_inline)) {
+        const int two = cg + 1 < G ? 1 : 0;            // the iteration has a second group
+        if (producer) {
+            const uint32_t gsel = (uint32_t)(cg + (pk & two));
+#pragma unroll
+            for (int b = 0; b < kAHalf; ++b)
+                dma16(abase, a_voff[b] + gsel * (uint32_t)kGroup, aring_addr + slot * kASlot + b * 1024);
+            if (ph == 0) dma4(meta_base, lane4 + gsel * m_g_stride + (uint32_t)csb * 256u, mring_addr + slot * 512);
+            if (pk == 0 && ph == 1) dma4(sbase, lane4 + (uint32_t)csb * 256u, sring_addr + slot * 256);
+        } else {
+            const uint32_t gsel = (uint32_t)(cg + (e & two));
+            const uint32_t unit = ((uint32_t)(csb * 8 + 2 * fp) * (uint32_t)G + gsel) << 10;
+            dma16(codes_base, lane16 + unit, wring_addr + slot * 2048);
+            dma16(codes_base, lane16 + unit + ((uint32_t)G << 10), wring_addr + slot * 2048 + 1024);   // next fragment
+        }
+        if (cleft > 1) {
+            --cleft;
+            cg += 2;
+            if (cg >= G) { cg = 0; ++csb; }
+        }
+    };
+
+    const int hsw = ((ml >> 1) ^ (ml >> 2)) & 3;
+    const int a_src = 4 * ml + (q ^ hsw);
+    auto compute = [&](int slot) __attribute__((always_inline)) {
+        const uint4 wq0 = wring[wave & 7][slot][0][lane], wq1 = wring[wave & 7][slot][1][lane];
+        const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][e][0]);
+        const uint32_t mt0 = mrow[(2 * fp) * 16 + ml], mt1 = mrow[(2 * fp + 1) * 16 + ml];
+        const uint32_t S0 = __builtin_amdgcn_perm(mt0, mt0, 0x0c000c00u), B0 = __builtin_amdgcn_perm(mt0, mt0, 0x01010101u);
+        const uint32_t S1 = __builtin_amdgcn_perm(mt1, mt1, 0x0c000c00u), B1 = __builtin_amdgcn_perm(mt1, mt1, 0x01010101u);
+        const uint4* slab = aring[slot][e];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i a_op[MF];
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(slab[(mf * 2 + ks) * 64 + a_src]);
+            const v4i w0 = dequant<true>(ks ? wq0.z : wq0.x, ks ? wq0.w : wq0.y, S0, B0);
+            const v4i w1 = dequant<true>(ks ? wq1.z : wq1.x, ks ? wq1.w : wq1.y, S1, B1);
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                acc[0][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, a_op[mf], acc[0][mf], 0, 0, 0);
+                acc[1][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, a_op[mf], acc[1][mf], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main loop: one wait + one barrier per iteration, as in the staged kernel -------------------------
+#pragma unroll
+    for (int k = 0; k < kRing - 1; ++k) issue(k);
+    if (wave == 11 && lane < 16 * MF)
+        sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[min(m0 + lane, p.M - 1)]) : 0.f;
+    const int my_dma = producer ? kAHalf + (ph == 0 ? 1 : 0) + ((pk == 0 && ph == 1) ? 1 : 0) : 2;
+    int sb = sb0, g = 0, slot = 0;
+    for (int it = 0; it < T; ++it) {
+        if (my_dma == 2) wait_vmcnt<(kRing - 2) * 2>();
+        else if (my_dma == kAHalf) wait_vmcnt<(kRing - 2) * kAHalf>();
+        else wait_vmcnt<(kRing - 2) * (kAHalf + 1)>();
+        __syncthreads();
+        issue(slot == 0 ? kRing - 1 : slot - 1);
+        if (!producer && (e == 0 || g + 1 < G)) compute(slot);
+        if (g + 2 >= G) {                              // the pair is finished (uniform over the workgroup)
+            if (!producer && e == 1) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int mf = 0; mf < MF; ++mf) {
+                        red[fp][(i * MF + mf) * 64 + lane] = make_int4(acc[i][mf].x, acc[i][mf].y, acc[i][mf].z, acc[i][mf].w);
+                        acc[i][mf] = (v4i){0, 0, 0, 0};
+                    }
+            }
+            __syncthreads();
+            if (!producer && e == 0) {
+                const char* sc = reinterpret_cast<const char*>(&sring[slot][0]);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int f = 2 * fp + i;          // fragment of the pair: block f / 4, fragment f % 4 of it
+                    const int nl = (f >> 2) * 64 + 16 * q + 4 * (f & 3);
+                    const uint2 sw = *reinterpret_cast<const uint2*>(sc + nl * 2);
+                    float sn[4];
+                    const int zn[4] = {0, 0, 0, 0};
+                    sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
+                    sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
+                    sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
+                    sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
+#pragma unroll
+                    for (int mf = 0; mf < MF; ++mf) {
+                        const int4 o = red[fp][(i * MF + mf) * 64 + lane];
+                        v4i v = acc[i][mf];
+                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                        acc[i][mf] = (v4i){0, 0, 0, 0};
+                        const int m = m0 + mf * 16 + ml;
+                        if (m < p.M) finish4<true, OUT>(p, m, sb * 128 + nl, v, sn, zn, sx_lds[mf * 16 + ml], 0);
+                    }
+                }
+            }
+        }
+        g += 2;
+        if (g >= G) { g = 0; ++sb; }
+        slot = slot + 1 == kRing ? 0 : slot + 1;
+    }
+    wait_vmcnt<0>();   // tail copies still target the rings
+}
+
+// ------------------------------------------------------------------------------------------
 // "mma" kernel (compute bound, M > 64).  Four waves per workgroup, exactly one per SIMD; a wave owns
 // 128 tokens x (32 * CF) channels in 4 x CF accumulator tiles of v_mfma_i32_32x32x32_i8 (CF = 4: 256
 // accumulator registers per lane).  Four workgroup shapes share the code:
@@ -1391,7 +1567,13 @@ void launch_mma(const GemmDev& p, bool fp16, hipStream_t s)
 template <bool GROUP>
 void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
-    if (tile_m <= 64) {
+    if (tile_m == 65) {
+        const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
+        if constexpr (GROUP) {
+            if (fp16) pstream_kernel<OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+            else pstream_kernel<OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+        }
+    } else if (tile_m <= 64) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + tile_m - 1) / tile_m));
         if (tile_m == 16) launch_stream<1, GROUP>(p, fp16, grid, s);
         else if (tile_m == 32) launch_stream<2, GROUP>(p, fp16, grid, s);
@@ -1461,6 +1643,8 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 // tiles that run side by side, each re-reading the weights through L2, than to leave most CUs idle.  Per token tile
 // the units are dealt either in equal contiguous shares (blocks shared, hand-over) or as whole blocks (k per
 // workgroup, no partial tiles), whichever is estimated cheaper.
+// One iteration of the pair-streaming kernel (two blocks x two groups), microseconds (measured 0.90 - 0.94).
+constexpr double kPairIteration = 0.92;
 struct StreamPlan { int64_t nwg; double cost; };
 static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t forced_nwg)
 {
@@ -1500,9 +1684,21 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t
     return best;
 }
 
-void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k)
+// Pair-streaming kernel: whole pairs of blocks per workgroup, kp of them; one iteration = two blocks x two groups.
+static StreamPlan pair_plan(int64_t N, int64_t G, int64_t forced_nwg)
+{
+    const int64_t pairs = N / 128;
+    const int64_t kp = forced_nwg > 0 ? (pairs + std::min(forced_nwg, pairs) - 1) / std::min(forced_nwg, pairs) : (pairs + 255) / 256;
+    const int64_t nwg = (pairs + kp - 1) / kp;
+    const double weight_mb = (double)N * (double)G * (double)kGroup / 2.0e6;
+    const double loop = (double)(kp * ((G + 1) / 2)) * kPairIteration + (double)(kp - 1) * 0.3;
+    return {nwg, 4.3 + std::max(loop, weight_mb / 4.5)};
+}
+
+void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
+    const bool pairs_ok = mode == 0 && N % 128 == 0;   // the pair-streaming kernel: group mode, whole block pairs
     const int natural = M <= 16 ? 16 : M <= 32 ? 32 : 64;   // smallest streaming tile that holds min(M, 64) tokens
     int stream_tile = natural;
     StreamPlan plan = stream_plan(M, N, G, natural, 0);
@@ -1511,6 +1707,12 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
         if (c.cost < 0.97 * plan.cost) { plan = c; stream_tile = t; }
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
+    if (tile_m == 65 && !pairs_ok) tile_m = 64;
+    if (!forced.tile_m && M <= 64 && stream_tile == 64 && pairs_ok && pair_plan(N, G, 0).cost < 0.97 * plan.cost) tile_m = 65;
+    if (tile_m == 65) {
+        split_k = (int)pair_plan(N, G, forced.split_k).nwg;
+        return;
+    }
     if (!forced.tile_m && M > 64) {
         // Cheapest of the four tile shapes of the compute-bound kernel or, for a few hundred tokens, the streaming
         // kernels (they re-read the weights once per token tile but spread K over the whole chip).
@@ -1534,6 +1736,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced,
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
 {
+    if (tile_m == 65) return 0;                        // whole block pairs per workgroup: nothing is exchanged
     if (tile_m <= 64) {
         const int64_t m_tiles = (M + tile_m - 1) / tile_m;
         const int64_t units = (N / 64) * (K / kGroup);
@@ -1568,7 +1771,14 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     p.counters = reinterpret_cast<int*>(a.workspace);
     int nwg = 0;
     size_t counters;
-    if (a.tile_m <= 64) {
+    if (a.tile_m == 65) {
+        if (a.mode != 0 || a.N % 128 != 0) return hipErrorInvalidValue;
+        const int64_t pairs = a.N / 128;
+        p.upw = (int)((pairs + a.split_k - 1) / a.split_k);   // whole block pairs per workgroup
+        nwg = a.split_k;
+        p.S = 1; p.gps = (int)L.G;
+        counters = 0;
+    } else if (a.tile_m <= 64) {
         const int64_t units = (a.N / 64) * L.G;
         p.upw = (int)((units + a.split_k - 1) / a.split_k);
         nwg = a.split_k;

@@ -67,6 +67,6 @@ size_t kv4_decode_workspace_bytes(int64_t B, int64_t H, int64_t Hkv, int64_t S_m
 
 // Launch configuration the library picks for a problem (also sizes the workspace).
 struct GemmTuning { int tile_m, split_k; };  // 0 = let the heuristic decide
-void pick_gemm_config(int64_t M, int64_t N, int64_t K, const GemmTuning& forced, int& tile_m, int& split_k);
+void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTuning& forced, int& tile_m, int& split_k);
 
 }  // namespace qoq

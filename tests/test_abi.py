@@ -93,16 +93,19 @@ def test_launch_plan_host_logic(api):
         for K in (128, 1152, 4096, 11008, 28672):
             for M in (1, 7, 16, 17, 32, 33, 64, 65, 100, 128, 200, 256, 512, 1024, 4096):
                 tile, split = api.query_gemm_config(M, N, K)
-                assert tile in (16, 32, 64, 128, 129, 130, 131) and split >= 1, (M, N, K, tile, split)
+                assert tile in (16, 32, 64, 65, 128, 129, 130, 131) and split >= 1, (M, N, K, tile, split)
                 units = (N // 64) * (K // 128)
-                if tile <= 64:
+                if tile == 65:
+                    assert N % 128 == 0 and M <= 64 and split <= N // 128
+                elif tile <= 64:
                     assert split <= min(256, max(1, (units + 1) // 2)), (M, N, K, tile, split)
                 else:
                     assert M > 64 and split <= K // 128
                 assert api.gemm_workspace_bytes(M, N, K) % 16 == 0
     assert api.query_gemm_config(64, 4096, 4096) == (16, 64)        # 64 blocks: four 16-token tiles x 64 workgroups
     assert api.query_gemm_config(64, 12288, 4096) == (64, 192)      # one block per workgroup already
-    assert api.query_gemm_config(64, 22016, 4096) == (64, 172)      # two whole blocks per workgroup
+    assert api.query_gemm_config(64, 22016, 4096) == (65, 172)      # one whole pair of blocks per workgroup, in lockstep
+    assert api.query_gemm_config(64, 22016, 4096, api.QOQ_PER_CHANNEL) == (64, 172)   # (group mode only)
     assert api.query_gemm_config(1024, 12288, 4096)[0] == 131       # 256 tiles of 256 x 192
     api.set_gemm_config(32, 5)
     try:

@@ -162,6 +162,16 @@ def test_group_one_or_few_groups(api, M, N, K, tile_m):
     run_group_case(api, M, N, K, seed=3 + M + K, tile_m=tile_m)
 
 
+@pytest.mark.parametrize("M,N,K,split_k", [(64, 640, 1152, 0), (1, 640, 1152, 1), (17, 640, 1152, 3), (100, 640, 1152, 5),
+                                           (150, 384, 128, 0), (64, 384, 384, 2), (63, 1280, 2048, 0), (64, 128, 256, 0),
+                                           (64, 576, 1152, 0)])
+def test_group_pair_streaming_kernel(api, M, N, K, split_k):
+    """The kernel that streams two adjacent blocks in lockstep (whole pairs per workgroup): several pairs per
+    workgroup, one group and an odd number of groups per pair, ragged and several token tiles, a single pair; the
+    last case has an odd number of blocks, for which the library falls back to the single-block kernel."""
+    run_group_case(api, M, N, K, seed=41 + M, tile_m=65, split_k=split_k)
+
+
 @pytest.mark.parametrize("M,tile_m,split_k", [(256, 64, 0), (256, 64, 8), (200, 32, 6), (320, 64, 12)])
 def test_group_streaming_kernel_many_token_tiles(api, M, tile_m, split_k):
     """The M <= 64 kernel forced onto several token tiles, with runs that end exactly at a block end and
