@@ -28,7 +28,7 @@ INT8_PEAK_TOPS = 5033.0     # MI355X dense INT8 matrix, published (5.0 POP/s)
 CALIB_BYTES = 256 << 20     # size of the calibration copy
 # HBM bytes per GEMM launch of the default workload, from the two counter runs summarised in
 # profiles/w4a8_gemm_llama2_7b_decode_m64.txt (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy); None for any other workload.
-TRAFFIC_BYTES_PER_LAUNCH_DEFAULT = 31.52e6
+TRAFFIC_BYTES_PER_LAUNCH_DEFAULT = 31.45e6
 
 
 def algorithmic_bytes(M, N, K, mode=0):
