@@ -17,9 +17,60 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// ---- reductions over a wave without LDS traffic: four cross-lane (DPP) steps leave every row of 16 lanes with its
+// own result, the four row results are read into scalar registers and combined there.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+constexpr int kQuadSwap1 = 0xB1, kQuadSwap2 = 0x4E, kRowHalfMirror = 0x141, kRowMirror = 0x140;   // lanes ^1, ^2, 7-l, 15-l
+__device__ __forceinline__ float wave_max_nonneg(float v)   // v >= 0: the bit patterns order like the values
+{
+    int b = __float_as_int(v);
+    b = max(b, dpp_i32<kQuadSwap1>(b));
+    b = max(b, dpp_i32<kQuadSwap2>(b));
+    b = max(b, dpp_i32<kRowHalfMirror>(b));
+    b = max(b, dpp_i32<kRowMirror>(b));
+    const int r = max(max(__builtin_amdgcn_readlane(b, 0), __builtin_amdgcn_readlane(b, 16)),
+                      max(__builtin_amdgcn_readlane(b, 32), __builtin_amdgcn_readlane(b, 48)));
+    return __int_as_float(r);
+}
+__device__ __forceinline__ int wave_sum_i32(int v)
+{
+    v += dpp_i32<kQuadSwap1>(v);
+    v += dpp_i32<kQuadSwap2>(v);
+    v += dpp_i32<kRowHalfMirror>(v);
+    v += dpp_i32<kRowMirror>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+    v += __int_as_float(dpp_i32<kQuadSwap1>(__float_as_int(v)));
+    v += __int_as_float(dpp_i32<kQuadSwap2>(__float_as_int(v)));
+    v += __int_as_float(dpp_i32<kRowHalfMirror>(__float_as_int(v)));
+    v += __int_as_float(dpp_i32<kRowMirror>(__float_as_int(v)));
+    return (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)) + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)) + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48)));
+}
+
+// round_half_away(x / s), clamped to [-127, 127], for FP16 values x and s > 0 (held in FP32), without a division.
+// x and s have 11-bit significands, so the exact quotient is either exactly on a rounding midpoint k + 1/2 or at
+// least 2^-12 away from every midpoint (|x / s| < 256); x * fl(1 / s) is within 3e-5 of the quotient, and pushing
+// it 1e-4 away from zero sends exact midpoints up and nothing else across: the result is the one the correctly
+// rounded division followed by round-half-away gives, bit for bit (checked against exact rational arithmetic on
+// the FP16 neighbours of all midpoints of several thousand scales, and on the GPU against the CPU reference).
+__device__ __forceinline__ int quantize_code(float x, float inv_s)
+{
+    const float t = x * inv_s;
+    const int a = (int)(t + copysignf(0.5f + 1e-4f, t));   // conversion truncates toward zero
+    return max(-127, min(127, a));
+}
+
 __device__ inline float block_reduce_max(float v, float* smem)
 {
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    v = wave_max_nonneg(v);
     if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
     __syncthreads();
     float r = smem[0];
@@ -55,6 +106,7 @@ __global__ __launch_bounds__(kThreads) void act_quant_kernel(const __half* __res
     __half sxh = __float2half_rn(amax / 127.0f);
     if (__half2float(sxh) == 0.f) sxh = __float2half_rn(1.0f);
     const float s = __half2float(sxh);
+    const float inv_s = 1.0f / s;
 
     int isum = 0;
     float fsum = 0.f;
@@ -66,20 +118,15 @@ __global__ __launch_bounds__(kThreads) void act_quant_kernel(const __half* __res
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float2 f = __half22float2(h[j]);
-            // true IEEE division, then round half away from zero
-            int a = (int)roundf(f.x / s), b = (int)roundf(f.y / s);
-            a = max(-127, min(127, a));
-            b = max(-127, min(127, b));
+            const int a = quantize_code(f.x, inv_s), b = quantize_code(f.y, inv_s);   // round half away from zero
             isum += a + b;
             fsum += f.x + f.y;
             packed[j >> 1] |= ((uint32_t)(a & 0xFF) << (16 * (j & 1))) | ((uint32_t)(b & 0xFF) << (16 * (j & 1) + 8));
         }
         qrow[c] = make_uint2(packed[0], packed[1]);
     }
-    for (int o = 32; o > 0; o >>= 1) {
-        isum += __shfl_xor(isum, o, 64);
-        fsum += __shfl_xor(fsum, o, 64);
-    }
+    isum = wave_sum_i32(isum);
+    fsum = wave_sum_f32(fsum);
     if ((threadIdx.x & 63) == 0) { s_i[threadIdx.x >> 6] = isum; s_f[threadIdx.x >> 6] = fsum; }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -114,7 +161,7 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
             amax = fmaxf(amax, fmaxf(fabsf(f.x), fabsf(f.y)));
         }
     }
-    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    amax = wave_max_nonneg(amax);
     if ((threadIdx.x & 63) == 0) s_f[threadIdx.x >> 6] = amax;
     __syncthreads();
     amax = s_f[0];
@@ -125,6 +172,7 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
     __half sxh = __float2half_rn(amax / 127.0f);   // see act_quant_kernel for why FP32 suffices here
     if (__half2float(sxh) == 0.f) sxh = __float2half_rn(1.0f);
     const float s = __half2float(sxh);
+    const float inv_s = 1.0f / s;
 
     int isum = 0;
     float fsum = 0.f;
@@ -138,9 +186,7 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float2 f = __half22float2(h[j]);
-                int a = (int)roundf(f.x / s), b = (int)roundf(f.y / s);   // IEEE division, round half away from zero
-                a = max(-127, min(127, a));
-                b = max(-127, min(127, b));
+                const int a = quantize_code(f.x, inv_s), b = quantize_code(f.y, inv_s);   // round half away from zero
                 isum += a + b;
                 fsum += f.x + f.y;
                 packed[j >> 1] |= ((uint32_t)(a & 0xFF) << (16 * (j & 1))) | ((uint32_t)(b & 0xFF) << (16 * (j & 1) + 8));
@@ -152,10 +198,8 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
         if (threadIdx.x == 0) sx[m] = sxh;
         return;
     }
-    for (int o = 32; o > 0; o >>= 1) {
-        isum += __shfl_xor(isum, o, 64);
-        fsum += __shfl_xor(fsum, o, 64);
-    }
+    isum = wave_sum_i32(isum);
+    fsum = wave_sum_f32(fsum);
     if ((threadIdx.x & 63) == 0) { s_i[threadIdx.x >> 6] = isum; s_f[threadIdx.x >> 6] = fsum; }
     __syncthreads();
     if (threadIdx.x == 0) {

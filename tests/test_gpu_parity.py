@@ -107,6 +107,37 @@ def test_act_quant_ties_round_away(api):
     assert (_np(sx).view(np.uint16) == rsx.view(np.uint16)).all() and (_np(qx) == rqx).all()
 
 
+@pytest.mark.parametrize("K", [1024, 11008, 40960])
+def test_act_quant_midpoint_neighbours(api, K):
+    """Rows whose elements are the FP16 values next to (and on) every rounding midpoint (k + 1/2) * s of their own
+    scale, for 96 scales over the FP16 range (normal, subnormal, few and many significant bits): the codes must be
+    the oracle's for every one of them, and so must the scale."""
+    rng = np.random.default_rng(K)
+    allh = np.arange(1, 0x7C00, dtype=np.uint16).view(np.float16)
+    scales = np.concatenate([allh[rng.choice(len(allh), 64, replace=False)], allh[:8], allh[0x0400:0x0408],
+                             np.array([2.0 ** -6, 3 * 2.0 ** -10, 1.0, 5.5, 96.0, 257.0, 384.0, 500.0], dtype=np.float16),
+                             allh[-8:]])
+    rows = []
+    for s16 in scales:
+        s = float(s16)
+        top = np.float16(min(127.0 * s, 65504.0))                      # the row maximum fixes the row's scale near s
+        mids = (np.arange(0, 127) + 0.5) * s
+        mids = mids[mids <= 65504.0].astype(np.float16)
+        with np.errstate(over="ignore"):
+            cand = np.concatenate([mids, np.nextafter(mids, np.float16(np.inf)), np.nextafter(mids, np.float16(-np.inf))])
+        cand = cand[np.isfinite(cand) & (np.abs(cand.astype(np.float64)) <= float(top))]
+        row = np.zeros(K, dtype=np.float16)
+        vals = np.concatenate([[top], cand, -cand])[:K]
+        row[:len(vals)] = vals
+        rows.append(rng.permutation(row))
+    x = torch.from_numpy(np.stack(rows)).to(DEV)
+    qx, sx, rowsum, _ = api.quant_act_per_token(x, want_rowsum=True)
+    rqx, rsx, rrow, _ = qq.act_quant(_np(x))
+    assert (_np(sx).view(np.uint16) == rsx.view(np.uint16)).all()
+    assert (_np(qx).astype(np.int64) == rqx).all()
+    assert (_np(rowsum).astype(np.int64) == rrow).all()
+
+
 # ---------------------------------------------------------------------------- GEMM
 def run_group_case(api, M, N, K, seed, tile_m=0, split_k=0):
     w, x = rand_inputs(M, N, K, seed)
