@@ -211,6 +211,7 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
     }
 }
 
+template <int CACHE>
 __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* __restrict__ x, int64_t K,
                                                                  int8_t* __restrict__ qx, __half* __restrict__ sx,
                                                                  int32_t* __restrict__ rowsum, float* __restrict__ tx)
@@ -220,9 +221,9 @@ __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* _
     const int64_t m = blockIdx.x;
     const uint4* row = reinterpret_cast<const uint4*>(x + m * K);
     const int chunks = (int)(K / 8);
-    uint4 v[kCache];
+    uint4 v[CACHE];
 #pragma unroll
-    for (int i = 0; i < kCache; ++i) {
+    for (int i = 0; i < CACHE; ++i) {
         const int c = (int)threadIdx.x + i * kWide;
         v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
     }
@@ -367,8 +368,11 @@ hipError_t launch_act_quant(const void* x_fp16, int64_t M, int64_t K, int8_t* qx
 {
     if (M == 0) return hipSuccess;
     if (K <= kMaxCachedK) {
-        act_quant_cached_kernel<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx,
-                                                                   static_cast<__half*>(sx), rowsum, tx);
+        // as many cached 16-byte chunks per thread as the row needs: short rows spend nothing on empty ones
+        auto* kern = K <= (int64_t)kWide * 8 ? act_quant_cached_kernel<1>
+                   : K <= (int64_t)kWide * 2 * 8 ? act_quant_cached_kernel<2>
+                   : K <= (int64_t)kWide * 4 * 8 ? act_quant_cached_kernel<4> : act_quant_cached_kernel<kCache>;
+        kern<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx, static_cast<__half*>(sx), rowsum, tx);
         return hipGetLastError();
     }
     act_quant_kernel<<<dim3((unsigned)M), kThreads, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx,
