@@ -841,7 +841,7 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 }
 
 // ------------------------------------------------------------------------------------------
-// Pair-streaming kernel (64-token tiles, group mode, wide layers).  Same copy scheme as the LDS-staged kernel, but a
+// Pair-streaming kernel (64-token tiles, wide layers).  Same copy scheme as the LDS-staged kernel, but a
 // workgroup works on TWO adjacent 64-channel blocks in lockstep and the consumer waves are cut differently: wave
 // (fp, e) takes fragments 2fp and 2fp + 1 of the pair's eight and, in every iteration, the group of parity e.  The
 // two activation slabs an iteration stages serve both blocks (half the activation bytes through the vector cache
@@ -851,7 +851,7 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 // Workgroups own whole pairs (p.upw of them, all K): no partial tiles, no workspace.  The host picks this kernel
 // only where whole pairs still fill the chip (N / 128 of the order of the CU count or more).
 // ------------------------------------------------------------------------------------------
-template <int OUT>
+template <bool GROUP, int OUT>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void pstream_kernel(GemmDev p)
 {
     constexpr int MF = 4;
@@ -861,9 +861,10 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     __shared__ uint4 wring[8][kRing][2][64];           // per consumer wave: the units of its two fragments
     __shared__ uint4 aring[kRing][2][kABlocks * 64];   // activation slabs of the iteration's two groups
     __shared__ uint4 mring[kRing][2][16];              // level-2 metadata: 8 fragments x 16 rows x uint16 per group
-    __shared__ uint4 sring[kRing][16];                 // the pair's 128 FP16 scales
+    __shared__ uint4 sring[kRing][32];                 // the pair's 128 FP16 scales (256 B); 128 zero bytes, copied twice (a copy fills 256 B)
     __shared__ int4 red[4][2 * MF * 64];               // sums of the parity-1 waves at the end of a pair
     __shared__ float sx_lds[16 * MF];
+    __shared__ int rs_lds[16 * MF];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -920,8 +921,10 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
             for (int b = 0; b < kAHalf; ++b)
                 dma16(abase, a_voff[b] + gsel * (uint32_t)kGroup, aring_addr + slot * kASlot + b * 1024);
-            if (ph == 0) dma4(meta_base, lane4 + gsel * m_g_stride + (uint32_t)csb * 256u, mring_addr + slot * 512);
-            if (pk == 0 && ph == 1) dma4(sbase, lane4 + (uint32_t)csb * 256u, sring_addr + slot * 256);
+            if (GROUP && ph == 0) dma4(meta_base, lane4 + gsel * m_g_stride + (uint32_t)csb * 256u, mring_addr + slot * 512);
+            if (pk == 0 && ph == 1) dma4(sbase, lane4 + (uint32_t)csb * 256u, sring_addr + slot * 512);
+            if (!GROUP && pk == 1 && ph == 1)          // 128 zero bytes; the upper lanes repeat them
+                dma4(reinterpret_cast<const char*>(p.zeros), (uint32_t)(lane & 31) * 4u + (uint32_t)csb * 128u, sring_addr + slot * 512 + 256);
         } else {
             const uint32_t gsel = (uint32_t)(cg + (e & two));
             const uint32_t unit = ((uint32_t)(csb * 8 + 2 * fp) * (uint32_t)G + gsel) << 10;
@@ -939,18 +942,21 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     const int a_src = 4 * ml + (q ^ hsw);
     auto compute = [&](int slot) __attribute__((always_inline)) {
         const uint4 wq0 = wring[wave & 7][slot][0][lane], wq1 = wring[wave & 7][slot][1][lane];
-        const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][e][0]);
-        const uint32_t mt0 = mrow[(2 * fp) * 16 + ml], mt1 = mrow[(2 * fp + 1) * 16 + ml];
-        const uint32_t S0 = __builtin_amdgcn_perm(mt0, mt0, 0x0c000c00u), B0 = __builtin_amdgcn_perm(mt0, mt0, 0x01010101u);
-        const uint32_t S1 = __builtin_amdgcn_perm(mt1, mt1, 0x0c000c00u), B1 = __builtin_amdgcn_perm(mt1, mt1, 0x01010101u);
+        uint32_t S0 = 0, B0 = 0, S1 = 0, B1 = 0;
+        if (GROUP) {
+            const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][e][0]);
+            const uint32_t mt0 = mrow[(2 * fp) * 16 + ml], mt1 = mrow[(2 * fp + 1) * 16 + ml];
+            S0 = __builtin_amdgcn_perm(mt0, mt0, 0x0c000c00u); B0 = __builtin_amdgcn_perm(mt0, mt0, 0x01010101u);
+            S1 = __builtin_amdgcn_perm(mt1, mt1, 0x0c000c00u); B1 = __builtin_amdgcn_perm(mt1, mt1, 0x01010101u);
+        }
         const uint4* slab = aring[slot][e];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             v4i a_op[MF];
 #pragma unroll
             for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(slab[(mf * 2 + ks) * 64 + a_src]);
-            const v4i w0 = dequant<true>(ks ? wq0.z : wq0.x, ks ? wq0.w : wq0.y, S0, B0);
-            const v4i w1 = dequant<true>(ks ? wq1.z : wq1.x, ks ? wq1.w : wq1.y, S1, B1);
+            const v4i w0 = dequant<GROUP>(ks ? wq0.z : wq0.x, ks ? wq0.w : wq0.y, S0, B0);
+            const v4i w1 = dequant<GROUP>(ks ? wq1.z : wq1.x, ks ? wq1.w : wq1.y, S1, B1);
 #pragma unroll
             for (int mf = 0; mf < MF; ++mf) {
                 acc[0][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, a_op[mf], acc[0][mf], 0, 0, 0);
@@ -962,9 +968,13 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     // ---- main loop: one wait + one barrier per iteration, as in the staged kernel -------------------------
 #pragma unroll
     for (int k = 0; k < kRing - 1; ++k) issue(k);
-    if (wave == 11 && lane < 16 * MF)
-        sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[min(m0 + lane, p.M - 1)]) : 0.f;
-    const int my_dma = producer ? kAHalf + (ph == 0 ? 1 : 0) + ((pk == 0 && ph == 1) ? 1 : 0) : 2;
+    if (wave == 11 && lane < 16 * MF) {
+        const int m = min(m0 + lane, p.M - 1);
+        sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
+        rs_lds[lane] = GROUP ? 0 : p.rowsum[m];
+    }
+    const int my_dma = producer ? kAHalf + ((GROUP && ph == 0) ? 1 : 0) + ((pk == 0 && ph == 1) ? 1 : 0) +
+                                      ((!GROUP && pk == 1 && ph == 1) ? 1 : 0) : 2;
     int sb = sb0, g = 0, slot = 0;
     for (int it = 0; it < T; ++it) {
         if (my_dma == 2) wait_vmcnt<(kRing - 2) * 2>();
@@ -992,7 +1002,12 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
                     const int nl = (f >> 2) * 64 + 16 * q + 4 * (f & 3);
                     const uint2 sw = *reinterpret_cast<const uint2*>(sc + nl * 2);
                     float sn[4];
-                    const int zn[4] = {0, 0, 0, 0};
+                    int zn[4] = {0, 0, 0, 0};
+                    if (!GROUP) {
+                        const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 256 + nl);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
+                    }
                     sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
                     sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
                     sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
@@ -1004,7 +1019,7 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
                         v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
                         acc[i][mf] = (v4i){0, 0, 0, 0};
                         const int m = m0 + mf * 16 + ml;
-                        if (m < p.M) finish4<true, OUT>(p, m, sb * 128 + nl, v, sn, zn, sx_lds[mf * 16 + ml], 0);
+                        if (m < p.M) finish4<GROUP, OUT>(p, m, sb * 128 + nl, v, sn, zn, sx_lds[mf * 16 + ml], rs_lds[mf * 16 + ml]);
                     }
                 }
             }
@@ -1569,10 +1584,8 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
     if (tile_m == 65) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
-        if constexpr (GROUP) {
-            if (fp16) pstream_kernel<OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
-            else pstream_kernel<OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
-        }
+        if (fp16) pstream_kernel<GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else pstream_kernel<GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
     } else if (tile_m <= 64) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + tile_m - 1) / tile_m));
         if (tile_m == 16) launch_stream<1, GROUP>(p, fp16, grid, s);
@@ -1698,7 +1711,8 @@ static StreamPlan pair_plan(int64_t N, int64_t G, int64_t forced_nwg)
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
-    const bool pairs_ok = mode == 0 && N % 128 == 0;   // the pair-streaming kernel: group mode, whole block pairs
+    const bool pairs_ok = N % 128 == 0;                // the pair-streaming kernel takes whole block pairs
+    (void)mode;
     const int natural = M <= 16 ? 16 : M <= 32 ? 32 : 64;   // smallest streaming tile that holds min(M, 64) tokens
     int stream_tile = natural;
     StreamPlan plan = stream_plan(M, N, G, natural, 0);
@@ -1772,7 +1786,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     int nwg = 0;
     size_t counters;
     if (a.tile_m == 65) {
-        if (a.mode != 0 || a.N % 128 != 0) return hipErrorInvalidValue;
+        if (a.N % 128 != 0) return hipErrorInvalidValue;
         const int64_t pairs = a.N / 128;
         p.upw = (int)((pairs + a.split_k - 1) / a.split_k);   // whole block pairs per workgroup
         nwg = a.split_k;

@@ -105,7 +105,7 @@ def test_launch_plan_host_logic(api):
     assert api.query_gemm_config(64, 4096, 4096) == (16, 64)        # 64 blocks: four 16-token tiles x 64 workgroups
     assert api.query_gemm_config(64, 12288, 4096) == (64, 192)      # one block per workgroup already
     assert api.query_gemm_config(64, 22016, 4096) == (65, 172)      # one whole pair of blocks per workgroup, in lockstep
-    assert api.query_gemm_config(64, 22016, 4096, api.QOQ_PER_CHANNEL) == (64, 172)   # (group mode only)
+    assert api.query_gemm_config(64, 22016, 4096, api.QOQ_PER_CHANNEL) == (65, 172)   # in either mode
     assert api.query_gemm_config(1024, 12288, 4096)[0] == 131       # 256 tiles of 256 x 192
     api.set_gemm_config(32, 5)
     try:

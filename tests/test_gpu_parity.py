@@ -257,13 +257,13 @@ def test_extreme_magnitudes_fit_int32(api):
     assert np.abs(ref).max() == 127 * 128 * K and (acc == ref).all()
 
 
-@pytest.mark.parametrize("M,N,K", [(16, 256, 256), (70, 192, 640), (200, 448, 1152)])
+@pytest.mark.parametrize("M,N,K", [(16, 256, 256), (70, 192, 640), (200, 448, 1152), (64, 640, 1152), (50, 384, 384)])
 def test_per_channel_gemm(api, M, N, K):
     w, x = rand_inputs(M, N, K, seed=M + N)
     ref = ogemm.forward_per_channel(_np(w), _np(x))
     blob = api.pack_weights(w, api.QOQ_PER_CHANNEL)
     qx, sx, rowsum, _ = api.quant_act_per_token(x)
-    for tile_m, split_k in [(0, 0), (32, 3), (128, 1), (129, 1), (130, 1), (131, 1), (129, 2), (128, 3), (131, 3)]:
+    for tile_m, split_k in [(0, 0), (32, 3), (65, 0), (65, 1), (128, 1), (129, 1), (130, 1), (131, 1), (129, 2), (128, 3), (131, 3)]:
         api.set_gemm_config(tile_m, split_k)
         try:
             acc = api.w4a8_gemm_i32(qx, blob, N, api.QOQ_PER_CHANNEL, rowsum=rowsum)
@@ -341,7 +341,8 @@ def test_linear_equals_quant_then_gemm(api, M, N, K, mode):
 # ---------------------------------------------------------------------------- token-sum form of the per-channel epilogue
 @pytest.mark.parametrize("M,N,K,cfg", [(16, 256, 256, (0, 0)), (64, 512, 4096, (0, 0)), (70, 192, 640, (32, 3)),
                                        (200, 448, 1152, (128, 1)), (200, 448, 1152, (129, 2)), (300, 320, 2048, (130, 1)),
-                                       (300, 320, 2048, (131, 1)), (200, 448, 1152, (131, 2)), (257, 256, 640, (131, 1))])
+                                       (300, 320, 2048, (131, 1)), (200, 448, 1152, (131, 2)), (257, 256, 640, (131, 1)),
+                                       (64, 640, 1152, (65, 0)), (100, 384, 384, (65, 2))])
 def test_per_channel_token_sum_epilogue(api, M, N, K, cfg):
     """out = acc * sx * sw - t_X * (z * sw) with t_X summed over the unquantized activations (Section 5.2.2),
     against the oracle's FP64 form.  Tolerance: the stated 1e-3 relative on the result plus the FP32 rounding
