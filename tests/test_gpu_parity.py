@@ -274,6 +274,30 @@ def test_per_channel_gemm(api, M, N, K):
         check_fp16(out, ref["out64"])
 
 
+def test_random_shapes_in_the_configuration_the_library_picks(api):
+    """Thirty seeded shapes (tokens, channels, depth, mode) in whatever kernel, tile and partition the library
+    chooses for them: INT32 accumulators bit for bit, FP16 output within tolerance."""
+    rng = np.random.default_rng(2405)
+    seen = set()
+    for it in range(30):
+        N = int(rng.integers(1, 17)) * 64
+        K = int(rng.integers(1, 17)) * 128
+        M = int(rng.choice([1, 3, 16, 17, 31, 32, 33, 48, 63, 64, 65, 96, 100, 128, 130, 200, 257, 300]))
+        mode = int(rng.integers(0, 2))
+        if it >= 26:                                   # wide ones: block pairs, two compute-bound tile shapes
+            M, N, K = [(64, 22016, 256), (48, 24576, 256), (520, 12288, 384), (1030, 12288, 128)][it - 26]
+        w, x = rand_inputs(M, N, K, seed=1000 + it)
+        ref = (ogemm.forward_per_channel if mode else ogemm.forward_group)(_np(w), _np(x))
+        blob = api.pack_weights(w, mode)
+        qx, sx, rowsum, _ = api.quant_act_per_token(x)
+        seen.add(api.query_gemm_config(M, N, K, mode)[0])
+        acc = api.w4a8_gemm_i32(qx, blob, N, mode, rowsum=rowsum)
+        out = api.w4a8_gemm(qx, sx, blob, N, mode, rowsum=rowsum)
+        assert (_np(acc).astype(np.int64) == ref["acc"]).all(), (M, N, K, mode)
+        check_fp16(out, ref["out64"])
+    assert {16, 64, 65, 128, 129} <= seen, seen        # the draw reaches the kernel families
+
+
 def test_repeated_launches_are_identical(api):
     """Double-buffer hazards would show as run-to-run differences."""
     w, x = rand_inputs(96, 512, 2048, seed=21)
