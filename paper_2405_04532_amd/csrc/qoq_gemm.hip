@@ -1656,8 +1656,8 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 // tiles that run side by side, each re-reading the weights through L2, than to leave most CUs idle.  Per token tile
 // the units are dealt either in equal contiguous shares (blocks shared, hand-over) or as whole blocks (k per
 // workgroup, no partial tiles), whichever is estimated cheaper.
-// One iteration of the pair-streaming kernel (two blocks x two groups), microseconds (measured 0.90 - 0.94).
-constexpr double kPairIteration = 0.92;
+// One iteration of the pair-streaming kernel (two blocks x two groups), microseconds (measured 0.79 - 0.94).
+constexpr double kPairIteration = 0.88;
 struct StreamPlan { int64_t nwg; double cost; };
 static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t forced_nwg)
 {
@@ -1678,7 +1678,9 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t
         // every further block of a workgroup's run ends in an exchange of partial sums and an epilogue
         const double loop = (double)rounds * ((double)((upw + per_it - 1) / per_it) * t_it +
                                               (double)((upw + G - 1) / G - 1) * (tile == 64 ? 0.3 : 0.8));
-        return fixed + std::max(loop, weight_mb * reads / 4.5) + (upw % G ? handover : 0.0);
+        // the hand-over follows the loop; a later round pays it again and waits 1.5 us for its first copies
+        return fixed + std::max(loop, weight_mb * reads / 4.5) + (double)rounds * (upw % G ? handover : 0.0) +
+               (double)(rounds - 1) * 1.5;
     };
     StreamPlan best{1, 0.0};
     if (forced_nwg > 0) {
@@ -1697,15 +1699,21 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t
     return best;
 }
 
-// Pair-streaming kernel: whole pairs of blocks per workgroup, kp of them; one iteration = two blocks x two groups.
-static StreamPlan pair_plan(int64_t N, int64_t G, int64_t forced_nwg)
+// Pair-streaming kernel: whole pairs of blocks per workgroup, kp of them; one iteration = two blocks x two groups; all
+// 64-token tiles of the launch together fill the chip once.
+static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg)
 {
-    const int64_t pairs = N / 128;
-    const int64_t kp = forced_nwg > 0 ? (pairs + std::min(forced_nwg, pairs) - 1) / std::min(forced_nwg, pairs) : (pairs + 255) / 256;
+    const int64_t pairs = N / 128, m_tiles = (M + 63) / 64;
+    const int64_t kp = forced_nwg > 0 ? (pairs + std::min(forced_nwg, pairs) - 1) / std::min(forced_nwg, pairs)
+                                      : std::min(pairs, (pairs * m_tiles + 255) / 256);
     const int64_t nwg = (pairs + kp - 1) / kp;
+    const int64_t rounds = (m_tiles * nwg + 255) / 256;
     const double weight_mb = (double)N * (double)G * (double)kGroup / 2.0e6;
-    const double loop = (double)(kp * ((G + 1) / 2)) * kPairIteration + (double)(kp - 1) * 0.3;
-    return {nwg, 4.3 + std::max(loop, weight_mb / 4.5)};
+    const double miss = std::min(1.0, weight_mb / 32.0);
+    const double reads = (nwg % 8 == 0 && rounds == 1) ? 1.0 + miss * (double)(m_tiles - 1) : (double)m_tiles;
+    const double loop = (double)rounds * ((double)(kp * ((G + 1) / 2)) * kPairIteration + (double)(kp - 1) * 0.3) +
+                        (double)(rounds - 1) * 1.5;
+    return {nwg, 4.3 + std::max(loop, weight_mb * reads / 4.5)};
 }
 
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTuning& forced, int& tile_m, int& split_k)
@@ -1716,15 +1724,16 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
     const int natural = M <= 16 ? 16 : M <= 32 ? 32 : 64;   // smallest streaming tile that holds min(M, 64) tokens
     int stream_tile = natural;
     StreamPlan plan = stream_plan(M, N, G, natural, 0);
-    for (int t = natural / 2; t >= 16; t /= 2) {             // smaller tiles, more of them: must be clearly cheaper
+    for (int t = natural / 2; t >= 16; t /= 2) {             // smaller tiles, more of them
         const StreamPlan c = stream_plan(M, N, G, t, 0);
-        if (c.cost < 0.97 * plan.cost) { plan = c; stream_tile = t; }
+        if (c.cost < 0.99 * plan.cost) { plan = c; stream_tile = t; }
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
     if (tile_m == 65 && !pairs_ok) tile_m = 64;
-    if (!forced.tile_m && M <= 64 && stream_tile == 64 && pairs_ok && pair_plan(N, G, 0).cost < 0.97 * plan.cost) tile_m = 65;
+    const bool pair_wins = pairs_ok && stream_tile == 64 && pair_plan(M, N, G, 0).cost < 0.97 * plan.cost;
+    if (!forced.tile_m && M <= 64 && pair_wins) tile_m = 65;
     if (tile_m == 65) {
-        split_k = (int)pair_plan(N, G, forced.split_k).nwg;
+        split_k = (int)pair_plan(M, N, G, forced.split_k).nwg;
         return;
     }
     if (!forced.tile_m && M > 64) {
@@ -1736,7 +1745,12 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
             const double c = mma_cost(M, N, G, cand, S);
             if (c < 0.98 * best) { best = c; tile_m = cand; }
         }
-        if (plan.cost < 0.9 * best) tile_m = stream_tile;
+        const double stream_cost = pair_wins ? pair_plan(M, N, G, 0).cost : plan.cost;
+        if (stream_cost < 0.9 * best) tile_m = pair_wins ? 65 : stream_tile;
+        if (tile_m == 65) {
+            split_k = (int)pair_plan(M, N, G, 0).nwg;
+            return;
+        }
     }
     if (tile_m <= 64) {
         const int64_t units = (N / 64) * G;

@@ -96,7 +96,7 @@ def test_launch_plan_host_logic(api):
                 assert tile in (16, 32, 64, 65, 128, 129, 130, 131) and split >= 1, (M, N, K, tile, split)
                 units = (N // 64) * (K // 128)
                 if tile == 65:
-                    assert N % 128 == 0 and M <= 64 and split <= N // 128
+                    assert N % 128 == 0 and split <= N // 128
                 elif tile <= 64:
                     assert split <= min(256, max(1, (units + 1) // 2)), (M, N, K, tile, split)
                 else:
