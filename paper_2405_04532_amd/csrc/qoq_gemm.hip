@@ -1032,6 +1032,186 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 }
 
 // ------------------------------------------------------------------------------------------
+// Quad-streaming kernel (64-token tiles, very wide layers or a few hundred tokens).  Four adjacent 64-channel blocks
+// per workgroup in lockstep: per byte of weights a quarter of the activation bytes of the single-block kernel go
+// through the vector cache.  Consumer wave w takes fragments 2w and 2w + 1 of the quad's sixteen and BOTH groups
+// of an iteration, so no wave needs another's sums and the end of a quad is a plain epilogue per wave; the LDS reads
+// (160 KiB per 32 KiB of weights) stay below what the copies cost.  Whole quads per workgroup (p.upw of them, all
+// K): no partial tiles, no workspace.  N % 256 == 0.
+// ------------------------------------------------------------------------------------------
+template <bool GROUP, int OUT>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void qstream_kernel(GemmDev p)
+{
+    constexpr int MF = 4;
+    constexpr int kRing = 3;
+    constexpr int kABlocks = 2 * MF;                   // 1 KiB blocks (m-fragment, k-step) per group
+    constexpr int kAHalf = kABlocks / 2;
+    __shared__ uint4 wring[8][kRing][2][2][64];        // per consumer wave: [group][fragment] units of an iteration
+    __shared__ uint4 aring[kRing][2][kABlocks * 64];   // activation slabs of the iteration's two groups
+    __shared__ uint4 mring[kRing][2][32];              // level-2 metadata: 16 fragments x 16 rows x uint16 per group
+    __shared__ uint4 sring[kRing][48];                 // the quad's 256 FP16 scales (512 B) and 256 zero bytes
+    __shared__ float sx_lds[16 * MF];
+    __shared__ int rs_lds[16 * MF];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool producer = wave >= 8;
+    const int pk = wave & 1, ph = (wave >> 1) & 1;     // producer: group of the iteration, half of its activation blocks
+    const int w8 = wave & 7;                           // consumer: fragments 2 * w8, 2 * w8 + 1 of the quad
+    const int m0 = blockIdx.y * (16 * MF);
+    const int G = p.G;
+    const int quads = p.N / 256;
+    const int sb0 = min(quads, (int)blockIdx.x * p.upw), sb1 = min(quads, sb0 + p.upw);
+    if (sb0 >= sb1) return;
+    const int q = lane >> 4, ml = lane & 15;
+    const int T = (sb1 - sb0) * ((G + 1) / 2);
+
+    v4i acc[2][MF];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int mf = 0; mf < MF; ++mf) acc[i][mf] = (v4i){0, 0, 0, 0};
+
+    uint32_t a_voff[kAHalf];
+    {
+        const int r = lane >> 2, c = lane & 3;
+        const int h = ((r >> 1) ^ (r >> 2)) & 3;
+#pragma unroll
+        for (int j = 0; j < kAHalf; ++j) {
+            const int b = ph * kAHalf + j;
+            const int row = min(m0 + (b >> 1) * 16 + r, p.M - 1);   // rows past M repeat the last one; never stored
+            a_voff[j] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((b & 1) * 64 + (c ^ h) * 16);
+        }
+    }
+    const uint32_t lane4 = (uint32_t)lane * 4u, lane16 = (uint32_t)lane * 16u;
+    const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0][0][0] + (uint32_t)w8 * (kRing * 4096);
+    const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)(pk * kABlocks + ph * kAHalf) * 1024u;
+    const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * 512;
+    const uint32_t sring_addr = (uint32_t)(uintptr_t)&sring[0][0];
+    constexpr uint32_t kASlot = 2 * kABlocks * 1024;
+    const char* abase = reinterpret_cast<const char*>(p.qx);
+    const char* sbase = reinterpret_cast<const char*>(p.scales);
+    const char* zbase = reinterpret_cast<const char*>(p.zeros);
+    const char* codes_base = reinterpret_cast<const char*>(p.codes);
+    const char* meta_base = reinterpret_cast<const char*>(p.meta);
+    const uint32_t m_g_stride = (uint32_t)(p.N / 16) * 32u;
+
+    // copy front, kRing - 1 iterations ahead; past the end of the run it repeats the last iteration
+    int csb = sb0, cg = 0, cleft = T;
+    auto issue = [&](int slot) __attribute__((always_inline)) {
+        const int two = cg + 1 < G ? 1 : 0;            // the iteration has a second group
+        if (producer) {
+            const uint32_t gsel = (uint32_t)(cg + (pk & two));
+#pragma unroll
+            for (int b = 0; b < kAHalf; ++b)
+                dma16(abase, a_voff[b] + gsel * (uint32_t)kGroup, aring_addr + slot * kASlot + b * 1024);
+            if (GROUP && ph == 0) {                    // 512 B of metadata of the quad for this group
+                const uint32_t moff = lane4 + gsel * m_g_stride + (uint32_t)csb * 512u;
+                dma4(meta_base, moff, mring_addr + slot * 1024);
+                dma4(meta_base, moff + 256u, mring_addr + slot * 1024 + 256);
+            }
+            if (pk == 0 && ph == 1) {
+                dma4(sbase, lane4 + (uint32_t)csb * 512u, sring_addr + slot * 768);
+                dma4(sbase, lane4 + (uint32_t)csb * 512u + 256u, sring_addr + slot * 768 + 256);
+            }
+            if (!GROUP && pk == 1 && ph == 1) dma4(zbase, lane4 + (uint32_t)csb * 256u, sring_addr + slot * 768 + 512);
+        } else {
+            const uint32_t unit = ((uint32_t)(csb * 16 + 2 * w8) * (uint32_t)G + (uint32_t)cg) << 10;
+            const uint32_t nf = (uint32_t)G << 10, ng = (uint32_t)two << 10;   // next fragment, next group
+            dma16(codes_base, lane16 + unit, wring_addr + slot * 4096);
+            dma16(codes_base, lane16 + unit + nf, wring_addr + slot * 4096 + 1024);
+            dma16(codes_base, lane16 + unit + ng, wring_addr + slot * 4096 + 2048);
+            dma16(codes_base, lane16 + unit + ng + nf, wring_addr + slot * 4096 + 3072);
+        }
+        if (cleft > 1) {
+            --cleft;
+            cg += 2;
+            if (cg >= G) { cg = 0; ++csb; }
+        }
+    };
+
+    const int hsw = ((ml >> 1) ^ (ml >> 2)) & 3;
+    const int a_src = 4 * ml + (q ^ hsw);
+    auto compute = [&](int slot, int e) __attribute__((always_inline)) {
+        const uint4 wq0 = wring[w8][slot][e][0][lane], wq1 = wring[w8][slot][e][1][lane];
+        uint32_t S0 = 0, B0 = 0, S1 = 0, B1 = 0;
+        if (GROUP) {
+            const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][e][0]);
+            const uint32_t mt0 = mrow[(2 * w8) * 16 + ml], mt1 = mrow[(2 * w8 + 1) * 16 + ml];
+            S0 = __builtin_amdgcn_perm(mt0, mt0, 0x0c000c00u); B0 = __builtin_amdgcn_perm(mt0, mt0, 0x01010101u);
+            S1 = __builtin_amdgcn_perm(mt1, mt1, 0x0c000c00u); B1 = __builtin_amdgcn_perm(mt1, mt1, 0x01010101u);
+        }
+        const uint4* slab = aring[slot][e];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i a_op[MF];
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(slab[(mf * 2 + ks) * 64 + a_src]);
+            const v4i w0 = dequant<GROUP>(ks ? wq0.z : wq0.x, ks ? wq0.w : wq0.y, S0, B0);
+            const v4i w1 = dequant<GROUP>(ks ? wq1.z : wq1.x, ks ? wq1.w : wq1.y, S1, B1);
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                acc[0][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, a_op[mf], acc[0][mf], 0, 0, 0);
+                acc[1][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, a_op[mf], acc[1][mf], 0, 0, 0);
+            }
+        }
+    };
+
+#pragma unroll
+    for (int k = 0; k < kRing - 1; ++k) issue(k);
+    if (wave == 11 && lane < 16 * MF) {
+        const int m = min(m0 + lane, p.M - 1);
+        sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
+        rs_lds[lane] = GROUP ? 0 : p.rowsum[m];
+    }
+    // copies per iteration: consumers 4; producers 4 activation blocks + 2 (metadata, or scales) or + 1 (zero bytes)
+    const int my_dma = !producer ? 4
+                     : kAHalf + ((GROUP && ph == 0) ? 2 : 0) + ((pk == 0 && ph == 1) ? 2 : 0) + ((!GROUP && pk == 1 && ph == 1) ? 1 : 0);
+    int sb = sb0, g = 0, slot = 0;
+    for (int it = 0; it < T; ++it) {
+        if (my_dma == 4) wait_vmcnt<(kRing - 2) * 4>();
+        else if (my_dma == 5) wait_vmcnt<(kRing - 2) * 5>();
+        else wait_vmcnt<(kRing - 2) * 6>();
+        __syncthreads();
+        issue(slot == 0 ? kRing - 1 : slot - 1);
+        if (!producer) {
+            compute(slot, 0);
+            if (g + 1 < G) compute(slot, 1);
+            if (g + 2 >= G) {                          // the quad is finished: this wave's 32 channels x 64 tokens
+                const char* sc = reinterpret_cast<const char*>(&sring[slot][0]);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int f = 2 * w8 + i;          // fragment of the quad: block f / 4, fragment f % 4 of it
+                    const int nl = (f >> 2) * 64 + 16 * q + 4 * (f & 3);
+                    const uint2 sw = *reinterpret_cast<const uint2*>(sc + nl * 2);
+                    float sn[4];
+                    int zn[4] = {0, 0, 0, 0};
+                    if (!GROUP) {
+                        const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 512 + nl);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
+                    }
+                    sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
+                    sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
+                    sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
+                    sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
+#pragma unroll
+                    for (int mf = 0; mf < MF; ++mf) {
+                        const int m = m0 + mf * 16 + ml;
+                        if (m < p.M) finish4<GROUP, OUT>(p, m, sb * 256 + nl, acc[i][mf], sn, zn, sx_lds[mf * 16 + ml], rs_lds[mf * 16 + ml]);
+                        acc[i][mf] = (v4i){0, 0, 0, 0};
+                    }
+                }
+            }
+        }
+        g += 2;
+        if (g >= G) { g = 0; ++sb; }
+        slot = slot + 1 == kRing ? 0 : slot + 1;
+    }
+    wait_vmcnt<0>();   // tail copies still target the rings
+}
+
+// ------------------------------------------------------------------------------------------
 // "mma" kernel (compute bound, M > 64).  Four waves per workgroup, exactly one per SIMD; a wave owns
 // 128 tokens x (32 * CF) channels in 4 x CF accumulator tiles of v_mfma_i32_32x32x32_i8 (CF = 4: 256
 // accumulator registers per lane).  Four workgroup shapes share the code:
@@ -1582,7 +1762,11 @@ void launch_mma(const GemmDev& p, bool fp16, hipStream_t s)
 template <bool GROUP>
 void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
-    if (tile_m == 65) {
+    if (tile_m == 66) {
+        const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
+        if (fp16) qstream_kernel<GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else qstream_kernel<GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+    } else if (tile_m == 65) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
         if (fp16) pstream_kernel<GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
         else pstream_kernel<GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
@@ -1645,7 +1829,7 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
     const double light = tile_m == 128 ? 1.18 : tile_m == 131 ? 0.92 : tile_m == 130 ? 0.64 : 0.62;
     const double per_group = light * (1.0 + 0.45 * load * load);
     return (double)rounds * (8.0 + per_group * (double)((G + S - 1) / S)) +
-           (S > 1 ? (tile_m == 128 ? 30.0 : tile_m == 131 ? 22.0 : 14.0) : 0.0);
+           (S > 1 ? (tile_m == 128 ? 30.0 : tile_m == 131 ? 22.0 : 9.0) : 0.0);
 }
 
 // Streaming kernels: partition and cost of running `tile`-token tiles, in microseconds (fitted to measurements of the
@@ -1658,6 +1842,7 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 // workgroup, no partial tiles), whichever is estimated cheaper.
 // One iteration of the pair-streaming kernel (two blocks x two groups), microseconds (measured 0.79 - 0.94).
 constexpr double kPairIteration = 0.88;
+constexpr double kQuadIteration = 1.40;   // four blocks x two groups (measured 1.4 - 1.7)
 struct StreamPlan { int64_t nwg; double cost; };
 static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t forced_nwg)
 {
@@ -1701,9 +1886,9 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t
 
 // Pair-streaming kernel: whole pairs of blocks per workgroup, kp of them; one iteration = two blocks x two groups; all
 // 64-token tiles of the launch together fill the chip once.
-static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg)
+static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg, int nb = 2)
 {
-    const int64_t pairs = N / 128, m_tiles = (M + 63) / 64;
+    const int64_t pairs = N / (64 * nb), m_tiles = (M + 63) / 64;   // nb = 4: the quad-streaming kernel
     const int64_t kp = forced_nwg > 0 ? (pairs + std::min(forced_nwg, pairs) - 1) / std::min(forced_nwg, pairs)
                                       : std::min(pairs, (pairs * m_tiles + 255) / 256);
     const int64_t nwg = (pairs + kp - 1) / kp;
@@ -1711,8 +1896,8 @@ static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg)
     const double weight_mb = (double)N * (double)G * (double)kGroup / 2.0e6;
     const double miss = std::min(1.0, weight_mb / 32.0);
     const double reads = (nwg % 8 == 0 && rounds == 1) ? 1.0 + miss * (double)(m_tiles - 1) : (double)m_tiles;
-    const double loop = (double)rounds * ((double)(kp * ((G + 1) / 2)) * kPairIteration + (double)(kp - 1) * 0.3) +
-                        (double)(rounds - 1) * 1.5;
+    const double loop = (double)rounds * ((double)(kp * ((G + 1) / 2)) * (nb == 2 ? kPairIteration : kQuadIteration) +
+                                          (double)(kp - 1) * 0.3) + (double)(rounds - 1) * 1.5;
     return {nwg, 4.3 + std::max(loop, weight_mb * reads / 4.5)};
 }
 
@@ -1730,10 +1915,17 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
     if (tile_m == 65 && !pairs_ok) tile_m = 64;
-    const bool pair_wins = pairs_ok && stream_tile == 64 && pair_plan(M, N, G, 0).cost < 0.97 * plan.cost;
-    if (!forced.tile_m && M <= 64 && pair_wins) tile_m = 65;
-    if (tile_m == 65) {
-        split_k = (int)pair_plan(M, N, G, forced.split_k).nwg;
+    const bool quads_ok = N % 256 == 0;
+    if (tile_m == 66 && !quads_ok) tile_m = pairs_ok ? 65 : 64;
+    // block pairs or quads in lockstep, when cheaper than the single-block plan
+    int lock = 0;                                            // 0 = none, 65 = pairs, 66 = quads
+    double lock_cost = 0.97 * plan.cost;
+    if (stream_tile == 64 && pairs_ok && pair_plan(M, N, G, 0).cost < lock_cost) { lock = 65; lock_cost = pair_plan(M, N, G, 0).cost; }
+    if (stream_tile == 64 && quads_ok && pair_plan(M, N, G, 0, 4).cost < 0.97 * lock_cost) { lock = 66; lock_cost = pair_plan(M, N, G, 0, 4).cost; }
+    const bool pair_wins = lock != 0;
+    if (!forced.tile_m && M <= 64 && pair_wins) tile_m = lock;
+    if (tile_m == 65 || tile_m == 66) {
+        split_k = (int)pair_plan(M, N, G, forced.split_k, tile_m == 65 ? 2 : 4).nwg;
         return;
     }
     if (!forced.tile_m && M > 64) {
@@ -1745,10 +1937,10 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
             const double c = mma_cost(M, N, G, cand, S);
             if (c < 0.98 * best) { best = c; tile_m = cand; }
         }
-        const double stream_cost = pair_wins ? pair_plan(M, N, G, 0).cost : plan.cost;
-        if (stream_cost < 0.9 * best) tile_m = pair_wins ? 65 : stream_tile;
-        if (tile_m == 65) {
-            split_k = (int)pair_plan(M, N, G, 0).nwg;
+        const double stream_cost = pair_wins ? lock_cost : plan.cost;
+        if (stream_cost < (pair_wins ? 0.95 : 0.9) * best) tile_m = pair_wins ? lock : stream_tile;
+        if (tile_m == 65 || tile_m == 66) {
+            split_k = (int)pair_plan(M, N, G, 0, tile_m == 65 ? 2 : 4).nwg;
             return;
         }
     }
@@ -1764,7 +1956,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
 {
-    if (tile_m == 65) return 0;                        // whole block pairs per workgroup: nothing is exchanged
+    if (tile_m == 65 || tile_m == 66) return 0;        // whole block pairs / quads per workgroup: nothing is exchanged
     if (tile_m <= 64) {
         const int64_t m_tiles = (M + tile_m - 1) / tile_m;
         const int64_t units = (N / 64) * (K / kGroup);
@@ -1799,9 +1991,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     p.counters = reinterpret_cast<int*>(a.workspace);
     int nwg = 0;
     size_t counters;
-    if (a.tile_m == 65) {
-        if (a.N % 128 != 0) return hipErrorInvalidValue;
-        const int64_t pairs = a.N / 128;
+    if (a.tile_m == 65 || a.tile_m == 66) {
+        const int64_t width = a.tile_m == 65 ? 128 : 256;
+        if (a.N % width != 0) return hipErrorInvalidValue;
+        const int64_t pairs = a.N / width;
         p.upw = (int)((pairs + a.split_k - 1) / a.split_k);   // whole block pairs per workgroup
         nwg = a.split_k;
         p.S = 1; p.gps = (int)L.G;

@@ -203,6 +203,28 @@ def test_group_pair_streaming_kernel(api, M, N, K, split_k):
     run_group_case(api, M, N, K, seed=41 + M, tile_m=65, split_k=split_k)
 
 
+@pytest.mark.parametrize("M,N,K,split_k,mode", [(64, 1280, 1152, 0, 0), (1, 768, 1152, 1, 0), (17, 1280, 1152, 3, 1), (100, 768, 640, 2, 0),
+                                                (150, 512, 128, 0, 1), (64, 512, 384, 2, 0), (63, 2560, 2048, 0, 1), (64, 256, 256, 0, 0),
+                                                (64, 640, 1152, 0, 0)])
+def test_quad_streaming_kernel(api, M, N, K, split_k, mode):
+    """The kernel that streams four adjacent blocks in lockstep, in both modes: several quads per workgroup, one
+    group and an odd number of groups, ragged and several token tiles, a single quad; the last case is not a
+    multiple of 256 channels, for which the library falls back to block pairs."""
+    w, x = rand_inputs(M, N, K, seed=77 + M + N)
+    ref = (ogemm.forward_per_channel if mode else ogemm.forward_group)(_np(w), _np(x))
+    blob = api.pack_weights(w, mode)
+    qx, sx, rowsum, _ = api.quant_act_per_token(x)
+    api.set_gemm_config(66, split_k)
+    try:
+        acc = api.w4a8_gemm_i32(qx, blob, N, mode, rowsum=rowsum)
+        out = api.w4a8_gemm(qx, sx, blob, N, mode, rowsum=rowsum)
+        torch.cuda.synchronize()
+    finally:
+        api.set_gemm_config(0, 0)
+    assert (_np(acc).astype(np.int64) == ref["acc"]).all()
+    check_fp16(out, ref["out64"])
+
+
 @pytest.mark.parametrize("M,tile_m,split_k", [(256, 64, 0), (256, 64, 8), (200, 32, 6), (320, 64, 12)])
 def test_group_streaming_kernel_many_token_tiles(api, M, tile_m, split_k):
     """The M <= 64 kernel forced onto several token tiles, with runs that end exactly at a block end and
