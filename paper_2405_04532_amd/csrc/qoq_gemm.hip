@@ -841,28 +841,38 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 }
 
 // ------------------------------------------------------------------------------------------
-// Pair-streaming kernel (64-token tiles, wide layers).  Same copy scheme as the LDS-staged kernel, but a
-// workgroup works on TWO adjacent 64-channel blocks in lockstep and the consumer waves are cut differently: wave
-// (fp, e) takes fragments 2fp and 2fp + 1 of the pair's eight and, in every iteration, the group of parity e.  The
-// two activation slabs an iteration stages serve both blocks (half the activation bytes through the vector cache
-// per byte of weights, half the barriers), and a wave reads a slab from LDS once for two fragments (80 KiB of LDS
-// reads per 16 KiB of weights instead of 144): the two limits of the single-block loop move together.  At the end
-// of a pair the parity-1 waves hand their sums to the parity-0 waves through LDS, which run the epilogue.
-// Workgroups own whole pairs (p.upw of them, all K): no partial tiles, no workspace.  The host picks this kernel
-// only where whole pairs still fill the chip (N / 128 of the order of the CU count or more).
+// Lockstep-streaming kernel (64-token tiles, wide layers or a few hundred tokens).  Same copy scheme as the LDS-staged
+// kernel, but a workgroup works on NB = 2 or 4 adjacent 64-channel blocks at once, so that the two activation slabs
+// an iteration stages serve all of them: per byte of weights 1/NB of the activation bytes go through the vector
+// cache, and 1/NB of the barriers are met.  Every consumer wave takes two of the 4 * NB fragments.
+//   NB = 2 ("pairs"): wave (fp, e) takes fragments 2fp, 2fp + 1 and, in every iteration, the group of parity e: a
+//       slab is read from LDS once per two fragments (80 KiB of LDS reads per 16 KiB of weights instead of the 144 a
+//       wave-per-fragment cut needs, which made a first version no faster than the single-block kernel); at the end
+//       of a pair the parity-1 waves hand their sums to the parity-0 waves through LDS, which run the epilogue.
+//   NB = 4 ("quads"): wave w takes fragments 2w, 2w + 1 and both groups; no wave needs another's sums; 160 KiB of LDS
+//       reads per 32 KiB of weights stay below what the copies cost.
+// Workgroups own whole pairs / quads (p.upw of them, all K): no partial tiles, no workspace.  N % (64 * NB) == 0.
+// The host picks this kernel where that many whole pairs / quads, times the token tiles, still fill the chip.
 // ------------------------------------------------------------------------------------------
-template <bool GROUP, int OUT>
-__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void pstream_kernel(GemmDev p)
+template <int NB, bool GROUP, int OUT>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void lockstep_kernel(GemmDev p)
 {
+    static_assert(NB == 2 || NB == 4, "pairs or quads");
+    constexpr bool kParity = NB == 2;                  // consumer waves split the two groups of an iteration between them
     constexpr int MF = 4;
     constexpr int kRing = 3;
     constexpr int kABlocks = 2 * MF;                   // 1 KiB blocks (m-fragment, k-step) per group
     constexpr int kAHalf = kABlocks / 2;
-    __shared__ uint4 wring[8][kRing][2][64];           // per consumer wave: the units of its two fragments
+    constexpr int kWUnits = kParity ? 2 : 4;           // weight units a consumer wave copies per iteration
+    constexpr int kMetaBytes = NB * 128;               // per group: 4 * NB fragments x 16 rows x uint16
+    constexpr int kScaleBytes = NB * 128, kZeroBytes = NB * 64;
+    constexpr int kMetaCopies = kMetaBytes / 256, kScaleCopies = kScaleBytes / 256;   // a copy moves 256 B; zero bytes: one copy
+    constexpr int kSSlot = kScaleBytes + 256;          // scales, then the zero bytes (a 256-byte copy even where 128 are used)
+    __shared__ uint4 wring[8][kRing][kWUnits][64];     // per consumer wave: [fragment] (pairs) or [group][fragment] (quads)
     __shared__ uint4 aring[kRing][2][kABlocks * 64];   // activation slabs of the iteration's two groups
-    __shared__ uint4 mring[kRing][2][16];              // level-2 metadata: 8 fragments x 16 rows x uint16 per group
-    __shared__ uint4 sring[kRing][32];                 // the pair's 128 FP16 scales (256 B); 128 zero bytes, copied twice (a copy fills 256 B)
-    __shared__ int4 red[4][2 * MF * 64];               // sums of the parity-1 waves at the end of a pair
+    __shared__ uint4 mring[kRing][2][kMetaBytes / 16];
+    __shared__ uint4 sring[kRing][kSSlot / 16];
+    __shared__ int4 red[kParity ? 4 : 1][kParity ? 2 * MF * 64 : 1];   // pairs: sums of the parity-1 waves at the end of a pair
     __shared__ float sx_lds[16 * MF];
     __shared__ int rs_lds[16 * MF];
 
@@ -870,15 +880,16 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool producer = wave >= 8;
     const int pk = wave & 1, ph = (wave >> 1) & 1;     // producer: group of the iteration, half of its activation blocks
-    const int e = wave & 1, fp = (wave & 7) >> 1;      // consumer: group parity, fragment pair
+    const int w8 = wave & 7;
+    const int e = kParity ? (w8 & 1) : 0;              // pairs: the consumer's group parity
+    const int frag0 = kParity ? 2 * (w8 >> 1) : 2 * w8;   // the consumer's first fragment
     const int m0 = blockIdx.y * (16 * MF);
     const int G = p.G;
-    const int pairs = p.N / 128;
-    const int sb0 = min(pairs, (int)blockIdx.x * p.upw), sb1 = min(pairs, sb0 + p.upw);
+    const int sets = p.N / (64 * NB);                  // pairs or quads of blocks
+    const int sb0 = min(sets, (int)blockIdx.x * p.upw), sb1 = min(sets, sb0 + p.upw);
     if (sb0 >= sb1) return;
     const int q = lane >> 4, ml = lane & 15;
-    const int itpb = (G + 1) / 2;                      // iterations per pair
-    const int T = (sb1 - sb0) * itpb;
+    const int T = (sb1 - sb0) * ((G + 1) / 2);
 
     v4i acc[2][MF];
 #pragma unroll
@@ -899,21 +910,24 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
         }
     }
     const uint32_t lane4 = (uint32_t)lane * 4u, lane16 = (uint32_t)lane * 16u;
-    const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0][0] + (uint32_t)(wave & 7) * (kRing * 2048);
+    const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0][0] + (uint32_t)w8 * (kRing * kWUnits * 1024);
     const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)(pk * kABlocks + ph * kAHalf) * 1024u;
-    const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * 256;
+    const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * kMetaBytes;
     const uint32_t sring_addr = (uint32_t)(uintptr_t)&sring[0][0];
-    constexpr uint32_t kASlot = 2 * kABlocks * 1024;
+    constexpr uint32_t kASlot = 2 * kABlocks * 1024, kWSlot = kWUnits * 1024, kMSlot = 2 * kMetaBytes;
     const char* abase = reinterpret_cast<const char*>(p.qx);
     const char* sbase = reinterpret_cast<const char*>(p.scales);
+    const char* zbase = reinterpret_cast<const char*>(p.zeros);
     const char* codes_base = reinterpret_cast<const char*>(p.codes);
     const char* meta_base = reinterpret_cast<const char*>(p.meta);
     const uint32_t m_g_stride = (uint32_t)(p.N / 16) * 32u;
+    // the 128 zero bytes of a pair fill half a copy: the upper lanes repeat them
+    const uint32_t z_voff = kZeroBytes == 256 ? lane4 : (uint32_t)(lane & 31) * 4u;
 
     // The copy front runs kRing - 1 iterations ahead of the iteration being consumed; past the end of the run it
     // stays on the last iteration (every iteration issues the same number of copies, and a repeated copy reads
     // valid memory into a slot nobody reads any more).
-    int csb = sb0, cg = 0, cleft = T;                  // pair, first group, iterations left at the copy front
+    int csb = sb0, cg = 0, cleft = T;                  // set, first group, iterations left at the copy front
     auto issue = [&](int slot) __attribute__((always_inline)) {
         const int two = cg + 1 < G ? 1 : 0;            // the iteration has a second group
         if (producer) {
@@ -921,15 +935,31 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
             for (int b = 0; b < kAHalf; ++b)
                 dma16(abase, a_voff[b] + gsel * (uint32_t)kGroup, aring_addr + slot * kASlot + b * 1024);
-            if (GROUP && ph == 0) dma4(meta_base, lane4 + gsel * m_g_stride + (uint32_t)csb * 256u, mring_addr + slot * 512);
-            if (pk == 0 && ph == 1) dma4(sbase, lane4 + (uint32_t)csb * 256u, sring_addr + slot * 512);
-            if (!GROUP && pk == 1 && ph == 1)          // 128 zero bytes; the upper lanes repeat them
-                dma4(reinterpret_cast<const char*>(p.zeros), (uint32_t)(lane & 31) * 4u + (uint32_t)csb * 128u, sring_addr + slot * 512 + 256);
+            if (GROUP && ph == 0) {
+#pragma unroll
+                for (int c = 0; c < kMetaCopies; ++c)
+                    dma4(meta_base, lane4 + gsel * m_g_stride + (uint32_t)csb * kMetaBytes + c * 256u, mring_addr + slot * kMSlot + c * 256);
+            }
+            if (pk == 0 && ph == 1) {
+#pragma unroll
+                for (int c = 0; c < kScaleCopies; ++c)
+                    dma4(sbase, lane4 + (uint32_t)csb * kScaleBytes + c * 256u, sring_addr + slot * kSSlot + c * 256);
+            }
+            if (!GROUP && pk == 1 && ph == 1) dma4(zbase, z_voff + (uint32_t)csb * kZeroBytes, sring_addr + slot * kSSlot + kScaleBytes);
         } else {
-            const uint32_t gsel = (uint32_t)(cg + (e & two));
-            const uint32_t unit = ((uint32_t)(csb * 8 + 2 * fp) * (uint32_t)G + gsel) << 10;
-            dma16(codes_base, lane16 + unit, wring_addr + slot * 2048);
-            dma16(codes_base, lane16 + unit + ((uint32_t)G << 10), wring_addr + slot * 2048 + 1024);   // next fragment
+            const uint32_t nf = (uint32_t)G << 10;      // the next fragment's units lie G KiB further
+            if constexpr (kParity) {
+                const uint32_t unit = ((uint32_t)(csb * (4 * NB) + frag0) * (uint32_t)G + (uint32_t)(cg + (e & two))) << 10;
+                dma16(codes_base, lane16 + unit, wring_addr + slot * kWSlot);
+                dma16(codes_base, lane16 + unit + nf, wring_addr + slot * kWSlot + 1024);
+            } else {
+                const uint32_t unit = ((uint32_t)(csb * (4 * NB) + frag0) * (uint32_t)G + (uint32_t)cg) << 10;
+                const uint32_t ng = (uint32_t)two << 10;   // the next group's unit follows (the same one again on an odd tail)
+                dma16(codes_base, lane16 + unit, wring_addr + slot * kWSlot);
+                dma16(codes_base, lane16 + unit + nf, wring_addr + slot * kWSlot + 1024);
+                dma16(codes_base, lane16 + unit + ng, wring_addr + slot * kWSlot + 2048);
+                dma16(codes_base, lane16 + unit + ng + nf, wring_addr + slot * kWSlot + 3072);
+            }
         }
         if (cleft > 1) {
             --cleft;
@@ -940,16 +970,17 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 
     const int hsw = ((ml >> 1) ^ (ml >> 2)) & 3;
     const int a_src = 4 * ml + (q ^ hsw);
-    auto compute = [&](int slot) __attribute__((always_inline)) {
-        const uint4 wq0 = wring[wave & 7][slot][0][lane], wq1 = wring[wave & 7][slot][1][lane];
+    auto compute = [&](int slot, int grp) __attribute__((always_inline)) {   // the wave's two fragments x group grp of the iteration
+        const int u = kParity ? 0 : 2 * grp;
+        const uint4 wq0 = wring[w8][slot][u][lane], wq1 = wring[w8][slot][u + 1][lane];
         uint32_t S0 = 0, B0 = 0, S1 = 0, B1 = 0;
         if (GROUP) {
-            const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][e][0]);
-            const uint32_t mt0 = mrow[(2 * fp) * 16 + ml], mt1 = mrow[(2 * fp + 1) * 16 + ml];
+            const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][grp][0]);
+            const uint32_t mt0 = mrow[frag0 * 16 + ml], mt1 = mrow[(frag0 + 1) * 16 + ml];
             S0 = __builtin_amdgcn_perm(mt0, mt0, 0x0c000c00u); B0 = __builtin_amdgcn_perm(mt0, mt0, 0x01010101u);
             S1 = __builtin_amdgcn_perm(mt1, mt1, 0x0c000c00u); B1 = __builtin_amdgcn_perm(mt1, mt1, 0x01010101u);
         }
-        const uint4* slab = aring[slot][e];
+        const uint4* slab = aring[slot][grp];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             v4i a_op[MF];
@@ -961,6 +992,38 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
             for (int mf = 0; mf < MF; ++mf) {
                 acc[0][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, a_op[mf], acc[0][mf], 0, 0, 0);
                 acc[1][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, a_op[mf], acc[1][mf], 0, 0, 0);
+            }
+        }
+    };
+    // epilogue of the wave's two fragments of set sb; `other` = sums to add first (pairs: the parity-1 wave's)
+    auto finish = [&](int sb, int slot, const int4* other) __attribute__((always_inline)) {
+        const char* sc = reinterpret_cast<const char*>(&sring[slot][0]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = frag0 + i;                   // fragment of the set: block f / 4, fragment f % 4 of it
+            const int nl = (f >> 2) * 64 + 16 * q + 4 * (f & 3);
+            const uint2 sw = *reinterpret_cast<const uint2*>(sc + nl * 2);
+            float sn[4];
+            int zn[4] = {0, 0, 0, 0};
+            if (!GROUP) {
+                const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + kScaleBytes + nl);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
+            }
+            sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
+            sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
+            sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
+            sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
+#pragma unroll
+            for (int mf = 0; mf < MF; ++mf) {
+                v4i v = acc[i][mf];
+                if (other) {
+                    const int4 o = other[(i * MF + mf) * 64 + lane];
+                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                }
+                acc[i][mf] = (v4i){0, 0, 0, 0};
+                const int m = m0 + mf * 16 + ml;
+                if (m < p.M) finish4<GROUP, OUT>(p, m, sb * (64 * NB) + nl, v, sn, zn, sx_lds[mf * 16 + ml], rs_lds[mf * 16 + ml]);
             }
         }
     };
@@ -973,235 +1036,39 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
         sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
         rs_lds[lane] = GROUP ? 0 : p.rowsum[m];
     }
-    const int my_dma = producer ? kAHalf + ((GROUP && ph == 0) ? 1 : 0) + ((pk == 0 && ph == 1) ? 1 : 0) +
-                                      ((!GROUP && pk == 1 && ph == 1) ? 1 : 0) : 2;
+    // copies per iteration and wave: consumers kWUnits; producers their activation blocks plus metadata, scales or zero bytes
+    const int my_dma = !producer ? kWUnits
+                     : kAHalf + ((GROUP && ph == 0) ? kMetaCopies : 0) + ((pk == 0 && ph == 1) ? kScaleCopies : 0) +
+                           ((!GROUP && pk == 1 && ph == 1) ? 1 : 0);
     int sb = sb0, g = 0, slot = 0;
     for (int it = 0; it < T; ++it) {
         if (my_dma == 2) wait_vmcnt<(kRing - 2) * 2>();
-        else if (my_dma == kAHalf) wait_vmcnt<(kRing - 2) * kAHalf>();
-        else wait_vmcnt<(kRing - 2) * (kAHalf + 1)>();
-        __syncthreads();
-        issue(slot == 0 ? kRing - 1 : slot - 1);
-        if (!producer && (e == 0 || g + 1 < G)) compute(slot);
-        if (g + 2 >= G) {                              // the pair is finished (uniform over the workgroup)
-            if (!producer && e == 1) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int mf = 0; mf < MF; ++mf) {
-                        red[fp][(i * MF + mf) * 64 + lane] = make_int4(acc[i][mf].x, acc[i][mf].y, acc[i][mf].z, acc[i][mf].w);
-                        acc[i][mf] = (v4i){0, 0, 0, 0};
-                    }
-            }
-            __syncthreads();
-            if (!producer && e == 0) {
-                const char* sc = reinterpret_cast<const char*>(&sring[slot][0]);
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int f = 2 * fp + i;          // fragment of the pair: block f / 4, fragment f % 4 of it
-                    const int nl = (f >> 2) * 64 + 16 * q + 4 * (f & 3);
-                    const uint2 sw = *reinterpret_cast<const uint2*>(sc + nl * 2);
-                    float sn[4];
-                    int zn[4] = {0, 0, 0, 0};
-                    if (!GROUP) {
-                        const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 256 + nl);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
-                    }
-                    sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
-                    sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
-                    sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
-                    sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
-#pragma unroll
-                    for (int mf = 0; mf < MF; ++mf) {
-                        const int4 o = red[fp][(i * MF + mf) * 64 + lane];
-                        v4i v = acc[i][mf];
-                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                        acc[i][mf] = (v4i){0, 0, 0, 0};
-                        const int m = m0 + mf * 16 + ml;
-                        if (m < p.M) finish4<GROUP, OUT>(p, m, sb * 128 + nl, v, sn, zn, sx_lds[mf * 16 + ml], rs_lds[mf * 16 + ml]);
-                    }
-                }
-            }
-        }
-        g += 2;
-        if (g >= G) { g = 0; ++sb; }
-        slot = slot + 1 == kRing ? 0 : slot + 1;
-    }
-    wait_vmcnt<0>();   // tail copies still target the rings
-}
-
-// ------------------------------------------------------------------------------------------
-// Quad-streaming kernel (64-token tiles, very wide layers or a few hundred tokens).  Four adjacent 64-channel blocks
-// per workgroup in lockstep: per byte of weights a quarter of the activation bytes of the single-block kernel go
-// through the vector cache.  Consumer wave w takes fragments 2w and 2w + 1 of the quad's sixteen and BOTH groups
-// of an iteration, so no wave needs another's sums and the end of a quad is a plain epilogue per wave; the LDS reads
-// (160 KiB per 32 KiB of weights) stay below what the copies cost.  Whole quads per workgroup (p.upw of them, all
-// K): no partial tiles, no workspace.  N % 256 == 0.
-// ------------------------------------------------------------------------------------------
-template <bool GROUP, int OUT>
-__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void qstream_kernel(GemmDev p)
-{
-    constexpr int MF = 4;
-    constexpr int kRing = 3;
-    constexpr int kABlocks = 2 * MF;                   // 1 KiB blocks (m-fragment, k-step) per group
-    constexpr int kAHalf = kABlocks / 2;
-    __shared__ uint4 wring[8][kRing][2][2][64];        // per consumer wave: [group][fragment] units of an iteration
-    __shared__ uint4 aring[kRing][2][kABlocks * 64];   // activation slabs of the iteration's two groups
-    __shared__ uint4 mring[kRing][2][32];              // level-2 metadata: 16 fragments x 16 rows x uint16 per group
-    __shared__ uint4 sring[kRing][48];                 // the quad's 256 FP16 scales (512 B) and 256 zero bytes
-    __shared__ float sx_lds[16 * MF];
-    __shared__ int rs_lds[16 * MF];
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const bool producer = wave >= 8;
-    const int pk = wave & 1, ph = (wave >> 1) & 1;     // producer: group of the iteration, half of its activation blocks
-    const int w8 = wave & 7;                           // consumer: fragments 2 * w8, 2 * w8 + 1 of the quad
-    const int m0 = blockIdx.y * (16 * MF);
-    const int G = p.G;
-    const int quads = p.N / 256;
-    const int sb0 = min(quads, (int)blockIdx.x * p.upw), sb1 = min(quads, sb0 + p.upw);
-    if (sb0 >= sb1) return;
-    const int q = lane >> 4, ml = lane & 15;
-    const int T = (sb1 - sb0) * ((G + 1) / 2);
-
-    v4i acc[2][MF];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int mf = 0; mf < MF; ++mf) acc[i][mf] = (v4i){0, 0, 0, 0};
-
-    uint32_t a_voff[kAHalf];
-    {
-        const int r = lane >> 2, c = lane & 3;
-        const int h = ((r >> 1) ^ (r >> 2)) & 3;
-#pragma unroll
-        for (int j = 0; j < kAHalf; ++j) {
-            const int b = ph * kAHalf + j;
-            const int row = min(m0 + (b >> 1) * 16 + r, p.M - 1);   // rows past M repeat the last one; never stored
-            a_voff[j] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((b & 1) * 64 + (c ^ h) * 16);
-        }
-    }
-    const uint32_t lane4 = (uint32_t)lane * 4u, lane16 = (uint32_t)lane * 16u;
-    const uint32_t wring_addr = (uint32_t)(uintptr_t)&wring[0][0][0][0][0] + (uint32_t)w8 * (kRing * 4096);
-    const uint32_t aring_addr = (uint32_t)(uintptr_t)&aring[0][0][0] + (uint32_t)(pk * kABlocks + ph * kAHalf) * 1024u;
-    const uint32_t mring_addr = (uint32_t)(uintptr_t)&mring[0][0][0] + (uint32_t)pk * 512;
-    const uint32_t sring_addr = (uint32_t)(uintptr_t)&sring[0][0];
-    constexpr uint32_t kASlot = 2 * kABlocks * 1024;
-    const char* abase = reinterpret_cast<const char*>(p.qx);
-    const char* sbase = reinterpret_cast<const char*>(p.scales);
-    const char* zbase = reinterpret_cast<const char*>(p.zeros);
-    const char* codes_base = reinterpret_cast<const char*>(p.codes);
-    const char* meta_base = reinterpret_cast<const char*>(p.meta);
-    const uint32_t m_g_stride = (uint32_t)(p.N / 16) * 32u;
-
-    // copy front, kRing - 1 iterations ahead; past the end of the run it repeats the last iteration
-    int csb = sb0, cg = 0, cleft = T;
-    auto issue = [&](int slot) __attribute__((always_inline)) {
-        const int two = cg + 1 < G ? 1 : 0;            // the iteration has a second group
-        if (producer) {
-            const uint32_t gsel = (uint32_t)(cg + (pk & two));
-#pragma unroll
-            for (int b = 0; b < kAHalf; ++b)
-                dma16(abase, a_voff[b] + gsel * (uint32_t)kGroup, aring_addr + slot * kASlot + b * 1024);
-            if (GROUP && ph == 0) {                    // 512 B of metadata of the quad for this group
-                const uint32_t moff = lane4 + gsel * m_g_stride + (uint32_t)csb * 512u;
-                dma4(meta_base, moff, mring_addr + slot * 1024);
-                dma4(meta_base, moff + 256u, mring_addr + slot * 1024 + 256);
-            }
-            if (pk == 0 && ph == 1) {
-                dma4(sbase, lane4 + (uint32_t)csb * 512u, sring_addr + slot * 768);
-                dma4(sbase, lane4 + (uint32_t)csb * 512u + 256u, sring_addr + slot * 768 + 256);
-            }
-            if (!GROUP && pk == 1 && ph == 1) dma4(zbase, lane4 + (uint32_t)csb * 256u, sring_addr + slot * 768 + 512);
-        } else {
-            const uint32_t unit = ((uint32_t)(csb * 16 + 2 * w8) * (uint32_t)G + (uint32_t)cg) << 10;
-            const uint32_t nf = (uint32_t)G << 10, ng = (uint32_t)two << 10;   // next fragment, next group
-            dma16(codes_base, lane16 + unit, wring_addr + slot * 4096);
-            dma16(codes_base, lane16 + unit + nf, wring_addr + slot * 4096 + 1024);
-            dma16(codes_base, lane16 + unit + ng, wring_addr + slot * 4096 + 2048);
-            dma16(codes_base, lane16 + unit + ng + nf, wring_addr + slot * 4096 + 3072);
-        }
-        if (cleft > 1) {
-            --cleft;
-            cg += 2;
-            if (cg >= G) { cg = 0; ++csb; }
-        }
-    };
-
-    const int hsw = ((ml >> 1) ^ (ml >> 2)) & 3;
-    const int a_src = 4 * ml + (q ^ hsw);
-    auto compute = [&](int slot, int e) __attribute__((always_inline)) {
-        const uint4 wq0 = wring[w8][slot][e][0][lane], wq1 = wring[w8][slot][e][1][lane];
-        uint32_t S0 = 0, B0 = 0, S1 = 0, B1 = 0;
-        if (GROUP) {
-            const uint16_t* mrow = reinterpret_cast<const uint16_t*>(&mring[slot][e][0]);
-            const uint32_t mt0 = mrow[(2 * w8) * 16 + ml], mt1 = mrow[(2 * w8 + 1) * 16 + ml];
-            S0 = __builtin_amdgcn_perm(mt0, mt0, 0x0c000c00u); B0 = __builtin_amdgcn_perm(mt0, mt0, 0x01010101u);
-            S1 = __builtin_amdgcn_perm(mt1, mt1, 0x0c000c00u); B1 = __builtin_amdgcn_perm(mt1, mt1, 0x01010101u);
-        }
-        const uint4* slab = aring[slot][e];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i a_op[MF];
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) a_op[mf] = as_v4i(slab[(mf * 2 + ks) * 64 + a_src]);
-            const v4i w0 = dequant<GROUP>(ks ? wq0.z : wq0.x, ks ? wq0.w : wq0.y, S0, B0);
-            const v4i w1 = dequant<GROUP>(ks ? wq1.z : wq1.x, ks ? wq1.w : wq1.y, S1, B1);
-#pragma unroll
-            for (int mf = 0; mf < MF; ++mf) {
-                acc[0][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w0, a_op[mf], acc[0][mf], 0, 0, 0);
-                acc[1][mf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w1, a_op[mf], acc[1][mf], 0, 0, 0);
-            }
-        }
-    };
-
-#pragma unroll
-    for (int k = 0; k < kRing - 1; ++k) issue(k);
-    if (wave == 11 && lane < 16 * MF) {
-        const int m = min(m0 + lane, p.M - 1);
-        sx_lds[lane] = OUT == OUT_FP16 ? __half2float(p.sx[m]) : 0.f;
-        rs_lds[lane] = GROUP ? 0 : p.rowsum[m];
-    }
-    // copies per iteration: consumers 4; producers 4 activation blocks + 2 (metadata, or scales) or + 1 (zero bytes)
-    const int my_dma = !producer ? 4
-                     : kAHalf + ((GROUP && ph == 0) ? 2 : 0) + ((pk == 0 && ph == 1) ? 2 : 0) + ((!GROUP && pk == 1 && ph == 1) ? 1 : 0);
-    int sb = sb0, g = 0, slot = 0;
-    for (int it = 0; it < T; ++it) {
-        if (my_dma == 4) wait_vmcnt<(kRing - 2) * 4>();
+        else if (my_dma == 4) wait_vmcnt<(kRing - 2) * 4>();
         else if (my_dma == 5) wait_vmcnt<(kRing - 2) * 5>();
         else wait_vmcnt<(kRing - 2) * 6>();
         __syncthreads();
         issue(slot == 0 ? kRing - 1 : slot - 1);
-        if (!producer) {
-            compute(slot, 0);
-            if (g + 1 < G) compute(slot, 1);
-            if (g + 2 >= G) {                          // the quad is finished: this wave's 32 channels x 64 tokens
-                const char* sc = reinterpret_cast<const char*>(&sring[slot][0]);
+        const bool two = g + 1 < G, last = g + 2 >= G;   // uniform over the workgroup
+        if constexpr (kParity) {
+            if (!producer && (e == 0 || two)) compute(slot, e);
+            if (last) {
+                if (!producer && e == 1) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int f = 2 * w8 + i;          // fragment of the quad: block f / 4, fragment f % 4 of it
-                    const int nl = (f >> 2) * 64 + 16 * q + 4 * (f & 3);
-                    const uint2 sw = *reinterpret_cast<const uint2*>(sc + nl * 2);
-                    float sn[4];
-                    int zn[4] = {0, 0, 0, 0};
-                    if (!GROUP) {
-                        const uint32_t zw = *reinterpret_cast<const uint32_t*>(sc + 512 + nl);
+                    for (int i = 0; i < 2; ++i)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) zn[j] = (int)((zw >> (8 * j)) & 0xFFu);
-                    }
-                    sn[0] = __half2float(__ushort_as_half((unsigned short)(sw.x & 0xFFFFu)));
-                    sn[1] = __half2float(__ushort_as_half((unsigned short)(sw.x >> 16)));
-                    sn[2] = __half2float(__ushort_as_half((unsigned short)(sw.y & 0xFFFFu)));
-                    sn[3] = __half2float(__ushort_as_half((unsigned short)(sw.y >> 16)));
-#pragma unroll
-                    for (int mf = 0; mf < MF; ++mf) {
-                        const int m = m0 + mf * 16 + ml;
-                        if (m < p.M) finish4<GROUP, OUT>(p, m, sb * 256 + nl, acc[i][mf], sn, zn, sx_lds[mf * 16 + ml], rs_lds[mf * 16 + ml]);
-                        acc[i][mf] = (v4i){0, 0, 0, 0};
-                    }
+                        for (int mf = 0; mf < MF; ++mf) {
+                            red[w8 >> 1][(i * MF + mf) * 64 + lane] = make_int4(acc[i][mf].x, acc[i][mf].y, acc[i][mf].z, acc[i][mf].w);
+                            acc[i][mf] = (v4i){0, 0, 0, 0};
+                        }
                 }
+                __syncthreads();
+                if (!producer && e == 0) finish(sb, slot, &red[w8 >> 1][0]);
+            }
+        } else {
+            if (!producer) {
+                compute(slot, 0);
+                if (two) compute(slot, 1);
+                if (last) finish(sb, slot, nullptr);
             }
         }
         g += 2;
@@ -1764,12 +1631,12 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
     if (tile_m == 66) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
-        if (fp16) qstream_kernel<GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
-        else qstream_kernel<GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+        if (fp16) lockstep_kernel<4, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else lockstep_kernel<4, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
     } else if (tile_m == 65) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
-        if (fp16) pstream_kernel<GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
-        else pstream_kernel<GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+        if (fp16) lockstep_kernel<2, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else lockstep_kernel<2, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
     } else if (tile_m <= 64) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + tile_m - 1) / tile_m));
         if (tile_m == 16) launch_stream<1, GROUP>(p, fp16, grid, s);
