@@ -229,7 +229,8 @@ int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int
 /* Test/tuning hook: force the GEMM launch configuration instead of the built-in heuristic.
  * tile_m: 0 = auto; 16, 32, 64 = streaming kernel with that many tokens per tile; 65 = 64 tokens,
  * two adjacent blocks per workgroup in lockstep (N % 128 == 0; else as 64); 66 = four blocks in lockstep
- * (N % 256 == 0; else as 65); 128, 129, 130, 131 =
+ * (N % 256 == 0; else as 65); 67, 68 = two blocks in lockstep with 32 / 16 tokens per tile (else as 32 / 16);
+ * 128, 129, 130, 131 =
  * compute-bound kernel with tiles of 256 x 256, 128 x 256, 256 x 128, 256 x 192 (tokens x channels).
  * split_k >= 0 (0 = auto): for the compute-bound kernel the number of k-slices per output tile, for the
  * streaming kernel the number of workgroups the stream of work units is dealt to.  Process-wide;

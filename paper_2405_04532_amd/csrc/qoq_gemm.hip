@@ -854,12 +854,12 @@ __global__ __launch_bounds__(kRsThreads) void rstream_kernel(GemmDev p)
 // Workgroups own whole pairs / quads (p.upw of them, all K): no partial tiles, no workspace.  N % (64 * NB) == 0.
 // The host picks this kernel where that many whole pairs / quads, times the token tiles, still fill the chip.
 // ------------------------------------------------------------------------------------------
-template <int NB, bool GROUP, int OUT>
+template <int NB, int MF, bool GROUP, int OUT>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void lockstep_kernel(GemmDev p)
 {
     static_assert(NB == 2 || NB == 4, "pairs or quads");
+    static_assert(MF == 1 || MF == 2 || MF == 4, "token tiles of 16, 32 or 64");
     constexpr bool kParity = NB == 2;                  // consumer waves split the two groups of an iteration between them
-    constexpr int MF = 4;
     constexpr int kRing = 3;
     constexpr int kABlocks = 2 * MF;                   // 1 KiB blocks (m-fragment, k-step) per group
     constexpr int kAHalf = kABlocks / 2;
@@ -1042,7 +1042,10 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
                            ((!GROUP && pk == 1 && ph == 1) ? 1 : 0);
     int sb = sb0, g = 0, slot = 0;
     for (int it = 0; it < T; ++it) {
-        if (my_dma == 2) wait_vmcnt<(kRing - 2) * 2>();
+        // (1 ... 6 copies per wave and iteration, depending on role, mode and tile)
+        if (my_dma == 1) wait_vmcnt<(kRing - 2) * 1>();
+        else if (my_dma == 2) wait_vmcnt<(kRing - 2) * 2>();
+        else if (my_dma == 3) wait_vmcnt<(kRing - 2) * 3>();
         else if (my_dma == 4) wait_vmcnt<(kRing - 2) * 4>();
         else if (my_dma == 5) wait_vmcnt<(kRing - 2) * 5>();
         else wait_vmcnt<(kRing - 2) * 6>();
@@ -1631,12 +1634,20 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
     if (tile_m == 66) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
-        if (fp16) lockstep_kernel<4, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
-        else lockstep_kernel<4, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+        if (fp16) lockstep_kernel<4, 4, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else lockstep_kernel<4, 4, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
     } else if (tile_m == 65) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
-        if (fp16) lockstep_kernel<2, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
-        else lockstep_kernel<2, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+        if (fp16) lockstep_kernel<2, 4, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else lockstep_kernel<2, 4, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+    } else if (tile_m == 67) {
+        const dim3 grid((unsigned)nwg, (unsigned)((p.M + 31) / 32));
+        if (fp16) lockstep_kernel<2, 2, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else lockstep_kernel<2, 2, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
+    } else if (tile_m == 68) {
+        const dim3 grid((unsigned)nwg, (unsigned)((p.M + 15) / 16));
+        if (fp16) lockstep_kernel<2, 1, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
+        else lockstep_kernel<2, 1, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
     } else if (tile_m <= 64) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + tile_m - 1) / tile_m));
         if (tile_m == 16) launch_stream<1, GROUP>(p, fp16, grid, s);
@@ -1709,6 +1720,7 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 // workgroup, no partial tiles), whichever is estimated cheaper.
 // One iteration of the pair-streaming kernel (two blocks x two groups), microseconds (measured 0.79 - 0.94).
 constexpr double kPairIteration = 0.88;
+constexpr double kPairIteration32 = 0.70, kPairIteration16 = 0.60;   // pairs with 32- and 16-token tiles
 constexpr double kQuadIteration = 1.40;   // four blocks x two groups (measured 1.4 - 1.7)
 struct StreamPlan { int64_t nwg; double cost; };
 static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t forced_nwg)
@@ -1753,9 +1765,9 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t
 
 // Pair-streaming kernel: whole pairs of blocks per workgroup, kp of them; one iteration = two blocks x two groups; all
 // 64-token tiles of the launch together fill the chip once.
-static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg, int nb = 2)
+static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg, int nb = 2, int tile = 64)
 {
-    const int64_t pairs = N / (64 * nb), m_tiles = (M + 63) / 64;   // nb = 4: the quad-streaming kernel
+    const int64_t pairs = N / (64 * nb), m_tiles = (M + tile - 1) / tile;   // nb = 4: quads
     const int64_t kp = forced_nwg > 0 ? (pairs + std::min(forced_nwg, pairs) - 1) / std::min(forced_nwg, pairs)
                                       : std::min(pairs, (pairs * m_tiles + 255) / 256);
     const int64_t nwg = (pairs + kp - 1) / kp;
@@ -1763,7 +1775,8 @@ static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg,
     const double weight_mb = (double)N * (double)G * (double)kGroup / 2.0e6;
     const double miss = std::min(1.0, weight_mb / 32.0);
     const double reads = (nwg % 8 == 0 && rounds == 1) ? 1.0 + miss * (double)(m_tiles - 1) : (double)m_tiles;
-    const double loop = (double)rounds * ((double)(kp * ((G + 1) / 2)) * (nb == 2 ? kPairIteration : kQuadIteration) +
+    const double t_it = nb == 4 ? kQuadIteration : tile == 64 ? kPairIteration : tile == 32 ? kPairIteration32 : kPairIteration16;
+    const double loop = (double)rounds * ((double)(kp * ((G + 1) / 2)) * t_it +
                                           (double)(kp - 1) * 0.3) + (double)(rounds - 1) * 1.5;
     return {nwg, 4.3 + std::max(loop, weight_mb * reads / 4.5)};
 }
@@ -1782,17 +1795,35 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
     if (tile_m == 65 && !pairs_ok) tile_m = 64;
+    if (tile_m == 67 && !pairs_ok) tile_m = 32;
+    if (tile_m == 68 && !pairs_ok) tile_m = 16;
+    if (tile_m == 67 || tile_m == 68) {                    // pairs with 32- / 16-token tiles
+        split_k = (int)pair_plan(M, N, G, forced.split_k, 2, tile_m == 67 ? 32 : 16).nwg;
+        return;
+    }
     const bool quads_ok = N % 256 == 0;
     if (tile_m == 66 && !quads_ok) tile_m = pairs_ok ? 65 : 64;
     // block pairs or quads in lockstep, when cheaper than the single-block plan
-    int lock = 0;                                            // 0 = none, 65 = pairs, 66 = quads
+    int lock = 0;                                            // 0 = none, 65 = pairs, 66 = quads, 67 / 68 = pairs with 32 / 16-token tiles
     double lock_cost = 0.97 * plan.cost;
     if (stream_tile == 64 && pairs_ok && pair_plan(M, N, G, 0).cost < lock_cost) { lock = 65; lock_cost = pair_plan(M, N, G, 0).cost; }
     if (stream_tile == 64 && quads_ok && pair_plan(M, N, G, 0, 4).cost < 0.97 * lock_cost) { lock = 66; lock_cost = pair_plan(M, N, G, 0, 4).cost; }
+    if (stream_tile == natural && natural < 64 && pairs_ok) {
+        // 32- and 16-token tiles: the register-streaming kernels reach 3.5 / 4.0 TB/s on layers that keep the whole
+        // chip busy (measured), which the plan's estimate does not include
+        const double weight_mb = (double)N * (double)G * (double)kGroup / 2.0e6;
+        const double ref = std::max(plan.cost, 4.3 + weight_mb / (natural == 32 ? 3.5 : 4.0));
+        const double c = pair_plan(M, N, G, 0, 2, natural).cost;
+        if (c < 0.97 * ref) { lock = natural == 32 ? 67 : 68; lock_cost = c; }
+    }
     const bool pair_wins = lock != 0;
     if (!forced.tile_m && M <= 64 && pair_wins) tile_m = lock;
     if (tile_m == 65 || tile_m == 66) {
         split_k = (int)pair_plan(M, N, G, forced.split_k, tile_m == 65 ? 2 : 4).nwg;
+        return;
+    }
+    if (tile_m == 67 || tile_m == 68) {
+        split_k = (int)pair_plan(M, N, G, forced.split_k, 2, tile_m == 67 ? 32 : 16).nwg;
         return;
     }
     if (!forced.tile_m && M > 64) {
@@ -1823,7 +1854,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
 {
-    if (tile_m == 65 || tile_m == 66) return 0;        // whole block pairs / quads per workgroup: nothing is exchanged
+    if (tile_m >= 65 && tile_m <= 68) return 0;        // whole block pairs / quads per workgroup: nothing is exchanged
     if (tile_m <= 64) {
         const int64_t m_tiles = (M + tile_m - 1) / tile_m;
         const int64_t units = (N / 64) * (K / kGroup);
@@ -1858,8 +1889,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     p.counters = reinterpret_cast<int*>(a.workspace);
     int nwg = 0;
     size_t counters;
-    if (a.tile_m == 65 || a.tile_m == 66) {
-        const int64_t width = a.tile_m == 65 ? 128 : 256;
+    if (a.tile_m >= 65 && a.tile_m <= 68) {
+        const int64_t width = a.tile_m == 66 ? 256 : 128;
         if (a.N % width != 0) return hipErrorInvalidValue;
         const int64_t pairs = a.N / width;
         p.upw = (int)((pairs + a.split_k - 1) / a.split_k);   // whole block pairs per workgroup

@@ -203,6 +203,27 @@ def test_group_pair_streaming_kernel(api, M, N, K, split_k):
     run_group_case(api, M, N, K, seed=41 + M, tile_m=65, split_k=split_k)
 
 
+@pytest.mark.parametrize("tile_m", [67, 68])
+@pytest.mark.parametrize("M,N,K,split_k,mode", [(32, 640, 1152, 0, 0), (1, 640, 1152, 1, 1), (17, 640, 1152, 3, 0), (50, 384, 128, 0, 1),
+                                                (16, 384, 384, 2, 0), (31, 1280, 2048, 0, 1), (100, 128, 256, 0, 0), (32, 576, 1152, 0, 0)])
+def test_pair_streaming_kernel_small_token_tiles(api, tile_m, M, N, K, split_k, mode):
+    """Block pairs in lockstep with 32- and 16-token tiles (codes 67, 68), both modes; the last case has an odd
+    number of blocks and falls back to the single-block kernel of that tile."""
+    w, x = rand_inputs(M, N, K, seed=5 + M + N)
+    ref = (ogemm.forward_per_channel if mode else ogemm.forward_group)(_np(w), _np(x))
+    blob = api.pack_weights(w, mode)
+    qx, sx, rowsum, _ = api.quant_act_per_token(x)
+    api.set_gemm_config(tile_m, split_k)
+    try:
+        acc = api.w4a8_gemm_i32(qx, blob, N, mode, rowsum=rowsum)
+        out = api.w4a8_gemm(qx, sx, blob, N, mode, rowsum=rowsum)
+        torch.cuda.synchronize()
+    finally:
+        api.set_gemm_config(0, 0)
+    assert (_np(acc).astype(np.int64) == ref["acc"]).all()
+    check_fp16(out, ref["out64"])
+
+
 @pytest.mark.parametrize("M,N,K,split_k,mode", [(64, 1280, 1152, 0, 0), (1, 768, 1152, 1, 0), (17, 1280, 1152, 3, 1), (100, 768, 640, 2, 0),
                                                 (150, 512, 128, 0, 1), (64, 512, 384, 2, 0), (63, 2560, 2048, 0, 1), (64, 256, 256, 0, 0),
                                                 (64, 640, 1152, 0, 0)])
