@@ -111,13 +111,14 @@ def test_llama2_7b_m_sweep(layer):
     _check_layer("llama2_7b", layer, (8, 32, 128, 256, 512, 1024, 2048, 4096), api.QOQ_GROUP128, 2, samples=32)
 
 
-# C3: Llama-3-70B-shaped layers with heavy-tailed outlier channels.
+# C3: Llama-3-70B-shaped layers with heavy-tailed outlier channels (plus the decode and few-hundred-token sizes at
+# which the widest layers run blocks in lockstep).
 @pytest.mark.parametrize("layer", list(wl.LLAMA3_70B))
 def test_llama3_70b(layer):
-    _check_layer("llama3_70b", layer, (512, 2048), api.QOQ_GROUP128, 3, samples=32)
+    _check_layer("llama3_70b", layer, (64, 192, 512, 2048), api.QOQ_GROUP128, 3, samples=32)
 
 
 # C4: per-channel variant on Llama-3-8B-shaped layers.
 @pytest.mark.parametrize("layer", list(wl.LLAMA3_8B))
 def test_llama3_8b_per_channel(layer):
-    _check_layer("llama3_8b", layer, (64, 1024), api.QOQ_PER_CHANNEL, 4, samples=32)
+    _check_layer("llama3_8b", layer, (64, 256, 1024), api.QOQ_PER_CHANNEL, 4, samples=32)
