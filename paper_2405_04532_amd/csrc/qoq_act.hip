@@ -55,6 +55,25 @@ __device__ __forceinline__ float wave_sum_f32(float v)
            (__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)) + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48)));
 }
 
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+    auto moved = [](double d, auto ctrl) {
+        const long long b = __double_as_longlong(d);
+        const int lo = dpp_i32<decltype(ctrl)::value>((int)(b & 0xFFFFFFFFll)), hi = dpp_i32<decltype(ctrl)::value>((int)(b >> 32));
+        return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+    };
+    v += moved(v, std::integral_constant<int, kQuadSwap1>());
+    v += moved(v, std::integral_constant<int, kQuadSwap2>());
+    v += moved(v, std::integral_constant<int, kRowHalfMirror>());
+    v += moved(v, std::integral_constant<int, kRowMirror>());
+    auto lane = [](double d, int l) {
+        const long long b = __double_as_longlong(d);
+        const int lo = __builtin_amdgcn_readlane((int)(b & 0xFFFFFFFFll), l), hi = __builtin_amdgcn_readlane((int)(b >> 32), l);
+        return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+    };
+    return (lane(v, 0) + lane(v, 16)) + (lane(v, 32) + lane(v, 48));
+}
+
 // round_half_away(x / s), clamped to [-127, 127], for FP16 values x and s > 0 (held in FP32), without a division.
 // x and s have 11-bit significands, so the exact quotient is either exactly on a rounding midpoint k + 1/2 or at
 // least 2^-12 away from every midpoint (|x / s| < 256); x * fl(1 / s) is within 3e-5 of the quotient, and pushing
@@ -280,6 +299,37 @@ __device__ inline uint4 pack8(const double (&f)[8])
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// FP16 bits of a producer's output when an FP32 evaluation `p` of it is known to lie within `margin` FP32 units in
+// the last place of the FP64 value that defines the result: if p is further than that from every FP16 rounding
+// midpoint (the 13 dropped mantissa bits = 0x1000) and the result is a normal FP16 number, rounding p gives the same
+// bits as rounding the FP64 value, and the (much slower) FP64 evaluation is skipped.  Otherwise returns false: the
+// caller evaluates in FP64.  About margin / 4096 of the elements take that path.
+__device__ __forceinline__ bool half_bits_from_approx(float p, uint32_t margin, uint32_t& bits)
+{
+    const uint32_t u = __float_as_uint(p), a = u & 0x7FFFFFFFu;
+    if (a < 0x38800800u || a > 0x477D0000u) return false;   // |p| < 2^-14 (1 + 2^-12) or > 64768: subnormal, zero, overflow, NaN
+    const uint32_t low = u & 0x1FFFu;
+    const uint32_t d = low > 0x1000u ? low - 0x1000u : 0x1000u - low;
+    if (d <= margin) return false;
+    bits = (uint32_t)__half_as_ushort(__float2half_rn(p));
+    return true;
+}
+
+// Element idx (chunk idx / 8, half idx % 8) of the cached chunks := bits.  Written as compile-time indexed selects: a
+// register array indexed at run time would be moved to scratch memory.
+template <int CACHE>
+__device__ __forceinline__ void patch_half(uint4 (&v)[CACHE], int idx, uint32_t bits)
+{
+#pragma unroll
+    for (int i = 0; i < CACHE; ++i) {
+        uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (idx == i * 8 + j) w[j >> 1] = (w[j >> 1] & ~(0xFFFFu << (16 * (j & 1)))) | (bits << (16 * (j & 1)));
+        v[i] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // y = x * (1 / sqrt(mean(x^2) + eps)) * gamma
 template <int CACHE>
 __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __restrict__ x, const __half* __restrict__ gamma,
@@ -294,36 +344,61 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
     const uint4* row = reinterpret_cast<const uint4*>(x + m * K);
     const uint4* grow = reinterpret_cast<const uint4*>(gamma);
     const int chunks = (int)(K / 8);
-    uint4 v[CACHE];
+    uint4 v[CACHE], gv[CACHE];                         // the weights are fetched with the row, not after the reduction
     double ss = 0.0;
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
         const int c = (int)threadIdx.x + i * kWide;
         v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
+        gv[i] = c < chunks ? grow[c] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int i = 0; i < CACHE; ++i) {
         double f[8];
         unpack8(v[i], f);
 #pragma unroll
         for (int j = 0; j < 8; ++j) ss += f[j] * f[j];
     }
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    ss = wave_sum_f64(ss);
     if ((threadIdx.x & 63) == 0) s_d[threadIdx.x >> 6] = ss;
     __syncthreads();
     ss = 0.0;
 #pragma unroll
     for (int w = 0; w < kWide / 64; ++w) ss += s_d[w];
     const double inv = 1.0 / sqrt(ss / (double)K + eps);
+    const float inv32 = (float)inv;
+    uint64_t risky = 0;                                // elements to redo in FP64, bit = chunk * 8 + half
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
         const int c = (int)threadIdx.x + i * kWide;
         if (c < chunks) {
-            double f[8], g[8];
-            unpack8(v[i], f);
-            const uint4 gv = grow[c];
-            unpack8(gv, g);
+            const __half* hx = reinterpret_cast<const __half*>(&v[i]);
+            const __half* hg = reinterpret_cast<const __half*>(&gv[i]);
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int j = 0; j < 8; ++j) f[j] = f[j] * inv * g[j];
-            v[i] = pack8(f);
-            if (y) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
+            for (int j = 0; j < 8; ++j) {
+                // FP32 first: (x * fl32(r)) * gamma is within 3 units in the last place of the FP64 product
+                const float fx = __half2float(hx[j]), fg = __half2float(hg[j]);
+                uint32_t b = 0;
+                if (!half_bits_from_approx((fx * inv32) * fg, 8u, b)) risky |= 1ull << (i * 8 + j);
+                w[j >> 1] |= b << (16 * (j & 1));
+            }
+            v[i] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+    // the few elements (about 1 in 500) whose FP32 value is too close to a rounding midpoint: FP64, one at a time
+    while (risky) {
+        const int idx = __ffsll((unsigned long long)risky) - 1;
+        risky &= risky - 1;
+        const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * kWide) * 8 + (idx & 7);
+        const double fx = (double)__half2float(x[m * K + k]), fg = (double)__half2float(gamma[k]);
+        patch_half(v, idx, (uint32_t)double_to_half_rne(fx * inv * fg));
+    }
+    if (y) {
+#pragma unroll
+        for (int i = 0; i < CACHE; ++i) {
+            const int c = (int)threadIdx.x + i * kWide;
+            if (c < chunks) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
         }
     }
     quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
@@ -343,19 +418,41 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
     const uint4* urow = reinterpret_cast<const uint4*>(gate_up + m * 2 * K + K);
     const int chunks = (int)(K / 8);
     uint4 v[CACHE];
+    uint64_t risky = 0;                                // elements to redo in FP64, bit = chunk * 8 + half
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
         const int c = (int)threadIdx.x + i * kWide;
         v[i] = make_uint4(0u, 0u, 0u, 0u);
         if (c < chunks) {
-            double g[8], u[8];
             const uint4 gv = grow[c], uv = urow[c];
-            unpack8(gv, g);
-            unpack8(uv, u);
+            const __half* hg = reinterpret_cast<const __half*>(&gv);
+            const __half* hu = reinterpret_cast<const __half*>(&uv);
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int j = 0; j < 8; ++j) g[j] = g[j] / (1.0 + exp(-g[j])) * u[j];
-            v[i] = pack8(g);
-            if (y) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
+            for (int j = 0; j < 8; ++j) {
+                // FP32 first: expf, one addition, a correctly rounded division and a product stay within a few
+                // units in the last place of the FP64 value; 24 are allowed for
+                const float fg = __half2float(hg[j]), fu = __half2float(hu[j]);
+                uint32_t b = 0;
+                if (!half_bits_from_approx(fg / (1.0f + expf(-fg)) * fu, 24u, b)) risky |= 1ull << (i * 8 + j);
+                w[j >> 1] |= b << (16 * (j & 1));
+            }
+            v[i] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+    // the few elements (about 1 in 150) whose FP32 value is too close to a rounding midpoint: FP64, one at a time
+    while (risky) {
+        const int idx = __ffsll((unsigned long long)risky) - 1;
+        risky &= risky - 1;
+        const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * kWide) * 8 + (idx & 7);
+        const double dg = (double)__half2float(gate_up[m * 2 * K + k]), du = (double)__half2float(gate_up[m * 2 * K + K + k]);
+        patch_half(v, idx, (uint32_t)double_to_half_rne(dg / (1.0 + exp(-dg)) * du));
+    }
+    if (y) {
+#pragma unroll
+        for (int i = 0; i < CACHE; ++i) {
+            const int c = (int)threadIdx.x + i * kWide;
+            if (c < chunks) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
         }
     }
     quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);

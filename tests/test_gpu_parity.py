@@ -483,6 +483,24 @@ def test_silu_mul_quant_matches_oracle(api, M, K):
     assert np.allclose(_np(tx), rtx, rtol=1e-4, atol=1e-2)
 
 
+def test_fused_producers_many_elements_bit_exact(api):
+    """Two million elements each, with small, ordinary and large magnitudes: the producers round their FP32
+    evaluation where that is provably the FP64 result and evaluate in FP64 otherwise; every FP16 output bit must be
+    the oracle's (a wrong margin would show up among the thousands of elements that fall near a rounding midpoint)."""
+    M, K = 256, 8192
+    rng = np.random.default_rng(99)
+    scale = np.exp(rng.uniform(-9.0, 3.0, size=(M, 1)))              # per-token magnitude from 1e-4 to 20
+    x = torch.from_numpy((rng.standard_normal((M, K)) * scale).astype(np.float16)).to(DEV)
+    gamma = torch.from_numpy((1.0 + 0.5 * rng.standard_normal(K)).astype(np.float16)).to(DEV)
+    y, _, _, _, _ = api.rmsnorm_quant(x, gamma, 1e-5, want_y=True, want_rowsum=False)
+    ry = qq.rmsnorm_fp16(_np(x), _np(gamma), 1e-5)
+    assert (_np(y).view(np.uint16) == ry.view(np.uint16)).all()
+    gu = torch.from_numpy((rng.standard_normal((M, 2 * K)) * scale * 0.5).astype(np.float16)).to(DEV)
+    y, _, _, _, _ = api.silu_mul_quant(gu, want_y=True, want_rowsum=False)
+    ry = qq.silu_mul_fp16(_np(gu))
+    assert (_np(y).view(np.uint16) == ry.view(np.uint16)).all()
+
+
 def test_fused_producers_reject_long_rows(api):
     x = torch.zeros((1, 40960), dtype=torch.float16, device=DEV)
     g = torch.ones(40960, dtype=torch.float16, device=DEV)
