@@ -299,20 +299,30 @@ __device__ inline uint4 pack8(const double (&f)[8])
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// FP16 bits of a producer's output when an FP32 evaluation `p` of it is known to lie within `margin` FP32 units in
-// the last place of the FP64 value that defines the result: if p is further than that from every FP16 rounding
-// midpoint (the 13 dropped mantissa bits = 0x1000) and the result is a normal FP16 number, rounding p gives the same
-// bits as rounding the FP64 value, and the (much slower) FP64 evaluation is skipped.  Otherwise returns false: the
-// caller evaluates in FP64.  About margin / 4096 of the elements take that path.
-__device__ __forceinline__ bool half_bits_from_approx(float p, uint32_t margin, uint32_t& bits)
+// Keeps the compiler from merging an FP32 product with the conversion that follows it into one mixed-precision
+// multiply-add with a zero addend: that instruction turns a product of -0 into +0.
+__device__ __forceinline__ float opaque(float x)
 {
-    const uint32_t u = __float_as_uint(p), a = u & 0x7FFFFFFFu;
-    if (a < 0x38800800u || a > 0x477D0000u) return false;   // |p| < 2^-14 (1 + 2^-12) or > 64768: subnormal, zero, overflow, NaN
-    const uint32_t low = u & 0x1FFFu;
-    const uint32_t d = low > 0x1000u ? low - 0x1000u : 0x1000u - low;
-    if (d <= margin) return false;
-    bits = (uint32_t)__half_as_ushort(__float2half_rn(p));
-    return true;
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// FP16 bits of two producer outputs from FP32 evaluations p0, p1 of them and factors below < 1 < above such that the
+// FP64 value that defines each result lies between fl32(p below) and fl32(p above).  Rounding to FP16 is monotonic,
+// so where the two bounds round to the same FP16 number, every value between them does, the FP64 one included:
+// subnormal and overflowing results need no case of their own.  word = the two results (element 0 in
+// the low half); the return value is zero if both are decided and has a bit set in the half of an element that is
+// not (a rounding midpoint lies between the two bounds: about 1 in 1000 for bounds 4 * 2^-23 apart from 1), which the caller evaluates
+// more precisely.  Five instructions per element and no branch: a wave alone on its SIMD pays every instruction and
+// every taken branch in full, and a test with comparisons per case cost more than the rest of the kernel.
+__device__ __forceinline__ uint32_t half2_bits_from_approx(float p0, float p1, float below, float above, uint32_t& word)
+{
+    const uint32_t lo = (uint32_t)__half_as_ushort(__float2half_rn(opaque(p0 * below))) |
+                        ((uint32_t)__half_as_ushort(__float2half_rn(opaque(p1 * below))) << 16);
+    const uint32_t hi = (uint32_t)__half_as_ushort(__float2half_rn(opaque(p0 * above))) |
+                        ((uint32_t)__half_as_ushort(__float2half_rn(opaque(p1 * above))) << 16);
+    word = lo;
+    return lo ^ hi;
 }
 
 // Element idx (chunk idx / 8, half idx % 8) of the cached chunks := bits.  Written as compile-time indexed selects: a
@@ -328,6 +338,62 @@ __device__ __forceinline__ void patch_half(uint4 (&v)[CACHE], int idx, uint32_t 
             if (idx == i * 8 + j) w[j >> 1] = (w[j >> 1] & ~(0xFFFFu << (16 * (j & 1)))) | (bits << (16 * (j & 1)));
         v[i] = make_uint4(w[0], w[1], w[2], w[3]);
     }
+}
+
+// The same decision from a value known much more precisely: hi + lo with |lo| of the order of an FP32 unit in the
+// last place of hi and hi + lo within 2^-40 (relative) of the FP64 value.  All values between two neighbouring FP16
+// numbers round down below their midpoint and up above it, so only the side of the midpoint matters:
+// (|hi| - midpoint) is exact, adding lo keeps its sign unless the value sits within 2^-36 of the midpoint itself,
+// and any FP32 number strictly on that side of the midpoint then rounds (in hardware) to the right neighbour,
+// infinity above 65520 included.  Below 2^-13 the FP16 numbers are the multiples k 2^-24, whose bit pattern is k.
+// Returns false for the one element in about 10^8 that stays undecided (and for infinities and NaN): the caller
+// evaluates it in FP64.  Straight-line code: it runs, for all lanes of the wave, wherever one lane needs it.
+__device__ __forceinline__ bool half_bits_from_pair(float hi, float lo, uint32_t& bits)
+{
+    const uint32_t u = __float_as_uint(hi), a = u & 0x7FFFFFFFu, sign = u & 0x80000000u;
+    const float ah = __uint_as_float(a), alo = sign ? -lo : lo;   // magnitude = ah + alo
+    // 2^-13 and above: 13 dropped mantissa bits, midpoint 0x1000
+    const uint32_t mid = (a & ~0x1FFFu) | 0x1000u;
+    const float side_n = (ah - __uint_as_float(mid)) + alo;
+    const uint32_t mag = side_n > 0.f ? mid + 1u : mid - 1u;
+    const uint32_t bits_n = (uint32_t)__half_as_ushort(__float2half_rn(opaque(__uint_as_float(mag | sign))));
+    // below 2^-13
+    const float t = ah * 0x1p24f, fl = floorf(t);
+    const float side_t = ((t - fl) - 0.5f) + alo * 0x1p24f;
+    const uint32_t bits_t = (sign >> 16) | ((uint32_t)fl + (side_t > 0.f ? 1u : 0u));
+    const bool tiny = a < 0x39000000u;
+    bits = tiny ? bits_t : bits_n;
+    const float side = tiny ? side_t : side_n, ref = tiny ? t : ah;
+    return (fabsf(side) > ref * 0x1p-36f) & (a < 0x7F800000u);
+}
+
+// gate / (1 + exp(-gate)) in FP64 for the elements FP32 could not decide.  exp by its definition: -gate = n ln2 + r
+// with |r| <= ln2 / 2 (ln2 split so that n * ln2_hi is exact for |n| < 2^20), the Taylor series of exp(r) to the
+// term r^13 / 13! (the next one is below 2^-55) and a scaling by 2^n that saturates to 0 or infinity.  Within 2^-49
+// of the true value, which rounds to the same FP16 number unless the value lies that close to a midpoint.  One
+// FP64 instruction occupies the SIMD for 8 cycles whatever the number of active lanes, so the length of this
+// routine (about 40 of them, against several hundred in a general-purpose exp and division) is what the rare path costs.
+__device__ __forceinline__ double silu_f64(double g)
+{
+    const double z = fmin(fmax(-g, -1000.0), 1000.0);  // beyond +-745 exp is 0 or infinite anyway; keeps n small for +-inf and NaN
+    const double nf = rint(z * 1.4426950408889634074);
+    const double r = fma(-nf, 1.9082149292705877e-10, fma(-nf, 6.93147180369123816490e-01, z));
+    double e = 1.0 / 6227020800.0;
+    e = fma(e, r, 1.0 / 479001600.0);
+    e = fma(e, r, 1.0 / 39916800.0);
+    e = fma(e, r, 1.0 / 3628800.0);
+    e = fma(e, r, 1.0 / 362880.0);
+    e = fma(e, r, 1.0 / 40320.0);
+    e = fma(e, r, 1.0 / 5040.0);
+    e = fma(e, r, 1.0 / 720.0);
+    e = fma(e, r, 1.0 / 120.0);
+    e = fma(e, r, 1.0 / 24.0);
+    e = fma(e, r, 1.0 / 6.0);
+    e = fma(e, r, 0.5);
+    e = fma(e, r, 1.0);
+    e = fma(e, r, 1.0);
+    e = ldexp(e, (int)nf);                             // 2^n over- and underflows as exp does
+    return g / (1.0 + e);
 }
 
 // y = x * (1 / sqrt(mean(x^2) + eps)) * gamma
@@ -366,7 +432,7 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
 #pragma unroll
     for (int w = 0; w < kWide / 64; ++w) ss += s_d[w];
     const double inv = 1.0 / sqrt(ss / (double)K + eps);
-    const float inv32 = (float)inv;
+    const float inv32 = (float)inv, inv_lo = (float)(inv - (double)inv32);   // inv = inv32 + inv_lo to 2^-48
     uint64_t risky = 0;                                // elements to redo in FP64, bit = chunk * 8 + half
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
@@ -374,19 +440,32 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
         if (c < chunks) {
             const __half* hx = reinterpret_cast<const __half*>(&v[i]);
             const __half* hg = reinterpret_cast<const __half*>(&gv[i]);
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            uint32_t w[4], diff[4];
+            // FP32 first: fl32(r), x * fl32(r) and the product with gamma each round once, so the result is within
+            // 3 * 2^-24 (relative) of the FP64 product; the bounds are taken at 4 * 2^-23, their own rounding included
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                // FP32 first: (x * fl32(r)) * gamma is within 3 units in the last place of the FP64 product
-                const float fx = __half2float(hx[j]), fg = __half2float(hg[j]);
-                uint32_t b = 0;
-                if (!half_bits_from_approx((fx * inv32) * fg, 8u, b)) risky |= 1ull << (i * 8 + j);
-                w[j >> 1] |= b << (16 * (j & 1));
+            for (int j = 0; j < 4; ++j)
+                diff[j] = half2_bits_from_approx(__half2float(hx[2 * j]) * inv32 * __half2float(hg[2 * j]),
+                                                 __half2float(hx[2 * j + 1]) * inv32 * __half2float(hg[2 * j + 1]),
+                                                 1.0f - 4 * 0x1p-23f, 1.0f + 4 * 0x1p-23f, w[j]);
+            if (diff[0] | diff[1] | diff[2] | diff[3]) {   // about one element per wave and chunk
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if ((diff[j >> 1] >> (16 * (j & 1))) & 0xFFFFu) {
+                        // next to a rounding midpoint: the same product with its rounding errors carried along
+                        const float fx = __half2float(hx[j]), fg = __half2float(hg[j]);
+                        const float p1 = fx * inv32, e1 = fmaf(fx, inv32, -p1) + fx * inv_lo;
+                        const float p2 = p1 * fg, e2 = fmaf(p1, fg, -p2) + e1 * fg;
+                        uint32_t b = 0;
+                        if (!half_bits_from_pair(p2, e2, b)) risky |= 1ull << (i * 8 + j);
+                        w[j >> 1] = (w[j >> 1] & ~(0xFFFFu << (16 * (j & 1)))) | (b << (16 * (j & 1)));
+                    }
+                }
             }
             v[i] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
-    // the few elements (about 1 in 500) whose FP32 value is too close to a rounding midpoint: FP64, one at a time
+    // what is left (overflow range, values within 2^-36 of a midpoint): FP64, one at a time
     while (risky) {
         const int idx = __ffsll((unsigned long long)risky) - 1;
         risky &= risky - 1;
@@ -427,26 +506,31 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
             const uint4 gv = grow[c], uv = urow[c];
             const __half* hg = reinterpret_cast<const __half*>(&gv);
             const __half* hu = reinterpret_cast<const __half*>(&uv);
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            uint32_t w[4], diff[4];
+            // FP32 first: expf (1 unit in the last place), the addition, the division and the product (half a unit
+            // each) leave the result within 3 * 2^-23 (relative) of the FP64 value; the bounds are taken at 8 * 2^-23
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                // FP32 first: expf, one addition, a correctly rounded division and a product stay within a few
-                // units in the last place of the FP64 value; 24 are allowed for
-                const float fg = __half2float(hg[j]), fu = __half2float(hu[j]);
-                uint32_t b = 0;
-                if (!half_bits_from_approx(fg / (1.0f + expf(-fg)) * fu, 24u, b)) risky |= 1ull << (i * 8 + j);
-                w[j >> 1] |= b << (16 * (j & 1));
+            for (int j = 0; j < 4; ++j) {
+                const float g0 = __half2float(hg[2 * j]), g1 = __half2float(hg[2 * j + 1]);
+                diff[j] = half2_bits_from_approx(g0 / (1.0f + expf(-g0)) * __half2float(hu[2 * j]),
+                                                 g1 / (1.0f + expf(-g1)) * __half2float(hu[2 * j + 1]),
+                                                 1.0f - 8 * 0x1p-23f, 1.0f + 8 * 0x1p-23f, w[j]);
+            }
+            if (diff[0] | diff[1] | diff[2] | diff[3]) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if ((diff[j >> 1] >> (16 * (j & 1))) & 0xFFFFu) risky |= 1ull << (i * 8 + j);
             }
             v[i] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
-    // the few elements (about 1 in 150) whose FP32 value is too close to a rounding midpoint: FP64, one at a time
+    // the few elements (about 1 in 500) whose FP32 value is too close to a rounding midpoint: FP64, one at a time
     while (risky) {
         const int idx = __ffsll((unsigned long long)risky) - 1;
         risky &= risky - 1;
         const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * kWide) * 8 + (idx & 7);
         const double dg = (double)__half2float(gate_up[m * 2 * K + k]), du = (double)__half2float(gate_up[m * 2 * K + K + k]);
-        patch_half(v, idx, (uint32_t)double_to_half_rne(dg / (1.0 + exp(-dg)) * du));
+        patch_half(v, idx, (uint32_t)double_to_half_rne(silu_f64(dg) * du));
     }
     if (y) {
 #pragma unroll
