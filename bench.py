@@ -419,26 +419,36 @@ def sweep(path, api, wl, dev):
                 for i in range(3):
                     api.w4a8_gemm(qx, sx, blobs[i % copies], N, mode, rowsum=rowsum, out=out, workspace=ws)
                 torch.cuda.synchronize()
-                graph = torch.cuda.CUDAGraph()          # launches replayed from a graph, like the main measurement
-                with torch.cuda.graph(graph):
-                    for i in range(reps):
-                        api.w4a8_gemm(qx, sx, blobs[i % copies], N, mode, rowsum=rowsum, out=out, workspace=ws)
-                graph.replay()
-                torch.cuda.synchronize()
-                us = 1e9
-                for _ in range(3):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
+
+                def timed(n_copies):
+                    graph = torch.cuda.CUDAGraph()      # launches replayed from a graph, like the main measurement
+                    with torch.cuda.graph(graph):
+                        for i in range(reps):
+                            api.w4a8_gemm(qx, sx, blobs[i % n_copies], N, mode, rowsum=rowsum, out=out, workspace=ws)
                     graph.replay()
-                    e1.record()
                     torch.cuda.synchronize()
-                    us = min(us, e0.elapsed_time(e1) * 1e3 / reps)
-                del graph
+                    best = 1e9
+                    for _ in range(3):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        graph.replay()
+                        e1.record()
+                        torch.cuda.synchronize()
+                        best = min(best, e0.elapsed_time(e1) * 1e3 / reps)
+                    del graph
+                    return best
+
+                us = timed(copies)                      # HBM-cold: rotated copies
+                us_hot = timed(1)                       # cache-hot: the same weights every launch
                 ops = 2.0 * M * K * N
                 byts = algorithmic_bytes(M, N, K, mode)
+                # roofline for this shape: the lower of the matrix-core peak and intensity x HBM peak
+                roof = min(INT8_PEAK_TOPS, ops / byts * HBM_PEAK_GBS / 1e3)
                 rows.append({"family": fam, "layer": name, "mode": mode, "M": M, "K": K, "N": N, "us": round(us, 2),
                              "tops": round(ops / us / 1e6, 2), "mfma_frac": round(ops / us / 1e6 / INT8_PEAK_TOPS, 4),
-                             "gbs": round(byts / us / 1e3, 1), "hbm_frac": round(byts / us / 1e3 / HBM_PEAK_GBS, 4)})
+                             "gbs": round(byts / us / 1e3, 1), "hbm_frac": round(byts / us / 1e3 / HBM_PEAK_GBS, 4),
+                             "roof_tops": round(roof, 1), "roof_frac": round(ops / us / 1e6 / roof, 4),
+                             "us_cache_hot": round(us_hot, 2)})
                 del x, qx, sx, out, ws
             del blobs, blob0
             torch.cuda.empty_cache()
@@ -446,6 +456,13 @@ def sweep(path, api, wl, dev):
     with open(path, "w") as f:
         for r in rows:
             f.write(json.dumps(r) + "\n")
+    with open(path + ".txt", "w") as f:               # the same rows as a table
+        f.write("%-10s %-8s %4s %5s %6s %6s %9s %8s %6s %8s %6s %8s %6s %9s\n" % (
+            "family", "layer", "mode", "M", "K", "N", "us", "TOP/s", "mfma", "GB/s", "hbm", "roof", "frac", "us(hot)"))
+        for r in rows:
+            f.write("%-10s %-8s %4d %5d %6d %6d %9.2f %8.1f %6.3f %8.1f %6.3f %8.1f %6.3f %9.2f\n" % (
+                r["family"], r["layer"], r["mode"], r["M"], r["K"], r["N"], r["us"], r["tops"], r["mfma_frac"],
+                r["gbs"], r["hbm_frac"], r["roof_tops"], r["roof_frac"], r["us_cache_hot"]))
 
 
 if __name__ == "__main__":
