@@ -299,8 +299,8 @@ __device__ inline uint4 pack8(const double (&f)[8])
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// Keeps the compiler from merging an FP32 product with the conversion that follows it into one mixed-precision
-// multiply-add with a zero addend: that instruction turns a product of -0 into +0.
+// Keeps the compiler from merging an FP32 product with a conversion next to it (of an FP16 factor, or of the
+// product to FP16) into one mixed-precision multiply-add with a zero addend: that turns a product of -0 into +0.
 __device__ __forceinline__ float opaque(float x)
 {
     asm volatile("" : "+v"(x));
@@ -310,11 +310,12 @@ __device__ __forceinline__ float opaque(float x)
 // FP16 bits of two producer outputs from FP32 evaluations p0, p1 of them and factors below < 1 < above such that the
 // FP64 value that defines each result lies between fl32(p below) and fl32(p above).  Rounding to FP16 is monotonic,
 // so where the two bounds round to the same FP16 number, every value between them does, the FP64 one included:
-// subnormal and overflowing results need no case of their own.  word = the two results (element 0 in
-// the low half); the return value is zero if both are decided and has a bit set in the half of an element that is
-// not (a rounding midpoint lies between the two bounds: about 1 in 1000 for bounds 4 * 2^-23 apart from 1), which the caller evaluates
-// more precisely.  Five instructions per element and no branch: a wave alone on its SIMD pays every instruction and
-// every taken branch in full, and a test with comparisons per case cost more than the rest of the kernel.
+// subnormal and overflowing results need no case of their own.  word = the two results (element 0 in the low
+// half); the return value is zero if both are decided and has a bit set in the half of an element that is not (a
+// rounding midpoint lies between the two bounds: about 1 element in 1000 for factors 1 -+ 4 * 2^-23), which the
+// caller evaluates more precisely.  Five instructions per element and no branch: a wave alone on its SIMD pays
+// every instruction and every taken branch in full, and a test with comparisons per case cost more than the rest
+// of the kernel.
 __device__ __forceinline__ uint32_t half2_bits_from_approx(float p0, float p1, float below, float above, uint32_t& word)
 {
     const uint32_t lo = (uint32_t)__half_as_ushort(__float2half_rn(opaque(p0 * below))) |
@@ -444,11 +445,13 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
             // FP32 first: fl32(r), x * fl32(r) and the product with gamma each round once, so the result is within
             // 3 * 2^-24 (relative) of the FP64 product; the bounds are taken at 4 * 2^-23, their own rounding included
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                diff[j] = half2_bits_from_approx(__half2float(hx[2 * j]) * inv32 * __half2float(hg[2 * j]),
-                                                 __half2float(hx[2 * j + 1]) * inv32 * __half2float(hg[2 * j + 1]),
+            for (int j = 0; j < 4; ++j) {
+                const float x0 = opaque(__half2float(hx[2 * j])), x1 = opaque(__half2float(hx[2 * j + 1]));
+                const float g0 = opaque(__half2float(hg[2 * j])), g1 = opaque(__half2float(hg[2 * j + 1]));
+                diff[j] = half2_bits_from_approx(x0 * inv32 * g0, x1 * inv32 * g1,
                                                  1.0f - 4 * 0x1p-23f, 1.0f + 4 * 0x1p-23f, w[j]);
-            if (diff[0] | diff[1] | diff[2] | diff[3]) {   // about one element per wave and chunk
+            }
+            if (diff[0] | diff[1] | diff[2] | diff[3]) {   // every second wave and chunk has such an element
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     if ((diff[j >> 1] >> (16 * (j & 1))) & 0xFFFFu) {
@@ -512,8 +515,8 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float g0 = __half2float(hg[2 * j]), g1 = __half2float(hg[2 * j + 1]);
-                diff[j] = half2_bits_from_approx(g0 / (1.0f + expf(-g0)) * __half2float(hu[2 * j]),
-                                                 g1 / (1.0f + expf(-g1)) * __half2float(hu[2 * j + 1]),
+                diff[j] = half2_bits_from_approx(g0 / (1.0f + expf(-g0)) * opaque(__half2float(hu[2 * j])),
+                                                 g1 / (1.0f + expf(-g1)) * opaque(__half2float(hu[2 * j + 1])),
                                                  1.0f - 8 * 0x1p-23f, 1.0f + 8 * 0x1p-23f, w[j]);
             }
             if (diff[0] | diff[1] | diff[2] | diff[3]) {
