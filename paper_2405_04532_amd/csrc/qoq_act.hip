@@ -510,13 +510,14 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
             const __half* hg = reinterpret_cast<const __half*>(&gv);
             const __half* hu = reinterpret_cast<const __half*>(&uv);
             uint32_t w[4], diff[4];
-            // FP32 first: expf (1 unit in the last place), the addition, the division and the product (half a unit
-            // each) leave the result within 3 * 2^-23 (relative) of the FP64 value; the bounds are taken at 8 * 2^-23
+            // FP32 first: expf and the hardware reciprocal (1 unit in the last place each), the addition and the two
+            // products (half a unit each) leave the result within 3.5 * 2^-23 (relative) of the FP64 value; the bounds
+            // are taken at 8 * 2^-23, their own rounding included
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float g0 = __half2float(hg[2 * j]), g1 = __half2float(hg[2 * j + 1]);
-                diff[j] = half2_bits_from_approx(g0 / (1.0f + expf(-g0)) * opaque(__half2float(hu[2 * j])),
-                                                 g1 / (1.0f + expf(-g1)) * opaque(__half2float(hu[2 * j + 1])),
+                const float g0 = opaque(__half2float(hg[2 * j])), g1 = opaque(__half2float(hg[2 * j + 1]));
+                const float s0 = g0 * __builtin_amdgcn_rcpf(1.0f + expf(-g0)), s1 = g1 * __builtin_amdgcn_rcpf(1.0f + expf(-g1));
+                diff[j] = half2_bits_from_approx(s0 * opaque(__half2float(hu[2 * j])), s1 * opaque(__half2float(hu[2 * j + 1])),
                                                  1.0f - 8 * 0x1p-23f, 1.0f + 8 * 0x1p-23f, w[j]);
             }
             if (diff[0] | diff[1] | diff[2] | diff[3]) {
