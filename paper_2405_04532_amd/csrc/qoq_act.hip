@@ -11,6 +11,7 @@
 
 #include "qoq_internal.h"
 #include "qoq_fp16.h"
+#include "qoq_half_decide.h"
 
 namespace qoq {
 namespace {
@@ -299,32 +300,20 @@ __device__ inline uint4 pack8(const double (&f)[8])
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// Keeps the compiler from merging an FP32 product with a conversion next to it (of an FP16 factor, or of the
+// The machine operations behind the FP32 decision routines of qoq_half_decide.h.  keep(): an empty asm on the value,
+// which keeps the compiler from merging an FP32 product with a conversion next to it (of an FP16 factor, or of the
 // product to FP16) into one mixed-precision multiply-add with a zero addend: that turns a product of -0 into +0.
-__device__ __forceinline__ float opaque(float x)
-{
-    asm volatile("" : "+v"(x));
-    return x;
-}
-
-// FP16 bits of two producer outputs from FP32 evaluations p0, p1 of them and factors below < 1 < above such that the
-// FP64 value that defines each result lies between fl32(p below) and fl32(p above).  Rounding to FP16 is monotonic,
-// so where the two bounds round to the same FP16 number, every value between them does, the FP64 one included:
-// subnormal and overflowing results need no case of their own.  word = the two results (element 0 in the low
-// half); the return value is zero if both are decided and has a bit set in the half of an element that is not (a
-// rounding midpoint lies between the two bounds: about 1 element in 1000 for factors 1 -+ 4 * 2^-23), which the
-// caller evaluates more precisely.  Five instructions per element and no branch: a wave alone on its SIMD pays
-// every instruction and every taken branch in full, and a test with comparisons per case cost more than the rest
-// of the kernel.
-__device__ __forceinline__ uint32_t half2_bits_from_approx(float p0, float p1, float below, float above, uint32_t& word)
-{
-    const uint32_t lo = (uint32_t)__half_as_ushort(__float2half_rn(opaque(p0 * below))) |
-                        ((uint32_t)__half_as_ushort(__float2half_rn(opaque(p1 * below))) << 16);
-    const uint32_t hi = (uint32_t)__half_as_ushort(__float2half_rn(opaque(p0 * above))) |
-                        ((uint32_t)__half_as_ushort(__float2half_rn(opaque(p1 * above))) << 16);
-    word = lo;
-    return lo ^ hi;
-}
+struct DevF32 {
+    static __device__ __forceinline__ uint32_t bits(float x) { return __float_as_uint(x); }
+    static __device__ __forceinline__ float from_bits(uint32_t u) { return __uint_as_float(u); }
+    static __device__ __forceinline__ uint32_t half_bits(float x) { return (uint32_t)__half_as_ushort(__float2half_rn(x)); }
+    static __device__ __forceinline__ float keep(float x)
+    {
+        asm volatile("" : "+v"(x));
+        return x;
+    }
+};
+__device__ __forceinline__ float opaque(float x) { return DevF32::keep(x); }
 
 // Element idx (chunk idx / 8, half idx % 8) of the cached chunks := bits.  Written as compile-time indexed selects: a
 // register array indexed at run time would be moved to scratch memory.
@@ -339,33 +328,6 @@ __device__ __forceinline__ void patch_half(uint4 (&v)[CACHE], int idx, uint32_t 
             if (idx == i * 8 + j) w[j >> 1] = (w[j >> 1] & ~(0xFFFFu << (16 * (j & 1)))) | (bits << (16 * (j & 1)));
         v[i] = make_uint4(w[0], w[1], w[2], w[3]);
     }
-}
-
-// The same decision from a value known much more precisely: hi + lo with |lo| of the order of an FP32 unit in the
-// last place of hi and hi + lo within 2^-40 (relative) of the FP64 value.  All values between two neighbouring FP16
-// numbers round down below their midpoint and up above it, so only the side of the midpoint matters:
-// (|hi| - midpoint) is exact, adding lo keeps its sign unless the value sits within 2^-36 of the midpoint itself,
-// and any FP32 number strictly on that side of the midpoint then rounds (in hardware) to the right neighbour,
-// infinity above 65520 included.  Below 2^-13 the FP16 numbers are the multiples k 2^-24, whose bit pattern is k.
-// Returns false for the one element in about 10^8 that stays undecided (and for infinities and NaN): the caller
-// evaluates it in FP64.  Straight-line code: it runs, for all lanes of the wave, wherever one lane needs it.
-__device__ __forceinline__ bool half_bits_from_pair(float hi, float lo, uint32_t& bits)
-{
-    const uint32_t u = __float_as_uint(hi), a = u & 0x7FFFFFFFu, sign = u & 0x80000000u;
-    const float ah = __uint_as_float(a), alo = sign ? -lo : lo;   // magnitude = ah + alo
-    // 2^-13 and above: 13 dropped mantissa bits, midpoint 0x1000
-    const uint32_t mid = (a & ~0x1FFFu) | 0x1000u;
-    const float side_n = (ah - __uint_as_float(mid)) + alo;
-    const uint32_t mag = side_n > 0.f ? mid + 1u : mid - 1u;
-    const uint32_t bits_n = (uint32_t)__half_as_ushort(__float2half_rn(opaque(__uint_as_float(mag | sign))));
-    // below 2^-13
-    const float t = ah * 0x1p24f, fl = floorf(t);
-    const float side_t = ((t - fl) - 0.5f) + alo * 0x1p24f;
-    const uint32_t bits_t = (sign >> 16) | ((uint32_t)fl + (side_t > 0.f ? 1u : 0u));
-    const bool tiny = a < 0x39000000u;
-    bits = tiny ? bits_t : bits_n;
-    const float side = tiny ? side_t : side_n, ref = tiny ? t : ah;
-    return (fabsf(side) > ref * 0x1p-36f) & (a < 0x7F800000u);
 }
 
 // gate / (1 + exp(-gate)) in FP64 for the elements FP32 could not decide.  exp by its definition: -gate = n ln2 + r
@@ -448,7 +410,7 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
             for (int j = 0; j < 4; ++j) {
                 const float x0 = opaque(__half2float(hx[2 * j])), x1 = opaque(__half2float(hx[2 * j + 1]));
                 const float g0 = opaque(__half2float(hg[2 * j])), g1 = opaque(__half2float(hg[2 * j + 1]));
-                diff[j] = half2_bits_from_approx(x0 * inv32 * g0, x1 * inv32 * g1,
+                diff[j] = half2_bits_from_bounds<DevF32>(x0 * inv32 * g0, x1 * inv32 * g1,
                                                  1.0f - 4 * 0x1p-23f, 1.0f + 4 * 0x1p-23f, w[j]);
             }
             if (diff[0] | diff[1] | diff[2] | diff[3]) {   // every second wave and chunk has such an element
@@ -456,11 +418,10 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
                 for (int j = 0; j < 8; ++j) {
                     if ((diff[j >> 1] >> (16 * (j & 1))) & 0xFFFFu) {
                         // next to a rounding midpoint: the same product with its rounding errors carried along
-                        const float fx = __half2float(hx[j]), fg = __half2float(hg[j]);
-                        const float p1 = fx * inv32, e1 = fmaf(fx, inv32, -p1) + fx * inv_lo;
-                        const float p2 = p1 * fg, e2 = fmaf(p1, fg, -p2) + e1 * fg;
+                        float hi, lo;
+                        scaled_product_pair<DevF32>(__half2float(hx[j]), inv32, inv_lo, __half2float(hg[j]), hi, lo);
                         uint32_t b = 0;
-                        if (!half_bits_from_pair(p2, e2, b)) risky |= 1ull << (i * 8 + j);
+                        if (!half_bits_from_pair<DevF32>(hi, lo, b)) risky |= 1ull << (i * 8 + j);
                         w[j >> 1] = (w[j >> 1] & ~(0xFFFFu << (16 * (j & 1)))) | (b << (16 * (j & 1)));
                     }
                 }
@@ -517,7 +478,7 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
             for (int j = 0; j < 4; ++j) {
                 const float g0 = opaque(__half2float(hg[2 * j])), g1 = opaque(__half2float(hg[2 * j + 1]));
                 const float s0 = g0 * __builtin_amdgcn_rcpf(1.0f + expf(-g0)), s1 = g1 * __builtin_amdgcn_rcpf(1.0f + expf(-g1));
-                diff[j] = half2_bits_from_approx(s0 * opaque(__half2float(hu[2 * j])), s1 * opaque(__half2float(hu[2 * j + 1])),
+                diff[j] = half2_bits_from_bounds<DevF32>(s0 * opaque(__half2float(hu[2 * j])), s1 * opaque(__half2float(hu[2 * j + 1])),
                                                  1.0f - 8 * 0x1p-23f, 1.0f + 8 * 0x1p-23f, w[j]);
             }
             if (diff[0] | diff[1] | diff[2] | diff[3]) {
