@@ -119,8 +119,10 @@ int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packe
  * second FFN projection; RMSNorm and SiLU(gate) * up for the Llama-family layers the paper evaluates).
  *   qoq_rmsnorm_quant:   y[m, k] = x[m, k] * r[m] * gamma[k],  r[m] = 1 / sqrt(mean_k x[m, :]^2 + eps)
  *   qoq_silu_mul_quant:  y[m, k] = g / (1 + exp(-g)) * u,  g = gate_up[m, k], u = gate_up[m, K + k]  (gate_up is [M, 2K])
- * y is evaluated in FP64 and rounded once to FP16, the tensor an unfused pipeline would pass on; (qx, sx, rowsum, tx)
- * are then exactly qoq_quant_act_per_token(y).  One read of the input, no intermediate tensor.
+ * y is defined as the FP64 evaluation rounded once to FP16, the tensor an unfused pipeline would pass on (the kernels
+ * reach exactly those bits from FP32 arithmetic with proven error bounds and evaluate in FP64 only where FP32 cannot
+ * decide the rounding); (qx, sx, rowsum, tx) are then exactly qoq_quant_act_per_token(y).  One read of the input, no
+ * intermediate tensor.
  *   x_fp16 / gate_up_fp16   FP16, row-major (read only); gamma_fp16 [K] FP16; eps >= 0
  *   y_fp16     [M, K] FP16, optional (NULL: the FP16 activations are not written at all)
  *   qx, sx_fp16, rowsum (nullable), tx (nullable): as for qoq_quant_act_per_token
