@@ -13,6 +13,7 @@ Prints ONE JSON line: effective TOPS (2*M*K*N summed over the layers / step time
 roofline of the GEMM launch, and the CPU oracle timed on the host cores as a baseline.
 `--sweep FILE` additionally writes per-layer, per-M timings of every configuration family.
 `--attention` times the KV4 decode attention kernel instead (its own JSON line, same fields).
+`--producers` times RMSNorm and SiLU*up with the quantizer fused in, at --m tokens (its own JSON line, same fields).
 """
 import argparse
 import json
@@ -52,6 +53,8 @@ def main():
     ap.add_argument("--seq", type=int, default=1024, help="--attention: tokens in every sequence's cache")
     ap.add_argument("--batch", type=int, default=64, help="--attention: sequences decoded per launch")
     ap.add_argument("--family", type=str, default="llama2_7b", help="--attention: head configuration")
+    ap.add_argument("--producers", action="store_true",
+                    help="time the producers with the quantizer fused in (RMSNorm, SiLU*up) at --m tokens instead of the GEMM")
     ap.add_argument("--ablation", action="store_true",
                     help="dequantization-overhead ablation of the GEMM main loop and timings of the offline transforms")
     args = ap.parse_args()
@@ -75,6 +78,9 @@ def main():
         return
     if args.ablation:
         print(json.dumps(ablation_bench(args, api, wl, dev)))
+        return
+    if args.producers:
+        print(json.dumps(producers_bench(args, api, wl, dev)))
         return
     M = args.m
     layers = list(wl.LLAMA2_7B.items())          # name -> (K, N)
@@ -288,6 +294,111 @@ def attention_bench(args, api, wl, dev):
         result["cpu_baseline"] = {"value": round(dt / done * B * H * 1e3, 3), "unit": "ms", "cores": 1, "kind": "oracle",
                                   "sample": "%d of %d (sequence, head) pairs incl. their cache quantization, scaled to all pairs (%.1f s)"
                                             % (done, B * H, dt)}
+    return result
+
+
+def producers_bench(args, api, wl, dev):
+    """The producers with the per-token quantizer fused in (Section 5.1): RMSNorm in front of the QKV / first FFN
+    projection (K = 4096) and SiLU(gate) * up in front of the second FFN projection (K = 11008), Llama-2-7B widths,
+    --m tokens.  One step = one qoq_rmsnorm_quant + one qoq_silu_mul_quant call (FP16 activations not written: the
+    fused path's point), over six rotated inputs so that every call reads its input from HBM.  The stand-alone
+    quantizer is timed on the same shapes for comparison."""
+    import numpy as np
+    import torch
+
+    M = args.m
+    K1, K2 = 4096, 11008
+    n_in = 6
+    xs = [wl.make_activations(M, K1, 100 + i, dev) for i in range(n_in)]
+    gus = [wl.make_activations(M, 2 * K2, 200 + i, dev) for i in range(n_in)]
+    ys = [wl.make_activations(M, K2, 300 + i, dev) for i in range(n_in)]
+    gamma = (1.0 + 0.1 * torch.randn(K1, generator=torch.Generator().manual_seed(5))).to(torch.float16).to(dev)
+    q1 = torch.empty((M, K1), dtype=torch.int8, device=dev)
+    q2 = torch.empty((M, K2), dtype=torch.int8, device=dev)
+    sx = torch.empty(M, dtype=torch.float16, device=dev)
+    L = api.lib()
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(api.status_string(rc))
+
+    def rms(i, s):
+        check(L.qoq_rmsnorm_quant(xs[i % n_in].data_ptr(), gamma.data_ptr(), 1e-5, M, K1, None, q1.data_ptr(), sx.data_ptr(),
+                                  None, None, s))
+
+    def silu(i, s):
+        check(L.qoq_silu_mul_quant(gus[i % n_in].data_ptr(), M, K2, None, q2.data_ptr(), sx.data_ptr(), None, None, s))
+
+    def plain1(i, s):
+        check(L.qoq_quant_act_per_token(xs[i % n_in].data_ptr(), M, K1, q1.data_ptr(), sx.data_ptr(), None, None, s))
+
+    def plain2(i, s):
+        check(L.qoq_quant_act_per_token(ys[i % n_in].data_ptr(), M, K2, q2.data_ptr(), sx.data_ptr(), None, None, s))
+
+    def timed(fns, steps):
+        for i in range(args.warmup):
+            for fn in fns:
+                fn(i, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        per_graph = 2 * n_in
+        steps = max(1, steps // per_graph) * per_graph
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            cs = torch.cuda.current_stream().cuda_stream
+            for i in range(per_graph):
+                for fn in fns:
+                    fn(i, cs)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps // per_graph):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps, steps
+
+    ms, steps = timed([rms, silu], args.steps)
+    us_rms = timed([rms], args.steps)[0] * 1e3
+    us_silu = timed([silu], args.steps)[0] * 1e3
+    us_p1 = timed([plain1], args.steps)[0] * 1e3
+    us_p2 = timed([plain2], args.steps)[0] * 1e3
+    # algorithmic bytes: FP16 in (gate and up for SiLU), INT8 codes out, gamma once, one scale per token
+    b_rms = M * K1 * 3 + 2 * K1 + 2 * M
+    b_silu = M * K2 * 5 + 2 * M
+    byts = b_rms + b_silu
+    gbs = byts / (ms * 1e-3) / 1e9
+    elems = M * (K1 + K2)
+    result = {
+        "metric": "fused producer throughput (RMSNorm+quant K=4096, SiLU*up+quant K=11008, M=%d)" % M,
+        "value": round(elems / (ms * 1e-3) / 1e9, 3), "unit": "G elements/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "llama2_7b_fused_producers_m%d" % M, "M": M, "K_rmsnorm": K1, "K_silu_mul": K2,
+                   "inputs_rotated": n_in, "y_written": False,
+                   "step": "1 x qoq_rmsnorm_quant + 1 x qoq_silu_mul_quant, launches replayed from a HIP graph"},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "rmsnorm_quant_kernel + silu_mul_quant_kernel", "avg_launch_us": round(ms * 1e3 / 2, 3),
+                     "algorithmic_bytes_per_launch": byts // 2,
+                     "rmsnorm_us": round(us_rms, 2), "rmsnorm_gbs": round(b_rms / us_rms / 1e3, 1),
+                     "silu_mul_us": round(us_silu, 2), "silu_mul_gbs": round(b_silu / us_silu / 1e3, 1),
+                     "plain_quant_us": {"K4096": round(us_p1, 2), "K11008": round(us_p2, 2)}},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import qoq_quant as qq
+        rows = min(M, 64)
+        xn = xs[0][:rows].cpu().numpy()
+        gn = gus[0][:rows].cpu().numpy()
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            qq.act_quant(qq.rmsnorm_fp16(xn, gamma.cpu().numpy(), 1e-5))
+            qq.act_quant(qq.silu_mul_fp16(gn))
+            reps += 1
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(reps * rows * (K1 + K2) / dt / 1e9, 4), "unit": "G elements/s", "cores": 1,
+                                  "kind": "oracle", "sample": "%d tokens of both producers, %d passes (%.1f s)" % (rows, reps, dt)}
     return result
 
 
