@@ -158,12 +158,15 @@ __global__ __launch_bounds__(kThreads) void act_quant_kernel(const __half* __res
     }
 }
 
-// Single-read variant: 512 threads, up to kCache 16-byte chunks (8 halves each) per thread in registers.
+// Single-read variant: up to 512 threads, up to kCache 16-byte chunks (8 halves each) per thread in registers.
+// The kernels index by blockDim.x: with many rows to do and short rows the launcher takes 256 threads per row, so
+// that twice as many rows (and bytes) are in flight per compute unit -- at large M the latency of the row load,
+// not issue or bandwidth, sets the pace (vector pipe active 0.2 of the time with four rows per compute unit).
 constexpr int kWide = 512;
 constexpr int kCache = 8;
 constexpr int64_t kMaxCachedK = (int64_t)kWide * kCache * 8;
 
-// Quantize a token row that the workgroup holds in registers (chunk c = threadIdx.x + i * kWide in v[i],
+// Quantize a token row that the workgroup holds in registers (chunk c = threadIdx.x + i * blockDim.x in v[i],
 // zeros past the end): absmax, scale, INT8 codes, sums.  Used by the plain quantizer and by the producers the
 // quantization is fused into.
 template <int CACHE>
@@ -184,9 +187,11 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
     amax = wave_max_nonneg(amax);
     if ((threadIdx.x & 63) == 0) s_f[threadIdx.x >> 6] = amax;
     __syncthreads();
+    const int waves = (int)blockDim.x >> 6;
     amax = s_f[0];
 #pragma unroll
-    for (int w = 1; w < kWide / 64; ++w) amax = fmaxf(amax, s_f[w]);
+    for (int w = 1; w < kWide / 64; ++w)
+        if (w < waves) amax = fmaxf(amax, s_f[w]);
     __syncthreads();
 
     __half sxh = __float2half_rn(amax / 127.0f);   // see act_quant_kernel for why FP32 suffices here
@@ -199,7 +204,7 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
     uint2* qrow = reinterpret_cast<uint2*>(qx + m * K);
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
+        const int c = (int)threadIdx.x + i * (int)blockDim.x;
         if (c < chunks) {
             const __half2* h = reinterpret_cast<const __half2*>(&v[i]);
             uint32_t packed[2] = {0u, 0u};
@@ -224,7 +229,7 @@ __device__ inline void quantize_cached_row(const uint4 (&v)[CACHE], int chunks, 
     __syncthreads();
     if (threadIdx.x == 0) {
         int it = 0; float ft = 0.f;
-        for (int w = 0; w < kWide / 64; ++w) { it += s_i[w]; ft += s_f[w]; }
+        for (int w = 0; w < waves; ++w) { it += s_i[w]; ft += s_f[w]; }
         sx[m] = sxh;
         if (rowsum) rowsum[m] = it;
         if (tx) tx[m] = ft;
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(kWide) void act_quant_cached_kernel(const __half* _
     uint4 v[CACHE];
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
+        const int c = (int)threadIdx.x + i * (int)blockDim.x;
         v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
     }
     quantize_cached_row(v, chunks, m, K, qx, sx, rowsum, tx, s_f, s_i);
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(kWide) void act_quant_reordered_kernel(const __half
     uint4 v[kCache];
 #pragma unroll
     for (int i = 0; i < kCache; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
+        const int c = (int)threadIdx.x + i * (int)blockDim.x;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (c < chunks) {
             const int4 p0 = reinterpret_cast<const int4*>(perm)[2 * c], p1 = reinterpret_cast<const int4*>(perm)[2 * c + 1];
@@ -377,7 +382,7 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
     double ss = 0.0;
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
+        const int c = (int)threadIdx.x + i * (int)blockDim.x;
         v[i] = c < chunks ? row[c] : make_uint4(0u, 0u, 0u, 0u);
         gv[i] = c < chunks ? grow[c] : make_uint4(0u, 0u, 0u, 0u);
     }
@@ -393,13 +398,14 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
     __syncthreads();
     ss = 0.0;
 #pragma unroll
-    for (int w = 0; w < kWide / 64; ++w) ss += s_d[w];
+    for (int w = 0; w < kWide / 64; ++w)
+        if (w < ((int)blockDim.x >> 6)) ss += s_d[w];
     const double inv = 1.0 / sqrt(ss / (double)K + eps);
     const float inv32 = (float)inv, inv_lo = (float)(inv - (double)inv32);   // inv = inv32 + inv_lo to 2^-48
     uint64_t risky = 0;                                // elements to redo in FP64, bit = chunk * 8 + half
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
+        const int c = (int)threadIdx.x + i * (int)blockDim.x;
         if (c < chunks) {
             const __half* hx = reinterpret_cast<const __half*>(&v[i]);
             const __half* hg = reinterpret_cast<const __half*>(&gv[i]);
@@ -433,14 +439,14 @@ __global__ __launch_bounds__(kWide) void rmsnorm_quant_kernel(const __half* __re
     while (risky) {
         const int idx = __ffsll((unsigned long long)risky) - 1;
         risky &= risky - 1;
-        const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * kWide) * 8 + (idx & 7);
+        const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * (int64_t)blockDim.x) * 8 + (idx & 7);
         const double fx = (double)__half2float(x[m * K + k]), fg = (double)__half2float(gamma[k]);
         patch_half(v, idx, (uint32_t)double_to_half_rne(fx * inv * fg));
     }
     if (y) {
 #pragma unroll
         for (int i = 0; i < CACHE; ++i) {
-            const int c = (int)threadIdx.x + i * kWide;
+            const int c = (int)threadIdx.x + i * (int)blockDim.x;
             if (c < chunks) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
         }
     }
@@ -464,7 +470,7 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
     uint64_t risky = 0;                                // elements to redo in FP64, bit = chunk * 8 + half
 #pragma unroll
     for (int i = 0; i < CACHE; ++i) {
-        const int c = (int)threadIdx.x + i * kWide;
+        const int c = (int)threadIdx.x + i * (int)blockDim.x;
         v[i] = make_uint4(0u, 0u, 0u, 0u);
         if (c < chunks) {
             const uint4 gv = grow[c], uv = urow[c];
@@ -493,14 +499,14 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
     while (risky) {
         const int idx = __ffsll((unsigned long long)risky) - 1;
         risky &= risky - 1;
-        const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * kWide) * 8 + (idx & 7);
+        const int64_t k = ((int64_t)threadIdx.x + (int64_t)(idx >> 3) * (int64_t)blockDim.x) * 8 + (idx & 7);
         const double dg = (double)__half2float(gate_up[m * 2 * K + k]), du = (double)__half2float(gate_up[m * 2 * K + K + k]);
         patch_half(v, idx, (uint32_t)double_to_half_rne(silu_f64(dg) * du));
     }
     if (y) {
 #pragma unroll
         for (int i = 0; i < CACHE; ++i) {
-            const int c = (int)threadIdx.x + i * kWide;
+            const int c = (int)threadIdx.x + i * (int)blockDim.x;
             if (c < chunks) reinterpret_cast<uint4*>(y + m * K)[c] = v[i];
         }
     }
@@ -509,16 +515,24 @@ __global__ __launch_bounds__(kWide) void silu_mul_quant_kernel(const __half* __r
 
 }  // namespace
 
+// Threads per token row: 512, or 256 where there are rows enough to fill the chip several times over and a row is
+// at most two chunks per thread then (with few rows the time of one row counts, and more threads shorten it).
+static int64_t row_threads(int64_t M, int64_t K)
+{
+    return (M >= 2048 && K <= (int64_t)256 * 2 * 8) ? 256 : kWide;
+}
+
 hipError_t launch_act_quant(const void* x_fp16, int64_t M, int64_t K, int8_t* qx, void* sx, int32_t* rowsum,
                             float* tx, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
     if (K <= kMaxCachedK) {
         // as many cached 16-byte chunks per thread as the row needs: short rows spend nothing on empty ones
-        auto* kern = K <= (int64_t)kWide * 8 ? act_quant_cached_kernel<1>
-                   : K <= (int64_t)kWide * 2 * 8 ? act_quant_cached_kernel<2>
-                   : K <= (int64_t)kWide * 4 * 8 ? act_quant_cached_kernel<4> : act_quant_cached_kernel<kCache>;
-        kern<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx, static_cast<__half*>(sx), rowsum, tx);
+        const int64_t wide = row_threads(M, K);
+        auto* kern = K <= wide * 8 ? act_quant_cached_kernel<1>
+                   : K <= wide * 2 * 8 ? act_quant_cached_kernel<2>
+                   : K <= wide * 4 * 8 ? act_quant_cached_kernel<4> : act_quant_cached_kernel<kCache>;
+        kern<<<dim3((unsigned)M), (unsigned)wide, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx, static_cast<__half*>(sx), rowsum, tx);
         return hipGetLastError();
     }
     act_quant_kernel<<<dim3((unsigned)M), kThreads, 0, s>>>(static_cast<const __half*>(x_fp16), K, qx,
@@ -543,9 +557,10 @@ hipError_t launch_rmsnorm_quant(const void* x_fp16, const void* gamma_fp16, doub
 {
     if (M == 0) return hipSuccess;
     // shorter rows need fewer cached chunks per thread: far fewer registers, more waves per CU
-    auto* kern = K <= (int64_t)kWide * 2 * 8 ? rmsnorm_quant_kernel<2>
-               : K <= (int64_t)kWide * 4 * 8 ? rmsnorm_quant_kernel<4> : rmsnorm_quant_kernel<kCache>;
-    kern<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(x_fp16), static_cast<const __half*>(gamma_fp16), eps, K,
+    const int64_t wide = row_threads(M, K);
+    auto* kern = K <= wide * 2 * 8 ? rmsnorm_quant_kernel<2>
+               : K <= wide * 4 * 8 ? rmsnorm_quant_kernel<4> : rmsnorm_quant_kernel<kCache>;
+    kern<<<dim3((unsigned)M), (unsigned)wide, 0, s>>>(static_cast<const __half*>(x_fp16), static_cast<const __half*>(gamma_fp16), eps, K,
                                             static_cast<__half*>(y_fp16), qx, static_cast<__half*>(sx), rowsum, tx);
     return hipGetLastError();
 }
@@ -554,9 +569,10 @@ hipError_t launch_silu_mul_quant(const void* gate_up_fp16, int64_t M, int64_t K,
                                  int32_t* rowsum, float* tx, hipStream_t s)
 {
     if (M == 0) return hipSuccess;
-    auto* kern = K <= (int64_t)kWide * 2 * 8 ? silu_mul_quant_kernel<2>
-               : K <= (int64_t)kWide * 4 * 8 ? silu_mul_quant_kernel<4> : silu_mul_quant_kernel<kCache>;
-    kern<<<dim3((unsigned)M), kWide, 0, s>>>(static_cast<const __half*>(gate_up_fp16), K, static_cast<__half*>(y_fp16), qx,
+    const int64_t wide = row_threads(M, K);
+    auto* kern = K <= wide * 2 * 8 ? silu_mul_quant_kernel<2>
+               : K <= wide * 4 * 8 ? silu_mul_quant_kernel<4> : silu_mul_quant_kernel<kCache>;
+    kern<<<dim3((unsigned)M), (unsigned)wide, 0, s>>>(static_cast<const __half*>(gate_up_fp16), K, static_cast<__half*>(y_fp16), qx,
                                             static_cast<__half*>(sx), rowsum, tx);
     return hipGetLastError();
 }

@@ -86,7 +86,8 @@ def test_pack_quantized_roundtrip(api):
 
 
 # ---------------------------------------------------------------------------- activations
-@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768), (3, 40960)])
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768), (3, 40960),
+                                 (2048, 4096), (2100, 1024), (2048, 4224)])   # last three: many rows (256 threads per row where a row is short)
 def test_act_quant_matches_oracle(api, M, K):
     _, x = rand_inputs(M, 64, K, seed=M * 7 + K)
     qx, sx, rowsum, tx = api.quant_act_per_token(x, want_rowsum=True, want_tx=True)
@@ -449,7 +450,8 @@ def _producer_inputs(M, K, seed):
     return x, gamma
 
 
-@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768)])
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768),
+                                 (2048, 4096), (2100, 1024), (2048, 4224)])   # last three: many rows (256 threads per row where a row is short)
 def test_rmsnorm_quant_matches_oracle(api, M, K):
     x, gamma = _producer_inputs(M, K, seed=11 * M + K)
     if M >= 4:
@@ -470,7 +472,7 @@ def test_rmsnorm_quant_matches_oracle(api, M, K):
     assert torch.equal(sx.view(torch.int16), sx2.view(torch.int16)) and torch.equal(sx.view(torch.int16), sx3.view(torch.int16))
 
 
-@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 11008), (4, 14336), (2, 28672)])
+@pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 11008), (4, 14336), (2, 28672), (2048, 4096), (2100, 896)])
 def test_silu_mul_quant_matches_oracle(api, M, K):
     gu = wl.make_activations(M, 2 * K, 5 * M + K, DEV, outlier_count=max(1, K // 50), gain=6.0)
     y, qx, sx, rowsum, tx = api.silu_mul_quant(gu, want_y=True, want_rowsum=True, want_tx=True)
