@@ -27,9 +27,38 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5033.0     # MI355X dense INT8 matrix, published (5.0 POP/s)
 CALIB_BYTES = 256 << 20     # size of the calibration copy
-# HBM bytes per GEMM launch of the default workload, from the two counter runs summarised in
-# profiles/w4a8_gemm_llama2_7b_decode_m64.txt (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy); None for any other workload.
-TRAFFIC_BYTES_PER_LAUNCH_DEFAULT = 31.45e6
+# HBM traffic per GEMM launch is a counter figure (two `rocprofv3 --pmc` runs: FETCH_SIZE, WRITE_SIZE, scaled by the
+# calibration copy); a benchmark run cannot count it itself.  The committed counter summary of a workload carries one
+# machine-readable line
+#     traffic_bytes_per_launch: <bytes> config: <layer>=<tile_m>/<split_k>,...
+# and the figure is reported only while the launch configurations the library picks today are the ones that line
+# was measured with (otherwise null: the figure would be stale).
+TRAFFIC_PROFILES = {"llama2_7b_decode_m64": "profiles/w4a8_gemm_llama2_7b_decode_m64.txt"}
+
+
+def profile_traffic(workload, config_now):
+    """(bytes per launch, source file) from the committed counter summary, or (None, None)."""
+    rel = TRAFFIC_PROFILES.get(workload)
+    if rel is None:
+        return None, None
+    try:
+        with open(os.path.join(ROOT, rel)) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    head, _, cfg = line.partition("config:")
+                    if cfg.strip() == config_now:
+                        return float(head.split(":", 1)[1]), rel
+    except (OSError, ValueError):
+        pass
+    return None, None
+
+
+def graph_schedule(steps, per_graph):
+    """How `steps` timed steps are replayed from captured graphs: (replays of the full graph of `per_graph`
+    consecutive steps, steps in one shorter graph replayed once after them).  Any steps >= 1 is timed exactly."""
+    if steps < 1 or per_graph < 1:
+        raise ValueError("steps and per_graph must be at least 1")
+    return steps // per_graph, steps % per_graph
 
 
 def algorithmic_bytes(M, N, K, mode=0):
@@ -47,6 +76,8 @@ def main():
     ap.add_argument("--m", type=int, default=64, help="tokens per step (default workload: 64)")
     ap.add_argument("--copies", type=int, default=8, help="independently packed layer sets rotated per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-compute-leg", action="store_true",
+                    help="skip the compute-bound leg (Llama-3-70B layers at M = 2048) that the default run appends")
     ap.add_argument("--sweep", type=str, default=None, help="also write a per-layer/per-M table to this file")
     ap.add_argument("--attention", action="store_true",
                     help="time the KV4 decode attention kernel instead (64 sequences x --seq tokens, Llama-2-7B heads)")
@@ -136,26 +167,35 @@ def main():
             check(L.qoq_w4a8_linear(P(xs[name]), P(blobs[name][step % args.copies]), M, N, K, 0, P(b["out"]),
                                     P(b["qx"]), P(b["sx"]), None, P(b["ws"]), b["ws"].numel(), s))
 
-    def timed(fn, steps, warmup):
-        """Warm up eagerly, then time `steps` steps.  The launches of `copies` consecutive steps are
-        captured once into a HIP graph (launch-bound inner loops belong in graphs) and the graph is
-        replayed steps / copies times between two events on the capture stream's parent."""
+    def timed(fn, steps, warmup, per_graph=None):
+        """Warm up eagerly, then time exactly `steps` steps.  The launches of `copies` consecutive steps are
+        captured once into a HIP graph (launch-bound inner loops belong in graphs) and replayed steps // copies
+        times; the remaining steps % copies steps come from a second, shorter graph.  Both events are recorded on
+        the stream the graphs are launched on."""
         for i in range(warmup):
             fn(i)
         torch.cuda.synchronize()
-        per_graph = args.copies
-        assert steps % per_graph == 0, "--steps must be a multiple of --copies"
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            cs = torch.cuda.current_stream().cuda_stream
-            for i in range(per_graph):
-                fn(i, cs)
-        graph.replay()
+        per_graph = args.copies if per_graph is None else per_graph
+        full, rem = graph_schedule(steps, per_graph)
+
+        def capture(n):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                cs = torch.cuda.current_stream().cuda_stream
+                for i in range(n):
+                    fn(i, cs)
+            g.replay()                              # untimed first replay (uploads the graph)
+            return g
+
+        g_full = capture(per_graph) if full else None
+        g_rem = capture(rem) if rem else None
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(steps // per_graph):
-            graph.replay()
+        for _ in range(full):
+            g_full.replay()
+        if rem:
+            g_rem.replay()
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps      # ms per step
@@ -169,12 +209,17 @@ def main():
     gemm_gbs = byts / (ms_gemm * 1e-3) / 1e9
     gemm_tops = ops / (ms_gemm * 1e-3) / 1e12
 
+    workload = ("llama2_7b_decode_m%d" if M <= 128 else "llama2_7b_prefill_m%d") % M
+    picked = {name: api.query_gemm_config(M, N, K, 0) for name, (K, N) in layers}
+    config_now = ",".join("%s=%d/%d" % (name, picked[name][0], picked[name][1]) for name, _ in layers)
+    traffic, traffic_src = profile_traffic(workload, config_now)
+
     # The GEMM launch is bound by HBM at decode sizes and by the INT8 matrix cores once there are a few hundred
     # tokens (ridge of the published peaks: 629 ops per byte, i.e. about 160 tokens for 4-bit weights).
     if M <= 128:
         roofline = {"bound": "hbm", "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
-                    "traffic": TRAFFIC_BYTES_PER_LAUNCH_DEFAULT if (M == 64 and args.copies == 8) else None}
+                    "traffic": traffic, "traffic_source": traffic_src}
     else:
         roofline = {"bound": "mfma", "achieved": round(gemm_tops, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                     "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": None}
@@ -191,8 +236,9 @@ def main():
         "value": round(tops, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": ("llama2_7b_decode_m%d" if M <= 128 else "llama2_7b_prefill_m%d") % M, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
+        "config": {"workload": workload, "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers},
                    "M": M, "group": 128, "mode": "group128", "weight_copies_rotated": args.copies,
+                   "gemm_config": config_now,
                    "step": "4 x qoq_w4a8_linear (per-token activation quantization + W4A8 GEMM), launches replayed from a HIP graph"},
         "roofline": roofline,
     }
@@ -200,10 +246,97 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(M, xs, wl)
 
+    if M == 64 and not args.no_compute_leg:
+        # second half of the target: the compute-bound side, on the largest configuration (its own fields; `value`,
+        # `ms_per_step` and `roofline` above stay those of the decode workload)
+        del blobs, bufs, xs
+        torch.cuda.empty_cache()
+        leg = compute_leg(args, api, wl, dev)
+        result["compute_leg"] = leg
+        result["config"]["workload"] = workload + " (value, roofline) + " + leg["workload"] + " (compute_leg)"
+
     if args.sweep:
         sweep(args.sweep, api, wl, dev)
 
     print(json.dumps(result))
+
+
+def compute_leg(args, api, wl, dev, family="llama3_70b", M=2048):
+    """The compute-bound half of the target on the largest single-GPU configuration: the four Llama-3-70B-shaped
+    layers at M = 2048 tokens (g128), one step = 4 x (activation quantization + W4A8 GEMM) like the decode
+    workload.  The 429 MB of packed weights of the four layers exceed the 256 MB Infinity Cache, so every layer's
+    weights come from HBM without rotating copies.  Reports the step and the GEMM launches alone against the
+    published INT8 matrix-core peak."""
+    import torch
+
+    shapes = {"llama3_70b": wl.LLAMA3_70B, "llama2_7b": wl.LLAMA2_7B}[family]
+    layers = list(shapes.items())
+    L = api.lib()
+    P = lambda t: t.data_ptr()
+    st = {}
+    for name, (K, N) in layers:
+        w = wl.layer_weights(family, name, 3, dev)
+        blob = api.pack_weights(w)
+        del w
+        st[name] = dict(blob=blob, x=wl.layer_activations(family, name, M, 3, dev),
+                        qx=torch.empty((M, K), dtype=torch.int8, device=dev),
+                        sx=torch.empty(M, dtype=torch.float16, device=dev),
+                        out=torch.empty((M, N), dtype=torch.float16, device=dev),
+                        ws=api.new_workspace(api.gemm_workspace_bytes(M, N, K), dev))
+    torch.cuda.empty_cache()
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(api.status_string(rc))
+
+    def full_step(s):
+        for name, (K, N) in layers:
+            b = st[name]
+            check(L.qoq_w4a8_linear(P(b["x"]), P(b["blob"]), M, N, K, 0, P(b["out"]), P(b["qx"]), P(b["sx"]), None,
+                                    P(b["ws"]), b["ws"].numel(), s))
+
+    def gemm_only(s):
+        for name, (K, N) in layers:
+            b = st[name]
+            check(L.qoq_w4a8_gemm(P(b["qx"]), P(b["sx"]), None, P(b["blob"]), M, N, K, 0, P(b["out"]), P(b["ws"]),
+                                  b["ws"].numel(), s))
+
+    steps = max(1, min(args.steps, 20))
+    warm = max(1, min(args.warmup, 3))
+
+    def timed(fn):
+        for _ in range(warm):
+            fn(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn(torch.cuda.current_stream().cuda_stream)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms_step = timed(full_step)
+    ms_gemm = timed(gemm_only)
+    ops = sum(2.0 * M * K * N for _, (K, N) in layers)
+    byts = sum(algorithmic_bytes(M, N, K) for _, (K, N) in layers)
+    gemm_tops = ops / (ms_gemm * 1e-3) / 1e12
+    cfg = ",".join("%s=%d/%d" % ((name,) + tuple(api.query_gemm_config(M, N, K, 0))) for name, (K, N) in layers)
+    return {"workload": "%s_prefill_m%d" % (family, M), "metric": "W4A8 GEMM effective TOPS", "unit": "TOPS",
+            "value": round(ops / (ms_step * 1e-3) / 1e12, 3), "ms_per_step": round(ms_step, 5), "steps": steps, "warmup": warm,
+            "layers": {n: {"K": k, "N": nn} for n, (k, nn) in layers}, "M": M, "gemm_config": cfg,
+            "step": "4 x qoq_w4a8_linear (per-token activation quantization + W4A8 GEMM), launches replayed from a HIP graph",
+            "roofline": {"bound": "mfma", "achieved": round(gemm_tops, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                         "frac": round(gemm_tops / INT8_PEAK_TOPS, 4), "traffic": None,
+                         "kernel": "qoq_w4a8_gemm launch (average over the four layers)",
+                         "avg_launch_us": round(ms_gemm * 1e3 / len(layers), 3),
+                         "algorithmic_ops_per_launch": round(ops / len(layers)),
+                         "algorithmic_bytes_per_launch": round(byts / len(layers))}}
 
 
 def attention_bench(args, api, wl, dev):
@@ -519,14 +652,14 @@ def sweep(path, api, wl, dev):
             w = wl.layer_weights(fam, name, 2, dev)
             blob0 = api.pack_weights(w, mode)
             del w
-            copies = max(1, min(8, int(600e6 // blob0.numel())))
+            copies = max(2, -(-640_000_000 // blob0.numel()))   # rotate at least 640 MB: past L2 and Infinity Cache
             blobs = [blob0] + [blob0.clone() for _ in range(copies - 1)]
             for M in ms:
                 x = wl.layer_activations(fam, name, M, 2, dev)
                 qx, sx, rowsum, _ = api.quant_act_per_token(x)
                 out = torch.empty((M, N), dtype=torch.float16, device=dev)
                 ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, mode), dev)
-                reps = 16 if M >= 1024 else 48
+                reps = max(copies, 16 if M >= 1024 else 48)
                 for i in range(3):
                     api.w4a8_gemm(qx, sx, blobs[i % copies], N, mode, rowsum=rowsum, out=out, workspace=ws)
                 torch.cuda.synchronize()

@@ -12,8 +12,11 @@
  *     enqueued on it; no call synchronizes, except where stated.
  *   - Weights are [N, K] row-major, N = output channels, K = input channels (the paper's
  *     n x k code tensors).  Activations are [M, K] row-major, one row per token.
- *   - Shapes: K % 128 == 0 (group size g = 128 along k), N % 64 == 0, M >= 0.
- *     Device pointers must be 16-byte aligned.
+ *   - Shapes: K % 128 == 0 (group size g = 128 along k), N % 64 == 0, M >= 0.  (64, not 16: the blob interleaves
+ *     the rows of four 16-row matrix-core fragments so that one lane ends up with 4 consecutive output channels
+ *     of each, i.e. whole 8-byte FP16 row segments in the epilogue; a 64-channel block is the unit of that
+ *     permutation and of the work partition.  Pad N to a multiple of 64 with zero rows.)
+ *     Tensor pointers must be 16-byte aligned; the per-token vectors (sx, rowsum, tx) 4-byte aligned.
  *   - Return value: QOQ_OK or an error code; on error nothing was enqueued and no output
  *     was touched.  Errors are never reported any other way (no abort, no exception).
  *   - The library allocates no device memory.  Scratch comes from the caller's `workspace`.
@@ -33,9 +36,11 @@ typedef enum {
     QOQ_ERR_NULL = 1,       /* a required pointer is NULL */
     QOQ_ERR_SHAPE = 2,      /* M, N, K or mode outside the supported set */
     QOQ_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned */
-    QOQ_ERR_WORKSPACE = 4,  /* workspace missing or smaller than qoq_gemm_workspace_bytes */
-    QOQ_ERR_ARCH = 5,       /* current device is not gfx950 */
-    QOQ_ERR_HIP = 6         /* a HIP runtime call failed (launch error) */
+    QOQ_ERR_BLOB = 4,       /* the packed-weight blob's header does not describe an [N, K] layer of this mode
+                               (only calls that read the header report it: qoq_unpack_weights) */
+    QOQ_ERR_WORKSPACE = 5,  /* workspace missing or smaller than qoq_gemm_workspace_bytes */
+    QOQ_ERR_ARCH = 6,       /* current device is not gfx950 */
+    QOQ_ERR_HIP = 7         /* a HIP runtime call failed (launch error) */
 } qoq_status;
 
 typedef enum {
@@ -82,7 +87,11 @@ int qoq_pack_quantized(const uint8_t* q_u4, const uint8_t* s1_u8, const uint8_t*
                        void* packed_dev, void* stream);
 
 /* Inverse of the packing, for tests and debugging: logical tensors out of a blob, same
- * shapes as qoq_pack_quantized (s1_u8 may be NULL in per-channel mode). */
+ * shapes as qoq_pack_quantized (s1_u8 may be NULL in per-channel mode).
+ * This is the one call that reads device memory from the host: it copies the blob's 256-byte header back
+ * (synchronizing `stream`) and returns QOQ_ERR_BLOB, enqueuing nothing, unless the header carries the library's
+ * magic and version and describes exactly this (N, K, mode) with the section offsets the library would lay out.
+ * The GEMM calls trust their (N, K, mode) arguments and never read the header. */
 int qoq_unpack_weights(const void* packed_dev, int64_t N, int64_t K, int mode,
                        uint8_t* q_u4, uint8_t* s1_u8, uint8_t* z_u8, void* s_fp16, void* stream);
 
@@ -168,6 +177,7 @@ int qoq_w4a8_linear(const void* x_fp16, const void* packed, int64_t M, int64_t N
  * quantizer.  X W^T is unchanged.
  *   qoq_channel_absmax     x_fp16 [M, K] device -> absmax [K] FP32 device (overwritten).  K % 8 == 0.
  *   qoq_channel_order_host salience [K] FP32 HOST -> perm [K] INT32 HOST: new channel j = old channel perm[j].
+ *                          Every salience must be finite (a NaN has no place in an order): else QOQ_ERR_SHAPE.
  *   qoq_gather_channels    dst[r, j] = src[r, perm[j]], FP16 [rows, K] device, perm [K] INT32 device, not in place.
  *   qoq_quant_act_per_token_reordered   qoq_quant_act_per_token of x[:, perm] in one pass (K <= 32768).
  * perm entries outside [0, K) are clamped (a kernel cannot report them).
@@ -235,8 +245,12 @@ int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int
  * 128, 129, 130, 131 =
  * compute-bound kernel with tiles of 256 x 256, 128 x 256, 256 x 128, 256 x 192 (tokens x channels).
  * split_k >= 0 (0 = auto): for the compute-bound kernel the number of k-slices per output tile, for the
- * streaming kernel the number of workgroups the stream of work units is dealt to.  Process-wide;
- * returns QOQ_ERR_SHAPE for values outside the set.  Workspace sizes depend on it. */
+ * streaming kernel the number of workgroups the stream of work units is dealt to.
+ * Not part of the hot-call contract: the setting is process-wide (two atomics, no lock), so a thread that changes
+ * it while another thread sizes a workspace or launches a GEMM changes that thread's configuration too.  Set it
+ * once, before any qoq_gemm_workspace_bytes query whose result is still in use: workspace sizes depend on it, and a
+ * GEMM call checks its workspace against the size of the configuration in force at the call (QOQ_ERR_WORKSPACE if
+ * that is larger).  Returns QOQ_ERR_SHAPE for values outside the set. */
 int qoq_set_gemm_config(int tile_m, int split_k);
 /* The configuration a GEMM call of this shape would run with (host only, no device work): tile_m as above;
  * split_k = k-slices per tile (compute-bound kernel) or workgroups per token tile (streaming kernels).

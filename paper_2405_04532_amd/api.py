@@ -14,6 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libqoq_w4a8.so")
 
 QOQ_GROUP128 = 0
 QOQ_PER_CHANNEL = 1
+# qoq_status
+QOQ_OK, QOQ_ERR_NULL, QOQ_ERR_SHAPE, QOQ_ERR_ALIGN, QOQ_ERR_BLOB, QOQ_ERR_WORKSPACE, QOQ_ERR_ARCH, QOQ_ERR_HIP = range(8)
 GROUP = 128
 
 _lib = None

@@ -11,7 +11,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqoq_w4a8.so")
-PROBE = os.path.join(HERE, "mfma_ceiling")          # stand-alone matrix-core ceiling probe (measurement aid)
 SOURCES = ["qoq_api.hip", "qoq_pack.hip", "qoq_act.hip", "qoq_gemm.hip", "qoq_kv4.hip", "qoq_transforms.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions off (they have produced wrong results on these machines)
@@ -47,8 +46,6 @@ def build(extra_flags=(), verbose=False):
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
-    subprocess.check_call(["hipcc", os.path.join(CSRC, "mfma_ceiling.hip"), "-o", PROBE, "-w"] +
-                          [f for f in FLAGS if f != "-fPIC" and f != "-Wall"])
     if verbose:
         print("built", LIB)
     return LIB

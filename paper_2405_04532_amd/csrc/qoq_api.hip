@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <cmath>
 
 #include "../../include/qoq_w4a8.h"
 #include "qoq_internal.h"
@@ -15,6 +16,7 @@ std::atomic<int> g_forced_split_k{0};
 qoq::GemmTuning forced() { return {g_forced_tile_m.load(), g_forced_split_k.load()}; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 // 1 = gfx950, 0 = something else, cached per device (the query is slow).
 int arch_ok()
@@ -44,7 +46,8 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     if (M == 0) return QOQ_OK;  // empty batch: nothing to do
     if (!qx || !packed || (!out16 && !out32) || (out16 && !sx)) return QOQ_ERR_NULL;
     if (mode == QOQ_PER_CHANNEL && !rowsum && !tx) return QOQ_ERR_NULL;
-    if (tx && (reinterpret_cast<uintptr_t>(tx) & 3u)) return QOQ_ERR_ALIGN;
+    // the per-token vectors are fetched in 4-byte words (global->LDS copies in the compute-bound kernel)
+    if (!aligned4(tx) || !aligned4(sx) || !aligned4(rowsum)) return QOQ_ERR_ALIGN;
     if (!aligned16(qx) || !aligned16(packed) || !aligned16(out16) || !aligned16(out32) || !aligned16(ws))
         return QOQ_ERR_ALIGN;
     int tile_m, split_k;
@@ -78,6 +81,7 @@ const char* qoq_status_string(int status)
         case QOQ_ERR_NULL: return "QOQ_ERR_NULL: a required pointer is NULL";
         case QOQ_ERR_SHAPE: return "QOQ_ERR_SHAPE: unsupported M/N/K/mode (need K % 128 == 0, N % 64 == 0)";
         case QOQ_ERR_ALIGN: return "QOQ_ERR_ALIGN: pointer not 16-byte aligned";
+        case QOQ_ERR_BLOB: return "QOQ_ERR_BLOB: blob header does not match N, K, mode";
         case QOQ_ERR_WORKSPACE: return "QOQ_ERR_WORKSPACE: workspace missing or too small";
         case QOQ_ERR_ARCH: return "QOQ_ERR_ARCH: device is not gfx950";
         case QOQ_ERR_HIP: return "QOQ_ERR_HIP: HIP runtime error";
@@ -174,6 +178,12 @@ int qoq_unpack_weights(const void* packed_dev, int64_t N, int64_t K, int mode, u
     if (!aligned16(packed_dev)) return QOQ_ERR_ALIGN;
     if (!arch_ok()) return QOQ_ERR_ARCH;
     const qoq::BlobLayout L = qoq::make_layout(N, K, mode);
+    // debug path: read the blob's own description back and compare it with the arguments (synchronizes)
+    qoq::BlobHeader h;
+    if (hipMemcpyAsync(&h, packed_dev, sizeof(h), hipMemcpyDeviceToHost, static_cast<hipStream_t>(stream)) != hipSuccess ||
+        hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QOQ_ERR_HIP;
+    if (!qoq::header_matches(h, L)) return QOQ_ERR_BLOB;
     return qoq::launch_unpack(static_cast<const uint8_t*>(packed_dev), L, q_u4, s1_u8, z_u8, s_fp16,
                               static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
@@ -228,6 +238,8 @@ int qoq_channel_order_host(const float* salience_host, int64_t K, int32_t* perm_
 {
     if (K <= 0 || K > (1 << 24)) return QOQ_ERR_SHAPE;
     if (!salience_host || !perm_host) return QOQ_ERR_NULL;
+    for (int64_t k = 0; k < K; ++k)
+        if (!std::isfinite(salience_host[k])) return QOQ_ERR_SHAPE;   // a NaN would break the sort's ordering
     qoq::channel_order_host(salience_host, K, perm_host);
     return QOQ_OK;
 }

@@ -18,7 +18,7 @@
 //         the layer shape; a run may start and end in the middle of a block.
 //       - HBM latency under load is about 1.5-2.5 us here, so some 50-100 KiB per CU must be in flight.
 //         Each of eight consumer waves (fragment f, group parity e) copies the units it will itself consume
-//         into a private 10 deep LDS ring: no barrier guards the weights.  Activations come from L2 and
+//         into a private LDS ring, four units deep: no barrier guards the weights.  Activations come from L2 and
 //         need far less lead, but a wave's outstanding copies retire in order, so a wave issuing both would
 //         stall its deep weight prefetch on every activation wait: four producer waves copy the activation
 //         slabs, level-2 metadata and channel scales a couple of iterations ahead; one barrier per iteration

@@ -80,6 +80,14 @@ QOQ_HD BlobLayout make_layout(int64_t N, int64_t K, int mode)
     return L;
 }
 
+// Does a header read back from a blob describe exactly the layout `L` (same shape, mode and section offsets)?
+QOQ_HD bool header_matches(const BlobHeader& h, const BlobLayout& L)
+{
+    return h.magic == kMagic && h.version == kVersion && h.N == L.N && h.K == L.K && h.mode == L.mode &&
+           h.group == kGroup && h.codes_off == L.codes_off && h.meta_off == L.meta_off && h.scale_off == L.scale_off &&
+           h.zero_off == L.zero_off && h.total == L.total;
+}
+
 // logical output channel -> (physical fragment, row in fragment)
 QOQ_HD void phys_row(int64_t n, int64_t& nf, int& i)
 {

@@ -69,12 +69,26 @@ def test_argument_validation_without_gpu(api):
     assert L.qoq_w4a8_gemm(p, p, None, p, 0, 256, 256, 0, p, None, 0, None) == 0        # M = 0
     assert L.qoq_w4a8_gemm(p, p, None, p, 4, 256, 256, 0, None, None, 0, None) == 1
     assert L.qoq_w4a8_gemm_i32(p, None, p, 4, 256, 256, 0, p + 8, None, 0, None) == 3
+    # the per-token vectors are read in 4-byte words: a token-scale pointer that is only 2-byte aligned is refused
+    assert L.qoq_w4a8_gemm(p, p + 2, None, p, 4, 256, 256, 0, p, None, 0, None) == api.QOQ_ERR_ALIGN == 3
+    assert L.qoq_w4a8_gemm(p, p + 4, None, p, 4, 256, 256, 1, p, None, 0, None) == api.QOQ_ERR_NULL      # (aligned: next check)
+    assert L.qoq_w4a8_gemm(p, p, p + 2, p, 4, 256, 256, 1, p, None, 0, None) == api.QOQ_ERR_ALIGN
+    assert L.qoq_w4a8_gemm_token_sum(p, p, p + 2, p, 4, 256, 256, p, None, 0, None) == api.QOQ_ERR_ALIGN
+    assert "BLOB" in api.status_string(api.QOQ_ERR_BLOB) and api.QOQ_ERR_BLOB == 4
+    # a salience that is not finite has no place in an order
+    sal = (ctypes.c_float * 4)(1.0, float("nan"), 3.0, 2.0)
+    perm = (ctypes.c_int32 * 4)()
+    assert L.qoq_channel_order_host(sal, 4, perm) == api.QOQ_ERR_SHAPE
+    sal[1] = float("inf")
+    assert L.qoq_channel_order_host(sal, 4, perm) == api.QOQ_ERR_SHAPE
+    sal[1] = 0.5
+    assert L.qoq_channel_order_host(sal, 4, perm) == 0 and list(perm) == [2, 3, 0, 1]
     assert L.qoq_set_gemm_config(48, 0) == 2 and L.qoq_set_gemm_config(0, -1) == 2 and L.qoq_set_gemm_config(0, 0) == 0
     # split-k problems must come with a workspace
     need = api.gemm_workspace_bytes(16, 256, 4096)
     assert need >= 2 * 16 * 256 * 4 and need % 16 == 0          # counters + at least two partial tiles
-    assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, None, 0, None) == 4
-    assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, p, need - 16, None) == 4
+    assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, None, 0, None) == api.QOQ_ERR_WORKSPACE == 5
+    assert L.qoq_w4a8_gemm(p, p, None, p, 16, 256, 4096, 0, p, p, need - 16, None) == api.QOQ_ERR_WORKSPACE
     assert api.gemm_workspace_bytes(4096, 4096, 4096) == 0
     assert L.qoq_gemm_workspace_prepare(None, 64, None) == 1
     assert L.qoq_gemm_workspace_prepare(p, 24, None) == 3

@@ -1,0 +1,82 @@
+"""bench.py's contract with the driver: any --steps >= 1 and --warmup >= 0 are accepted and exactly that many
+steps are timed; the JSON line carries the roofline and the CPU baseline."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+
+def test_graph_schedule_times_exactly_the_requested_steps():
+    import bench
+
+    for per_graph in (1, 3, 8):
+        for steps in range(1, 50):
+            full, rem = bench.graph_schedule(steps, per_graph)
+            assert full >= 0 and 0 <= rem < per_graph
+            assert full * per_graph + rem == steps            # nothing rounded away, nothing added
+    assert bench.graph_schedule(20, 8) == (2, 4)               # the driver's command line
+    assert bench.graph_schedule(200, 8) == (25, 0)
+    assert bench.graph_schedule(1, 8) == (0, 1)
+    with pytest.raises(ValueError):
+        bench.graph_schedule(0, 8)
+
+
+def test_profile_traffic_follows_the_launch_configuration(tmp_path, monkeypatch):
+    """The counter figure is reported only while the library still picks the launch configurations it was measured
+    with; anything else reads as null rather than as a stale number."""
+    import bench
+
+    prof = tmp_path / "p.txt"
+    prof.write_text("some text\ntraffic_bytes_per_launch: 3.0e7 config: qkv=64/192,o=16/64\nmore text\n")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    monkeypatch.setattr(bench, "TRAFFIC_PROFILES", {"w": "p.txt", "gone": "missing.txt"})
+    assert bench.profile_traffic("w", "qkv=64/192,o=16/64") == (3.0e7, "p.txt")
+    assert bench.profile_traffic("w", "qkv=65/96,o=16/64") == (None, None)
+    assert bench.profile_traffic("gone", "qkv=64/192,o=16/64") == (None, None)
+    assert bench.profile_traffic("other", "x") == (None, None)
+
+
+def test_algorithmic_bytes_formula():
+    import bench
+
+    # packed codes + 1.5 B of level-2 metadata per group + FP16 channel scales + INT8 activations + FP16 token
+    # scales + FP16 output, for the QKV layer of the decode workload: 27.6 MB
+    M, N, K = 64, 12288, 4096
+    want = K * N // 2 + 3 * N * (K // 128) // 2 + 2 * N + M * K + 2 * M + 2 * M * N
+    assert bench.algorithmic_bytes(M, N, K) == want
+    assert abs(want - 27.6e6) < 0.1e6
+
+
+@pytest.mark.gpu
+@pytest.mark.timeout(900)
+def test_driver_command_line_prints_one_complete_json_line():
+    """`python bench.py --gpus 1 --steps 20 --warmup 5`, as the driver runs it, in a fresh process."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "1", "--steps", "20", "--warmup", "5"],
+                       cwd=ROOT, capture_output=True, text=True, timeout=850)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1, lines
+    d = json.loads(lines[0])
+    assert d["steps"] == 20 and d["warmup"] == 5 and d["n_gpus"] == 1
+    assert d["unit"] == "TOPS" and d["value"] > 0 and d["ms_per_step"] > 0 and d["higher_is_better"] is True
+    assert d["config"]["workload"].startswith("llama2_7b_decode_m64")
+    roof = d["roofline"]
+    assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    assert "traffic" in roof
+    cpu = d["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
+    leg = d["compute_leg"]
+    assert leg["workload"] == "llama3_70b_prefill_m2048"
+    assert leg["roofline"]["bound"] == "mfma" and leg["roofline"]["peak"] == 5033.0 and 0 < leg["roofline"]["frac"] < 1
+
+
+def test_more_than_one_gpu_is_refused():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], cwd=ROOT, capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr

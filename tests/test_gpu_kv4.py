@@ -154,7 +154,7 @@ def test_attention_split_over_workgroups(H, Hkv):
     L = api.lib()
     out = torch.empty_like(q)
     assert L.qoq_kv4_attention_decode_split(q.data_ptr(), cache.data_ptr(), seq.data_ptr(), 2, H, Hkv, 128, 2000, out.data_ptr(),
-                                            ws.data_ptr(), 16, None) == 4
+                                            ws.data_ptr(), 16, None) == api.QOQ_ERR_WORKSPACE
 
 
 def test_attention_long_sequence_many_pages():

@@ -85,6 +85,27 @@ def test_pack_quantized_roundtrip(api):
     assert (_np(s0g).view(np.uint16) == s0.view(np.uint16)).all()
 
 
+def test_unpack_refuses_a_blob_of_another_layer(api):
+    """The blob describes itself (shape, mode, section offsets); the debug unpack reads that header back and
+    refuses arguments that do not match it, instead of reading the sections at the wrong places."""
+    w = wl.make_weights(256, 512, 11, DEV)
+    blob = api.pack_weights(w, api.QOQ_GROUP128)
+    api.unpack_weights(blob, 256, 512, api.QOQ_GROUP128)                       # the right description passes
+    for N, K, mode in ((512, 256, api.QOQ_GROUP128), (256, 256, api.QOQ_GROUP128), (128, 512, api.QOQ_GROUP128),
+                       (256, 512, api.QOQ_PER_CHANNEL)):
+        with pytest.raises(api.QoqError) as e:
+            api.unpack_weights(blob, N, K, mode)
+        assert e.value.status == api.QOQ_ERR_BLOB, (N, K, mode)
+    junk = torch.zeros_like(blob)                                               # no magic at all
+    with pytest.raises(api.QoqError) as e:
+        api.unpack_weights(junk, 256, 512, api.QOQ_GROUP128)
+    assert e.value.status == api.QOQ_ERR_BLOB
+    blob_c = api.pack_weights(w, api.QOQ_PER_CHANNEL)
+    with pytest.raises(api.QoqError) as e:
+        api.unpack_weights(blob_c, 256, 512, api.QOQ_GROUP128)
+    assert e.value.status == api.QOQ_ERR_BLOB
+
+
 # ---------------------------------------------------------------------------- activations
 @pytest.mark.parametrize("M,K", [(16, 256), (1, 128), (37, 4096), (5, 11008), (3, 28672), (2, 32768), (3, 40960),
                                  (2048, 4096), (2100, 1024), (2048, 4224)])   # last three: many rows (256 threads per row where a row is short)
@@ -370,7 +391,7 @@ def test_runtime_errors_leave_outputs_untouched(api):
     tiny = torch.empty(16, dtype=torch.uint8, device=DEV)
     with pytest.raises(api.QoqError) as e:
         api.w4a8_gemm(qx, sx, blob, 256, out=out, workspace=tiny)
-    assert e.value.status == 4
+    assert e.value.status == api.QOQ_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
 
