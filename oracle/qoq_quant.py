@@ -17,7 +17,11 @@ in exact integer arithmetic.
 Pins (tests/test_oracle_*.py): the printed protective-range example, an exhaustive
 sweep of every level-2 group range inside [-119, 119], half-step round-trip bounds at
 both levels, exact-fraction re-computation on small inputs, and brute-force
-dequantize-then-FP64-matmul on tiny shapes.
+dequantize-then-FP64-matmul on tiny shapes.  The two producers (rmsnorm_fp16,
+silu_mul_fp16) are pinned by FP16 bit patterns computed in 60-digit decimal arithmetic
+(tests/golden/make_producer_golden.py, which imports nothing from here) and, for the
+order of the FP64 operations of rmsnorm_fp16, by inputs constructed next to FP16
+rounding midpoints on which the other natural order rounds differently.
 """
 import numpy as np
 

@@ -83,12 +83,21 @@ def test_level2_overflows_without_protection():
 
 
 def test_level2_literal_nearest_scale_breaks_half_step():
-    """Why the scale is rounded up: with round-to-nearest of span/15 the top code saturates
-    (span 112 -> scale 7 covers only 105) and the half-step bound fails."""
-    span, s_near = 112, int(np.floor(112 / 15 + 0.5))
-    assert s_near == 7 and 15 * s_near < span
-    s1, z = qq.level2_group_params(0, span)
-    assert int(s1) == 8 and 15 * int(s1) >= span
+    """Why the scale is rounded up: the encoder run with the scale rounded to NEAREST (span 112 -> 7, which covers
+    only 105) saturates the top code and breaks the half-step bound the protective range is derived from; with
+    the oracle's own scale (8) the same values round-trip within half a step."""
+    lo, hi = 0, 112
+    q = np.arange(lo, hi + 1)
+    s_near = np.int64((2 * (hi - lo) + 15) // 30)                    # round-half-up of span / 15
+    z_near = np.int64((2 * (-lo) + s_near) // (2 * s_near))
+    assert int(s_near) == 7 and int(z_near) == 0
+    back = (qq.level2_encode(q, s_near, z_near) - z_near) * s_near    # the oracle's encoder, literal nearest scale
+    assert int(back.max()) == 105                                     # 112 saturates at code 15
+    assert (2 * np.abs(back - q) > s_near).any()                      # half-step bound violated (112 - 105 = 7 > 3.5)
+    s1, z = qq.level2_group_params(lo, hi)
+    assert int(s1) == 8 and int(z) == 0
+    back = (qq.level2_encode(q, s1, z) - z) * s1
+    assert (2 * np.abs(back - q) <= s1).all() and int(back.max()) == 112
 
 
 def test_level2_group_layout_and_roundtrip():
@@ -301,20 +310,132 @@ def test_rmsnorm_against_per_element_fractions():
             assert abs(float(y[m, k]) - float(want)) <= abs(float(want)) * 2 ** -10   # at most one FP16 ulp apart
 
 
-def test_silu_mul_identities():
-    import math
-    g = np.array([[0.0, 1.0, -1.0, 8.0, -8.0, 0.5]], dtype=np.float16)
-    u = np.array([[3.0, 2.0, 2.0, 1.0, 1.0, -4.0]], dtype=np.float16)
-    y = qq.silu_mul_fp16(np.concatenate([g, u], axis=1)).astype(np.float64)[0]
-    for i in range(6):
-        gv, uv = float(g[0, i]), float(u[0, i])
-        want = np.float16(gv / (1.0 + math.exp(-gv)) * uv)
-        assert float(y[i]) == float(want)
-    assert y[0] == 0.0
-    # silu(x) - silu(-x) == x, checked through two columns with up = 1
-    gg = np.array([[1.5, -1.5]], dtype=np.float16)
-    yy = qq.silu_mul_fp16(np.concatenate([gg, np.ones((1, 2), np.float16)], axis=1)).astype(np.float64)[0]
-    assert abs((yy[0] - yy[1]) - 1.5) <= 2 ** -10
+def _golden_lines(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    return [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+
+
+def _silu_mul_against_decimal():
+    """400 (gate, up) pairs whose expected FP16 bits were computed from g / (1 + exp(-g)) * u in 60-digit decimal
+    arithmetic by tests/golden/make_producer_golden.py (which imports nothing of the oracle)."""
+    rows = _golden_lines("silu_mul_decimal.txt")
+    assert len(rows) == 400
+    g = np.array([int(r[0], 16) for r in rows], dtype=np.uint16).view(np.float16)
+    u = np.array([int(r[1], 16) for r in rows], dtype=np.uint16).view(np.float16)
+    want = np.array([int(r[2], 16) for r in rows], dtype=np.uint16)
+    with np.errstate(over="ignore"):
+        got = qq.silu_mul_fp16(np.concatenate([g, u])[None, :])[0].view(np.uint16)
+    # +0 and -0 are the same number: the decimal computation has no signed zero
+    same = (got == want) | (((got | want) & 0x7FFF) == 0)
+    assert same.all(), "first mismatch at pair %d" % int(np.argmin(same))
+    assert int(((want & 0x7FFF) != 0).sum()) > 300                 # most pairs have a non-zero result
+
+
+def test_silu_mul_literal_values():
+    _silu_mul_against_decimal()
+    # a few values one can check by hand: silu(0) = 0; silu(1) * 2 = 2 / (1 + 1/e) = 1.46211715...; silu(-1) * 2 = -0.53788...
+    y = qq.silu_mul_fp16(np.array([[0.0, 1.0, -1.0, 3.0, 2.0, 2.0]], dtype=np.float16))[0].astype(np.float64)
+    assert y[0] == 0.0 and abs(y[1] - 1.4621171572600098) < 2 ** -10 and abs(y[2] + 0.5378828427399902) < 2 ** -11
     # orientation: gate is the FIRST half
     z = qq.silu_mul_fp16(np.array([[0.0, 5.0]], dtype=np.float16))
     assert float(z[0, 0]) == 0.0
+
+
+@pytest.mark.parametrize("bad", ["exponent_sign", "halves_swapped", "sigmoid_only"])
+def test_silu_mul_pins_catch_planted_mistakes(bad, monkeypatch):
+    def wrong(gate_up_fp16):
+        a = np.asarray(gate_up_fp16, dtype=np.float16).astype(np.float64)
+        k = a.shape[1] // 2
+        gate, up = (a[:, k:], a[:, :k]) if bad == "halves_swapped" else (a[:, :k], a[:, k:])
+        with np.errstate(over="ignore"):
+            if bad == "exponent_sign":
+                return (gate / (1.0 + np.exp(gate)) * up).astype(np.float16)
+            if bad == "sigmoid_only":
+                return (1.0 / (1.0 + np.exp(-gate)) * up).astype(np.float16)
+            return (gate / (1.0 + np.exp(-gate)) * up).astype(np.float16)
+    monkeypatch.setattr(qq, "silu_mul_fp16", wrong)
+    with pytest.raises(AssertionError):
+        _silu_mul_against_decimal()
+
+
+def _rmsnorm_against_decimal():
+    """Eight token rows (eps = 0, the usual 1e-5/1e-6, large eps, an all-zero token) whose expected FP16 bits come
+    from x * gamma / sqrt(mean(x^2) + eps) in 60-digit decimal arithmetic (tests/golden/make_producer_golden.py)."""
+    rows = _golden_lines("rmsnorm_decimal.txt")
+    i = 0
+    seen = 0
+    while i < len(rows):
+        assert rows[i][0] == "row" and rows[i][2] == "eps"
+        eps = float.fromhex(rows[i][3])
+        body = rows[i + 1:i + 33]
+        x = np.array([int(r[0], 16) for r in body], dtype=np.uint16).view(np.float16)
+        g = np.array([int(r[1], 16) for r in body], dtype=np.uint16).view(np.float16)
+        want = np.array([int(r[2], 16) for r in body], dtype=np.uint16)
+        got = qq.rmsnorm_fp16(x[None, :], g, eps)[0].view(np.uint16)
+        same = (got == want) | (((got | want) & 0x7FFF) == 0)
+        assert same.all(), "row %d element %d" % (seen, int(np.argmin(same)))
+        i += 33
+        seen += 1
+    assert seen == 8
+
+
+def test_rmsnorm_literal_values():
+    _rmsnorm_against_decimal()
+
+
+@pytest.mark.parametrize("bad", ["sum_not_mean", "eps_outside_root", "no_gamma", "no_root"])
+def test_rmsnorm_pins_catch_planted_mistakes(bad, monkeypatch):
+    def wrong(x_fp16, gamma_fp16, eps):
+        x = np.asarray(x_fp16, dtype=np.float16).astype(np.float64)
+        g = np.asarray(gamma_fp16, dtype=np.float16).astype(np.float64)
+        ms = (x * x).sum(axis=1) / (1 if bad == "sum_not_mean" else x.shape[1])
+        with np.errstate(divide="ignore", invalid="ignore"):
+            if bad == "eps_outside_root":
+                r = 1.0 / (np.sqrt(ms) + float(eps))
+            elif bad == "no_root":
+                r = 1.0 / (ms + float(eps))
+            else:
+                r = 1.0 / np.sqrt(ms + float(eps))
+            y = x * r[:, None] * (1.0 if bad == "no_gamma" else g[None, :])
+        return np.nan_to_num(y).astype(np.float16)
+    monkeypatch.setattr(qq, "rmsnorm_fp16", wrong)
+    with pytest.raises(AssertionError):
+        _rmsnorm_against_decimal()
+
+
+def test_rmsnorm_evaluation_order_is_pinned():
+    """The order of the FP64 operations is part of the definition: y = fp16((x * r) * gamma) with r = 1 / sqrt(mean(x^2) + eps)
+    formed once per token.  The other natural order, (x / sqrt(...)) * gamma, agrees except when the exact value
+    lies within about 1e-16 (relative) of an FP16 rounding midpoint.  Such inputs are constructed here by steering
+    eps (any non-negative double is a valid input) so that one element's exact value falls next to a midpoint; in
+    every case below the two orders round to different FP16 numbers, and the oracle must give the first order's.
+    Which of the two is the correctly rounded exact value varies from case to case (checked in exact rationals):
+    neither order is "the" right one, so the choice is a convention, and this test is what fixes it."""
+    import math
+    from fractions import Fraction
+    K = 128
+    x = np.array([(((k * 37) % 129) - 64) / 64.0 for k in range(K)], dtype=np.float16)
+    ms = sum(Fraction(float(v)) ** 2 for v in x) / K
+    cases = [(1, 15039, "0x1.4482d7f405400p-12"), (1, 14558, "0x1.e2b71aa2c8000p-14"), (2, 14521, "0x1.0c3642b521200p-11"),
+             (2, 14632, "0x1.fb0326ebc4400p-12"), (1, 15409, "0x1.8986b51166800p-12"), (1, 15816, "0x1.03f1748838600p-11")]
+    chosen_is_exact = []
+    for k0, gbits, eps_hex in cases:
+        eps = float.fromhex(eps_hex)
+        g = np.ones(K, dtype=np.float16)
+        g[k0] = np.array([gbits], dtype=np.uint16).view(np.float16)[0]
+        x0, g0 = float(x[k0]), float(g[k0])
+        t = float(ms) + eps
+        assert Fraction(t) == ms + Fraction(eps)                           # the sum under the root is exact here
+        root = math.sqrt(t)
+        first = np.float16((x0 * (1.0 / root)) * g0)                       # reciprocal root once per token, multiplied in
+        other = np.float16((x0 / root) * g0)
+        assert first != other                                              # a genuine straddle
+        y = qq.rmsnorm_fp16(x[None, :], g, eps)[0]
+        assert y[k0] == first, (k0, gbits)
+        # the exact value: |x0 g0| / sqrt(t) compared with the midpoint between the two candidates, on squares
+        mid = (Fraction(float(first)) + Fraction(float(other))) / 2
+        above = (Fraction(x0) * Fraction(g0)) ** 2 > mid ** 2 * Fraction(t)
+        exact = max(first, other, key=lambda v: abs(float(v))) if above else min(first, other, key=lambda v: abs(float(v)))
+        chosen_is_exact.append(bool(exact == first))
+    assert any(chosen_is_exact) and not all(chosen_is_exact)
