@@ -53,7 +53,7 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     int tile_m, split_k;
     qoq::pick_gemm_config(M, N, K, mode, forced(), tile_m, split_k);
     if ((uint64_t)M * (uint64_t)K >= ((uint64_t)1 << 32)) return QOQ_ERR_SHAPE;  // 32-bit activation offsets
-    if (tile_m <= 68 && (uint64_t)N * (uint64_t)K >= ((uint64_t)1 << 33)) return QOQ_ERR_SHAPE;  // 32-bit weight offsets (4 GiB packed)
+    if (tile_m <= 71 && (uint64_t)N * (uint64_t)K >= ((uint64_t)1 << 33)) return QOQ_ERR_SHAPE;  // 32-bit weight offsets (4 GiB packed)
     const size_t need = qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
     if (need && (!ws || ws_bytes < need)) return QOQ_ERR_WORKSPACE;
     if (x_fp16 && !aligned16(x_fp16)) return QOQ_ERR_ALIGN;
@@ -132,7 +132,7 @@ int qoq_gemm_workspace_prepare(void* workspace, size_t workspace_bytes, void* st
 
 int qoq_set_gemm_config(int tile_m, int split_k)
 {
-    if (!(tile_m == 0 || tile_m == 16 || tile_m == 32 || tile_m == 64 || (tile_m >= 65 && tile_m <= 68) || (tile_m >= 128 && tile_m <= 131)) || split_k < 0)
+    if (!(tile_m == 0 || tile_m == 16 || tile_m == 32 || tile_m == 64 || (tile_m >= 65 && tile_m <= 71) || (tile_m >= 128 && tile_m <= 131)) || split_k < 0)
         return QOQ_ERR_SHAPE;
     g_forced_tile_m.store(tile_m);
     g_forced_split_k.store(split_k);

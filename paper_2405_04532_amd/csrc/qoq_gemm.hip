@@ -39,62 +39,11 @@
 #include <hip/hip_runtime.h>
 
 #include "qoq_internal.h"
+#include "qoq_gemm_common.h"
 #include "qoq_walk.h"
 
 namespace qoq {
 namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kThreads = 256;
-constexpr int kNFrag = 4;  // 16-row fragments per wave = 64 output channels
-
-struct GemmDev {
-    const int8_t* qx;
-    const uint4* codes;
-    const uint16_t* meta;
-    const __half* scales;
-    const uint8_t* zeros;
-    const __half* sx;
-    const int32_t* rowsum;
-    __half* out16;
-    int32_t* out32;
-    int* counters;  // split-k: one per output tile, zero on entry and on exit
-    int4* parts;    // split-k: [tile][split][value][thread]
-    int M, N, K, G, gps, S;  // gps = groups per k-split, S = number of k-splits (tiled kernel)
-    int upw;                 // stream kernel: work units per workgroup
-    int token_sum;           // per-channel FP16 epilogue in the token-sum form: `rowsum` then holds the FP32 sums t_X
-};
-
-enum { OUT_FP16 = 0, OUT_I32 = 1 };
-
-__device__ inline uint32_t pk_mad_u16(uint32_t a, uint32_t s, uint32_t b)
-{
-    us2 r = __builtin_bit_cast(us2, a) * __builtin_bit_cast(us2, s) + __builtin_bit_cast(us2, b);
-    return __builtin_bit_cast(uint32_t, r);
-}
-
-// Two packed dwords (16 codes) -> one 16-byte INT8 MFMA operand.
-template <bool GROUP>
-__device__ inline v4i dequant(uint32_t x0, uint32_t x1, uint32_t S, uint32_t B)
-{
-    const uint32_t m = 0x0F0F0F0Fu;
-    uint32_t o0 = x0 & m, o1 = (x0 >> 4) & m, o2 = x1 & m, o3 = (x1 >> 4) & m;
-    if (GROUP) {
-        const uint32_t sign = 0x80808080u;
-        o0 = pk_mad_u16(o0, S, B) ^ sign;
-        o1 = pk_mad_u16(o1, S, B) ^ sign;
-        o2 = pk_mad_u16(o2, S, B) ^ sign;
-        o3 = pk_mad_u16(o3, S, B) ^ sign;
-    }
-    v4i r;
-    r.x = (int)o0; r.y = (int)o1; r.z = (int)o2; r.w = (int)o3;
-    return r;
-}
-
-__device__ inline v4i as_v4i(uint4 t) { return (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w}; }
 
 // Hand-over of partial tiles between workgroups (which may sit on different XCDs, each with its own L2)
 // without device-wide fences: a release/acquire fence pair writes back and invalidates a whole L2 and was
@@ -109,33 +58,6 @@ __device__ inline v4i as_v4i(uint4 t) { return (v4i){(int)t.x, (int)t.y, (int)t.
 // iteration, the group of parity e of a pair of consecutive groups.
 // ------------------------------------------------------------------------------------------
 
-// Direct global -> LDS copy, 16 (or 4) bytes per lane; lane l lands at lds_addr + 16*l (4*l).
-// `base` is wave-uniform, `voff` the lane's byte offset.  Opaque to the compiler on purpose.
-// M0 (the copy's LDS base) is a reserved register that nothing else in these kernels uses, so
-// it is not listed as a clobber.
-__device__ __forceinline__ const void* to_sgpr(const void* ptr)   // value is wave-uniform; pin it to scalar registers
-{
-    const uint64_t v = reinterpret_cast<uint64_t>(ptr);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
-}
-__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(to_sgpr(base)) : "memory");
-}
-__device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(to_sgpr(base)) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
-}
 // Write-through store / cache-bypassing load of 16 bytes (device-coherent without fences).
 // A store of more than 8 bytes reads its data registers over several cycles after issue; the instruction that
 // follows must not write them (a documented wait-state requirement the compiler honours for its own stores but
@@ -146,24 +68,6 @@ __device__ __forceinline__ void wait_vmcnt()
 __device__ __forceinline__ void store_sc1(int4* ptr, v4i v)
 {
     asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" :: "v"(ptr), "v"(v) : "memory");
-}
-// Compiler-visible write-through store / cache-bypassing load (two relaxed device-scope 8-byte atomics each): the
-// compiler tracks their registers and waits itself.  For code with no copy queue to preserve, and wherever
-// control flow lies between a load and its use (the compiler may copy a register it believes already loaded).
-__device__ __forceinline__ void store_through(int4* ptr, int a, int b, int c, int d)
-{
-    unsigned long long* q = reinterpret_cast<unsigned long long*>(ptr);
-    __hip_atomic_store(q, (unsigned long long)(uint32_t)a | ((unsigned long long)(uint32_t)b << 32), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(q + 1, (unsigned long long)(uint32_t)c | ((unsigned long long)(uint32_t)d << 32), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ v4i load_through(const int4* ptr)
-{
-    unsigned long long* q = const_cast<unsigned long long*>(reinterpret_cast<const unsigned long long*>(ptr));
-    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return (v4i){(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
 }
 template <int CNT>
 __device__ __forceinline__ void store_sc1_and_wait(int4* ptr, int stride, const v4i (&v)[CNT])
@@ -200,40 +104,6 @@ __device__ __forceinline__ void wait_loads(v4i& a, v4i& b, v4i& c, v4i& d)
 }
 
 constexpr int kStreamThreads = 768;  // eight consumer waves + four producer waves
-
-template <bool GROUP, int OUT>
-__device__ __forceinline__ void finish4(const GemmDev& p, int m, int n0, v4i v, const float (&sn)[4],
-                                        const int (&zn)[4], float sxm, int rs)
-{
-    int t[4] = {v.x, v.y, v.z, v.w};
-    // Per-channel zero point: exact integer fold acc - z * rowsum (Eq. 6), or, in the token-sum form (Eq. 7),
-    // acc * sx * s - t_X * (z * s) in FP32 with `rs` carrying the bits of t_X.
-    const bool token_sum = !GROUP && OUT == OUT_FP16 && p.token_sum;
-    if constexpr (!GROUP) {
-        if (!token_sum) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) t[j] -= zn[j] * rs;
-        }
-    }
-    if constexpr (OUT == OUT_I32) {
-        *reinterpret_cast<int4*>(p.out32 + (size_t)m * p.N + n0) = make_int4(t[0], t[1], t[2], t[3]);
-    } else {
-        const float txm = __int_as_float(rs);
-        uint32_t h[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            float ra = (float)t[2 * j] * (sxm * sn[2 * j]), rb = (float)t[2 * j + 1] * (sxm * sn[2 * j + 1]);
-            if (token_sum) {
-                ra -= txm * ((float)zn[2 * j] * sn[2 * j]);
-                rb -= txm * ((float)zn[2 * j + 1] * sn[2 * j + 1]);
-            }
-            const __half a = __float2half_rn(ra);
-            const __half b = __float2half_rn(rb);
-            h[j] = (uint32_t)__half_as_ushort(a) | ((uint32_t)__half_as_ushort(b) << 16);
-        }
-        *reinterpret_cast<uint2*>(p.out16 + (size_t)m * p.N + n0) = make_uint2(h[0], h[1]);
-    }
-}
 
 // Blocks shared with other workgroups: this workgroup has written its partial tiles (at most two) to the
 // workspace and waited for them.  It bumps each block's counter; whoever arrives last at a block adds every
@@ -1632,7 +1502,9 @@ void launch_mma(const GemmDev& p, bool fp16, hipStream_t s)
 template <bool GROUP>
 void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 {
-    if (tile_m == 66) {
+    if (tile_m >= 69 && tile_m <= 71) {
+        (void)launch_astat(p, tile_m, nwg, GROUP, fp16, s);
+    } else if (tile_m == 66) {
         const dim3 grid((unsigned)nwg, (unsigned)((p.M + 63) / 64));
         if (fp16) lockstep_kernel<4, 4, GROUP, OUT_FP16><<<grid, kStreamThreads, 0, s>>>(p);
         else lockstep_kernel<4, 4, GROUP, OUT_I32><<<grid, kStreamThreads, 0, s>>>(p);
@@ -1781,6 +1653,27 @@ static StreamPlan pair_plan(int64_t M, int64_t N, int64_t G, int64_t forced_nwg,
     return {nwg, 4.3 + std::max(loop, weight_mb * reads / 4.5)};
 }
 
+// Activation-stationary kernels (tile_m 69 / 70 / 71 = 16 / 32 / 64 tokens): k-slices so that a slice's groups fit a
+// workgroup's registers, and the workgroups per (token tile, k-slice) that share the layer's 16-channel fragments.
+static int astat_tile(int tile_m) { return tile_m == 71 ? 64 : tile_m == 70 ? 32 : 16; }
+static void astat_slices(int64_t G, int tile_m, int64_t& S, int64_t& gps)
+{
+    const int64_t cap = astat_max_groups(astat_tile(tile_m));
+    S = (G + cap - 1) / cap;
+    gps = (G + S - 1) / S;
+    S = (G + gps - 1) / gps;
+}
+static int64_t astat_nwg(int64_t M, int64_t N, int64_t G, int tile_m, int64_t forced_nwg)
+{
+    const int64_t tile = astat_tile(tile_m), m_tiles = (M + tile - 1) / tile, frags = N / 16;
+    int64_t S, gps;
+    astat_slices(G, tile_m, S, gps);
+    int64_t nwg = forced_nwg > 0 ? forced_nwg : std::max<int64_t>(1, 256 / (m_tiles * S));
+    nwg = std::min(nwg, frags);
+    if (S > 1) nwg = std::max(nwg, (frags + 127) / 128);   // at most 128 fragments per workgroup when slices meet in the workspace
+    return nwg;
+}
+
 void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTuning& forced, int& tile_m, int& split_k)
 {
     const int64_t G = K / kGroup;
@@ -1794,6 +1687,20 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
         if (c.cost < 0.99 * plan.cost) { plan = c; stream_tile = t; }
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
+    // Up to 32 tokens the activation-stationary kernels are the fastest wherever one workgroup can hold the whole
+    // of K and there is at least a fragment per compute unit (measured on the Llama-2-7B layers at 1 ... 32 tokens:
+    // 5 - 25% ahead of the register-streaming and lockstep kernels for K = 4096, behind them for K = 11008, where
+    // those spread K over the chip; at 64 tokens loading the [64, K] slab costs more than it saves).
+    if (!forced.tile_m && M <= 32) {
+        const int cand = M <= 16 ? 69 : 70;
+        int64_t S, gps;
+        astat_slices(G, cand, S, gps);
+        if (S == 1 && G <= 64 && N / 16 >= 192) tile_m = cand;
+    }
+    if (tile_m >= 69 && tile_m <= 71) {
+        split_k = (int)astat_nwg(M, N, G, tile_m, forced.split_k);
+        return;
+    }
     if (tile_m == 65 && !pairs_ok) tile_m = 64;
     if (tile_m == 67 && !pairs_ok) tile_m = 32;
     if (tile_m == 68 && !pairs_ok) tile_m = 16;
@@ -1854,6 +1761,13 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
 {
+    if (tile_m >= 69 && tile_m <= 71) {               // k-slices of the activation-stationary kernels meet per fragment
+        int64_t S, gps;
+        astat_slices(K / kGroup, tile_m, S, gps);
+        if (S <= 1) return 0;
+        const int64_t tile = astat_tile(tile_m), m_tiles = (M + tile - 1) / tile, frags = N / 16;
+        return align256((size_t)(m_tiles * frags) * sizeof(int)) + (size_t)(m_tiles * frags * S) * (size_t)(tile * 64);
+    }
     if (tile_m >= 65 && tile_m <= 68) return 0;        // whole block pairs / quads per workgroup: nothing is exchanged
     if (tile_m <= 64) {
         const int64_t m_tiles = (M + tile_m - 1) / tile_m;
@@ -1868,6 +1782,17 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int spl
     mma_tile_shape(tile_m, tm, tn);
     const size_t tiles = (size_t)mma_tiles(M, N, tile_m);
     return align256(tiles * sizeof(int)) + tiles * (size_t)split_k * (size_t)(tm * tn) * sizeof(int32_t);
+}
+
+size_t gemm_counter_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k)
+{
+    if (gemm_workspace_bytes(M, N, K, tile_m, split_k) == 0) return 0;
+    if (tile_m >= 69 && tile_m <= 71) {
+        const int64_t tile = astat_tile(tile_m);
+        return align256((size_t)(((M + tile - 1) / tile) * (N / 16)) * sizeof(int));
+    }
+    if (tile_m <= 64) return align256((size_t)(((M + tile_m - 1) / tile_m) * (N / 64)) * sizeof(int));
+    return align256((size_t)mma_tiles(M, N, tile_m) * sizeof(int));
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
@@ -1889,7 +1814,14 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
     p.counters = reinterpret_cast<int*>(a.workspace);
     int nwg = 0;
     size_t counters;
-    if (a.tile_m >= 65 && a.tile_m <= 68) {
+    if (a.tile_m >= 69 && a.tile_m <= 71) {
+        int64_t S, gps;
+        astat_slices(L.G, a.tile_m, S, gps);
+        p.upw = 0;
+        nwg = a.split_k;
+        p.S = (int)S; p.gps = (int)gps;
+        counters = gemm_counter_bytes(a.M, a.N, a.K, a.tile_m, a.split_k);
+    } else if (a.tile_m >= 65 && a.tile_m <= 68) {
         const int64_t width = a.tile_m == 66 ? 256 : 128;
         if (a.N % width != 0) return hipErrorInvalidValue;
         const int64_t pairs = a.N / width;

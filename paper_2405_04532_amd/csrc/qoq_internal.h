@@ -40,6 +40,8 @@ struct GemmArgs {
     int tile_m;              // 16, 32, 64 (streaming kernels) or 128 ... 131 (compute-bound kernel, four tile shapes)
     int split_k;             // compute-bound kernel: k-slices per tile; streaming kernel: workgroups sharing the unit stream
 };
+// Bytes of arrival counters at the start of the workspace of a (tile_m, split_k) launch (0 if it exchanges nothing).
+size_t gemm_counter_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 
 // Workspace a (tile_m, split_k) launch needs: per-tile counters, then the partial tiles.

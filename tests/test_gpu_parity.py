@@ -268,6 +268,40 @@ def test_quad_streaming_kernel(api, M, N, K, split_k, mode):
     check_fp16(out, ref["out64"])
 
 
+@pytest.mark.parametrize("tile_m", [69, 70, 71])
+@pytest.mark.parametrize("M,N,K,split_k,mode", [
+    (64, 640, 1152, 0, 0),      # nine groups: slots past the slice in most waves
+    (1, 640, 1152, 1, 1),       # one workgroup walks all forty fragments
+    (17, 320, 640, 3, 0),       # ragged tokens, fragment runs of unequal length
+    (50, 384, 128, 0, 1),       # a single group
+    (64, 256, 4096, 0, 0),      # thirty-two groups: every register slot of a 64-token tile in use
+    (63, 1280, 2048, 7, 1),
+    (100, 128, 256, 0, 0),      # several token tiles side by side
+    (33, 192, 5120, 0, 0),      # forty groups: two k-slices for 64-token tiles, one for the smaller ones
+    (64, 256, 11008, 5, 1),     # eighty-six groups: k-slices meet in the workspace (3 / 2 / 1 slices), ragged last slice
+    (130, 320, 8192, 0, 0),     # k-slices and several token tiles
+])
+def test_activation_stationary_kernels(api, tile_m, M, N, K, split_k, mode):
+    """The kernels that keep the activations in registers and stream nothing but weights (codes 69, 70, 71 = 16, 32
+    and 64 tokens per tile), both modes, with and without k-slices."""
+    w, x = rand_inputs(M, N, K, seed=11 + M + N)
+    ref = (ogemm.forward_per_channel if mode else ogemm.forward_group)(_np(w), _np(x))
+    blob = api.pack_weights(w, mode)
+    qx, sx, rowsum, _ = api.quant_act_per_token(x)
+    api.set_gemm_config(tile_m, split_k)
+    try:
+        assert api.query_gemm_config(M, N, K, mode)[0] == tile_m
+        acc = api.w4a8_gemm_i32(qx, blob, N, mode, rowsum=rowsum)
+        out = api.w4a8_gemm(qx, sx, blob, N, mode, rowsum=rowsum)
+        acc2 = api.w4a8_gemm_i32(qx, blob, N, mode, rowsum=rowsum)      # again over the same workspace contract
+        torch.cuda.synchronize()
+    finally:
+        api.set_gemm_config(0, 0)
+    assert (_np(acc).astype(np.int64) == ref["acc"]).all()
+    assert (_np(acc2).astype(np.int64) == ref["acc"]).all()
+    check_fp16(out, ref["out64"])
+
+
 @pytest.mark.parametrize("M,tile_m,split_k", [(256, 64, 0), (256, 64, 8), (200, 32, 6), (320, 64, 12)])
 def test_group_streaming_kernel_many_token_tiles(api, M, tile_m, split_k):
     """The M <= 64 kernel forced onto several token tiles, with runs that end exactly at a block end and
