@@ -117,6 +117,22 @@ int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum,
                   const void* packed, int64_t M, int64_t N, int64_t K, int mode,
                   void* out_fp16, void* workspace, size_t workspace_bytes, void* stream);
 
+/* qoq_w4a8_gemm for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels, same result bit for
+ * bit; the split-k scratch (arrival counters and partial tiles) lives in an array inside the library instead of a
+ * caller's workspace: 16 MiB of partial tiles and 256 KiB of counters per GPU, held by every GPU the library runs on
+ * until the process ends.  The call allocates and frees nothing (the first call on a device looks up the array's
+ * address on that device, which allocates nothing either; make that first call before a capture begins).
+ *   - A problem whose launch configuration needs more scratch than that returns QOQ_ERR_WORKSPACE and enqueues
+ *     nothing (use qoq_w4a8_gemm with a workspace; qoq_gemm_workspace_bytes tells the size: up to 16 MiB + the
+ *     counters fit).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ *     race on it; order them on one stream.  The array keeps the last call's partial tiles; its counters are left
+ *     at zero by every call, which is all the next call relies on.
+ * Other arguments and errors as for qoq_w4a8_gemm. */
+int qoq_w4a8_gemm_noalloc(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum, const void* packed,
+                          int64_t M, int64_t N, int64_t K, int mode, void* out_fp16, void* stream);
+
 /* Debug twin of qoq_w4a8_gemm: same main loop, returns the raw INT32 accumulators acc[M, N]
  * (per-channel: already zero-corrected) instead of scaling them. */
 int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packed,

@@ -38,6 +38,9 @@ _SIGNATURES = {
     "qoq_w4a8_gemm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "qoq_w4a8_gemm_noalloc": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                             ctypes.c_void_p, ctypes.c_void_p]),
     "qoq_w4a8_gemm_i32": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
@@ -221,6 +224,17 @@ def w4a8_gemm(qx, sx, packed, N, mode=QOQ_GROUP128, rowsum=None, out=None, works
     workspace, ws_bytes = _workspace(M, N, K, mode, qx.device, workspace)
     _check(lib().qoq_w4a8_gemm(_ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(packed), M, N, K, mode, _ptr(out),
                                _ptr(workspace), ws_bytes, _stream(qx.device)))
+    return out
+
+
+def w4a8_gemm_noalloc(qx, sx, packed, N, out, mode=QOQ_GROUP128, rowsum=None):
+    """qoq_w4a8_gemm_noalloc: the same GEMM with the library's own per-GPU scratch array; `out` [M, N] FP16 is the
+    caller's (nothing is allocated on the way, here or in the library)."""
+    _dev(qx, torch.int8, "qx")
+    _dev(out, torch.float16, "out")
+    M, K = qx.shape
+    _check(lib().qoq_w4a8_gemm_noalloc(_ptr(qx), _ptr(sx), _ptr(rowsum), _ptr(packed), M, N, K, mode, _ptr(out),
+                                       _stream(qx.device)))
     return out
 
 

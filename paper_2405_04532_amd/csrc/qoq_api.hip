@@ -34,12 +34,37 @@ int arch_ok()
     return c == 1;
 }
 
+// ---- scratch of the entry point that allocates nothing ---------------------------------------------------
+// One array per GPU (every device that loads the library holds its own copy at its own address until the
+// process ends): a fixed region of arrival counters, then the partial tiles.  The counter region is the same for
+// every shape, so partial tiles of one call never land where a later call expects counters; the kernels leave
+// every counter they used at zero, and the array starts out zero-filled, so nothing is cleared per call.
+constexpr size_t kScratchCounterBytes = (size_t)256 << 10;
+constexpr size_t kScratchPartBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchCounterBytes + kScratchPartBytes];
+
+// The array's name is a host-side stand-in, not a device address: its address on the CURRENT device is looked up
+// once per device and kept; host code uses only that pointer.
+int scratch_of_current_device(void** out)
+{
+    static std::atomic<void*> ptrs[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return QOQ_ERR_HIP;
+    void* ptr = ptrs[dev].load();
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return QOQ_ERR_HIP;
+        ptrs[dev].store(ptr);
+    }
+    *out = ptr;
+    return QOQ_OK;
+}
+
 int check_shape(int64_t N, int64_t K, int mode) { return qoq::shape_ok(N, K, mode) ? QOQ_OK : QOQ_ERR_SHAPE; }
 
 // x_fp16 != NULL: quantize the activations first (into qx, sx, rowsum) by a launch of the activation kernel.
 int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const void* packed, int64_t M, int64_t N,
                 int64_t K, int mode, void* out16, int32_t* out32, void* ws, size_t ws_bytes, void* stream,
-                const void* x_fp16 = nullptr, const float* tx = nullptr)
+                const void* x_fp16 = nullptr, const float* tx = nullptr, bool static_scratch = false)
 {
     if (check_shape(N, K, mode) != QOQ_OK || M < 0 || M > (1 << 24)) return QOQ_ERR_SHAPE;
     if (M * N >= ((int64_t)1 << 40)) return QOQ_ERR_SHAPE;
@@ -55,7 +80,20 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     if ((uint64_t)M * (uint64_t)K >= ((uint64_t)1 << 32)) return QOQ_ERR_SHAPE;  // 32-bit activation offsets
     if (tile_m <= 71 && (uint64_t)N * (uint64_t)K >= ((uint64_t)1 << 33)) return QOQ_ERR_SHAPE;  // 32-bit weight offsets (4 GiB packed)
     const size_t need = qoq::gemm_workspace_bytes(M, N, K, tile_m, split_k);
-    if (need && (!ws || ws_bytes < need)) return QOQ_ERR_WORKSPACE;
+    size_t parts_offset = 0;
+    if (static_scratch) {
+        // the library's own per-device array instead of a caller's workspace: fixed counter region, then partial tiles
+        const size_t counters = qoq::gemm_counter_bytes(M, N, K, tile_m, split_k);
+        if (counters > kScratchCounterBytes || need - counters > kScratchPartBytes) return QOQ_ERR_WORKSPACE;
+        if (!arch_ok()) return QOQ_ERR_ARCH;
+        if (need) {
+            const int rc = scratch_of_current_device(&ws);
+            if (rc != QOQ_OK) return rc;
+            parts_offset = kScratchCounterBytes;
+        }
+    } else if (need && (!ws || ws_bytes < need)) {
+        return QOQ_ERR_WORKSPACE;
+    }
     if (x_fp16 && !aligned16(x_fp16)) return QOQ_ERR_ALIGN;
     if (!arch_ok()) return QOQ_ERR_ARCH;
     if (x_fp16 &&
@@ -66,7 +104,7 @@ int gemm_common(const int8_t* qx, const void* sx, const int32_t* rowsum, const v
     a.qx = qx; a.sx = sx; a.rowsum = rowsum; a.tx = tx; a.blob = static_cast<const uint8_t*>(packed);
     a.M = M; a.N = N; a.K = K; a.mode = mode;
     a.out_fp16 = out16; a.out_i32 = out32; a.workspace = ws;
-    a.tile_m = tile_m; a.split_k = split_k;
+    a.tile_m = tile_m; a.split_k = split_k; a.parts_offset = parts_offset;
     return qoq::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QOQ_OK : QOQ_ERR_HIP;
 }
 
@@ -356,6 +394,14 @@ int qoq_w4a8_gemm(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum, 
     if (!out_fp16 && M != 0) return QOQ_ERR_NULL;
     return gemm_common(qx, sx_fp16, rowsum, packed, M, N, K, mode, out_fp16, nullptr, workspace, workspace_bytes,
                        stream);
+}
+
+int qoq_w4a8_gemm_noalloc(const int8_t* qx, const void* sx_fp16, const int32_t* rowsum, const void* packed, int64_t M,
+                          int64_t N, int64_t K, int mode, void* out_fp16, void* stream)
+{
+    if (!out_fp16 && M != 0) return QOQ_ERR_NULL;
+    return gemm_common(qx, sx_fp16, rowsum, packed, M, N, K, mode, out_fp16, nullptr, nullptr, 0, stream, nullptr, nullptr,
+                       true);
 }
 
 int qoq_w4a8_gemm_i32(const int8_t* qx, const int32_t* rowsum, const void* packed, int64_t M, int64_t N, int64_t K,

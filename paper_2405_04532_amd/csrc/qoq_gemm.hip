@@ -1841,7 +1841,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s)
         p.gps = (int)((L.G + a.split_k - 1) / a.split_k);
         counters = align256((size_t)mma_tiles(a.M, a.N, a.tile_m) * sizeof(int));
     }
-    p.parts = reinterpret_cast<int4*>(reinterpret_cast<uint8_t*>(a.workspace) + counters);
+    p.parts = reinterpret_cast<int4*>(reinterpret_cast<uint8_t*>(a.workspace) + (a.parts_offset ? a.parts_offset : counters));
     if (a.mode == 0) launch_any<true>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);
     else launch_any<false>(p, a.tile_m, nwg, a.out_fp16 != nullptr, s);
     return hipGetLastError();

@@ -39,6 +39,7 @@ struct GemmArgs {
     void* workspace;         // split-k counters and partial tiles when split_k > 1
     int tile_m;              // 16, 32, 64 (streaming kernels) or 128 ... 131 (compute-bound kernel, four tile shapes)
     int split_k;             // compute-bound kernel: k-slices per tile; streaming kernel: workgroups sharing the unit stream
+    size_t parts_offset = 0; // byte offset of the partial tiles inside the workspace; 0 = directly behind the counters
 };
 // Bytes of arrival counters at the start of the workspace of a (tile_m, split_k) launch (0 if it exchanges nothing).
 size_t gemm_counter_bytes(int64_t M, int64_t N, int64_t K, int tile_m, int split_k);
