@@ -258,10 +258,13 @@ int qoq_kv4_unpack(const void* cache, int64_t B, int64_t Hkv, int64_t S_max, int
  * tile_m: 0 = auto; 16, 32, 64 = streaming kernel with that many tokens per tile; 65 = 64 tokens,
  * two adjacent blocks per workgroup in lockstep (N % 128 == 0; else as 64); 66 = four blocks in lockstep
  * (N % 256 == 0; else as 65); 67, 68 = two blocks in lockstep with 32 / 16 tokens per tile (else as 32 / 16);
- * 128, 129, 130, 131 =
- * compute-bound kernel with tiles of 256 x 256, 128 x 256, 256 x 128, 256 x 192 (tokens x channels).
+ * 69, 70, 71 = activation-stationary kernel with 16 / 32 / 64 tokens per tile (activations resident in registers,
+ * only weights streamed; K beyond what a workgroup holds is cut into slices that meet in the workspace);
+ * 128, 129, 130, 131 = compute-bound kernel with tiles of 256 x 256, 128 x 256, 256 x 128, 256 x 192
+ * (tokens x channels); 132 = 128 x 256 tiles with two workgroups per compute unit.
  * split_k >= 0 (0 = auto): for the compute-bound kernel the number of k-slices per output tile, for the
- * streaming kernel the number of workgroups the stream of work units is dealt to.
+ * streaming kernels the number of workgroups the stream of work units is dealt to (activation-stationary kernels:
+ * workgroups per token tile and k-slice that share the layer's 16-channel fragments).
  * Not part of the hot-call contract: the setting is process-wide (two atomics, no lock), so a thread that changes
  * it while another thread sizes a workspace or launches a GEMM changes that thread's configuration too.  Set it
  * once, before any qoq_gemm_workspace_bytes query whose result is still in use: workspace sizes depend on it, and a

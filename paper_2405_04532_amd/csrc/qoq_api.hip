@@ -170,7 +170,7 @@ int qoq_gemm_workspace_prepare(void* workspace, size_t workspace_bytes, void* st
 
 int qoq_set_gemm_config(int tile_m, int split_k)
 {
-    if (!(tile_m == 0 || tile_m == 16 || tile_m == 32 || tile_m == 64 || (tile_m >= 65 && tile_m <= 71) || (tile_m >= 128 && tile_m <= 131)) || split_k < 0)
+    if (!(tile_m == 0 || tile_m == 16 || tile_m == 32 || tile_m == 64 || (tile_m >= 65 && tile_m <= 71) || (tile_m >= 128 && tile_m <= 132)) || split_k < 0)
         return QOQ_ERR_SHAPE;
     g_forced_tile_m.store(tile_m);
     g_forced_split_k.store(split_k);

@@ -967,27 +967,34 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 // four token fragments of the wave: 3.5 vector instructions per MFMA), at most two LDS reads and at most
 // one copy.  A scheduling barrier after every chunk keeps the compiler from regrouping them.
 //
-// Copies are global->LDS DMA in half-group steps (k = 64): activations in a ring of six slabs, packed
-// weights (whole groups: the 16-byte lane word covers both halves) and metadata in rings of three.  In the
-// middle of half-stage h a wave waits for its own copies of half-stage h+1 and all waves meet: that
-// publishes h+1 and proves h-1 is no longer read, so its slab is refilled with h+5 (weights of group g+2 go
-// out with the even half-stages).  The rest of h overlaps the first LDS reads and the first dequantization
-// of h+1, so the matrix pipe does not drain at the barrier.  grid = (m-tiles * n-tiles, k-slices).
+// Copies are global->LDS DMA.  Activations, packed weights (the 16-byte lane word covers both halves of a group) and
+// metadata live in rings of three group slabs; an activation copy moves eight tokens x 128 k, i.e. whole cache
+// lines.  The main loop works in half-group steps (k = 64); every half-stage's operands are read into registers
+// during the half-stage before.  There is one barrier per group, in the middle of its second half-stage: a wave
+// first waits for its own copies of group g+1, all waves meet (that publishes g+1 and proves group g's slabs are
+// no longer read), and the slabs of group g are refilled with group g+3 -- four half-stages of lead.  The rest of
+// the half-stage overlaps the first LDS reads and the first dequantization of g+1, so the matrix pipe does not
+// drain at the barrier.  grid = (m-tiles * n-tiles, k-slices).
 // ------------------------------------------------------------------------------------------
 typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kMmaThreads = 256;
-constexpr int kASlots = 6;                          // activation slabs: (tokens of the tile) x 64 k per half-stage
-constexpr int kWSlots = 3;                          // weight slabs: (channels of the tile) x 128 k, 1 KiB per 16 channels
+// Ring depth (template parameter DEPTH): slabs of one quantization group each -- activations (tokens of the tile x
+// 128 k), weights (channels of the tile x 128 k, 1 KiB per 16 channels), metadata.  3 = one workgroup per compute
+// unit that hides the memory latency by its own lead of two groups; 2 = rings small enough for two workgroups per
+// compute unit (two waves per SIMD: while one waits for its copies or at its barrier, the other one's matrix
+// instructions keep the pipe busy).
 constexpr int kMSlotBytes = 1024;                   // metadata: 256 B per copying wave
 
-template <bool GROUP, int OUT, int CF, int WM>
-__global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
+template <bool GROUP, int OUT, int CF, int WM, int DEPTH>
+__global__ __launch_bounds__(kMmaThreads, DEPTH == 2 ? 2 : 1) void mma_kernel(GemmDev p)
 {
+    static_assert(DEPTH == 2 || DEPTH == 3, "ring depth");
+    constexpr int kASlots = DEPTH, kWSlots = DEPTH;
     constexpr int WN = 4 / WM;                      // waves along the channels
     constexpr int TMt = 128 * WM, TNt = 32 * CF * WN;   // tile: tokens x channels
     constexpr int kABlocks = TMt / 16;              // 1 KiB blocks (16 tokens x 64 k) per activation slab
     constexpr int kUnits = TNt / 16;                // 1 KiB weight units per slab
-    constexpr int kASlotBytes = kABlocks * 1024, kWSlotBytes = kUnits * 1024;
+    constexpr int kASlotBytes = 2 * kABlocks * 1024, kWSlotBytes = kUnits * 1024;   // a group of a tile: 128 B per token
     constexpr int kACopies = kABlocks / 4, kWCopies = kUnits / 4;     // per wave
     constexpr int NB = 2 * CF;                      // blocks (k32-step jj, channel fragment cf) per half-stage
     constexpr int NC = 4 * NB;                      // chunks per half-stage
@@ -1027,27 +1034,33 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     const int nf_base = tn * kUnits;                     // first 16-row fragment (unit row) of the tile
     const int nf_total = p.N / 16;
 
-    // ---- copy role: wave w copies token blocks kACopies*w.., weight units kWCopies*w.. and their metadata.
-    // Activation block = (16-token fragment, 64-wide half-stage): lane 4r+c copies 16-byte chunk
-    // c ^ h(r) of token r, so a quad reads one 64-byte row segment and fragment reads are conflict free.
-    constexpr int kOdd = kACopies, kEven = kACopies + kWCopies + (GROUP ? 1 : 0);   // copies per wave after an odd / even half-stage's barrier
-    static_assert(2 * kOdd + kEven < 64, "vmcnt range");
-    uint32_t a_voff[kACopies];
+    // ---- copy role: wave w copies a quarter of the tile's tokens, weight units kWCopies*w.. and their metadata.
+    // One activation copy = eight tokens x one whole quantization group: every eight lanes fetch one whole 128-byte
+    // line (the vector cache works in whole lines: 16 tokens x 64 bytes per copy, half a line each, was measured to
+    // cost it twice the requests for the same bytes).  Lane 8r+c fetches 16-byte chunk c ^ row_swizzle(r) of token
+    // row r, which keeps the fragment reads free of bank conflicts.  The
+    // copies of a group are issued in two halves, after the barriers of two consecutive half-stages.
+    constexpr int kAll = 2 * kACopies + kWCopies + (GROUP ? 1 : 0);   // copies per wave and group
+    static_assert((DEPTH - 1) * kAll < 64, "vmcnt range");
+    static_assert(kAll <= NC - BAR, "one copy per chunk after the barrier");
+    static_assert(kACopies % 2 == 0, "copy t of either half starts at row 8 * (t & 1) modulo 16");
+    uint32_t a_voff[2][kACopies];                      // [half of the group's copies][copy]
     {
-        const int r = lane >> 2, c = lane & 3;
-        const int h = ((r >> 1) ^ (r >> 2)) & 3;
+        const int r = lane >> 3, c = lane & 7;
 #pragma unroll
-        for (int t = 0; t < kACopies; ++t) {
-            const int row = min(m_base + (wave * kACopies + t) * 16 + r, p.M - 1);   // rows past M repeat the last one
-            a_voff[t] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((c ^ h) * 16);
-        }
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int t = 0; t < kACopies; ++t) {
+                const int row = min(m_base + ((wave * 2 + hf) * kACopies + t) * 8 + r, p.M - 1);   // rows past M repeat the last one
+                a_voff[hf][t] = (uint32_t)row * (uint32_t)p.K + (uint32_t)((c ^ row_swizzle(((t & 1) << 3) | r)) * 16);   // (a wave's copies start at a multiple of 16 rows)
+            }
     }
     const uint32_t w_voff = (uint32_t)lane * 16u;
     // metadata: 32 B per unit; lane l copies dword l % 8 of the wave's unit l / 8 (units past N repeat the last one,
     // lanes past the wave's units repeat its last dword)
     const int m_lane = min(lane, kWCopies * 8 - 1);
     const uint32_t m_voff = (uint32_t)min(nf_base + wave * kWCopies + (m_lane >> 3), nf_total - 1) * 32u + (uint32_t)(m_lane & 7) * 4u;
-    const uint32_t a_dst = (uint32_t)(uintptr_t)&aring[0] + (uint32_t)(wave * kACopies) * 1024u;
+    const uint32_t a_dst = (uint32_t)(uintptr_t)&aring[0] + (uint32_t)(wave * 2 * kACopies) * 1024u;
     const uint32_t w_dst = (uint32_t)(uintptr_t)&wring[0] + (uint32_t)(wave * kWCopies) * 1024u;
     const uint32_t m_dst = (uint32_t)(uintptr_t)&mring[0] + (uint32_t)wave * 256u;
     const char* abase = reinterpret_cast<const char*>(p.qx);
@@ -1057,18 +1070,20 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         wrow[u] = reinterpret_cast<const char*>(p.codes) + (size_t)min(nf_base + wave * kWCopies + u, nf_total - 1) * G * 1024;
     const char* mrow = reinterpret_cast<const char*>(p.meta);
     const size_t m_g_stride = (size_t)nf_total * 32;
-    int ca = 2 * g_first, cw = g_first;   // next half-stage / group to copy; past the end of the slice the last one is copied again into a free slab
-    const int ca_last = 2 * (g_first + Gs) - 1, cw_last = g_first + Gs - 1;
-    auto copy_a = [&](int t, int slot) { dma16(abase + (size_t)ca * 64, a_voff[t], a_dst + (uint32_t)(slot * kASlotBytes + t * 1024)); };
+    int ca = g_first, cw = g_first;   // next group of activations / weights to copy; past the end of the slice the last one is copied again into a free slab
+    const int cw_last = g_first + Gs - 1;
+    auto copy_a = [&](int t, int hf, int slot) {
+        dma16(abase + (size_t)ca * kGroup, a_voff[hf][t], a_dst + (uint32_t)(slot * kASlotBytes + (hf * kACopies + t) * 1024));
+    };
     auto copy_w = [&](int u, int slot) { dma16(wrow[u] + (size_t)cw * 1024, w_voff, w_dst + (uint32_t)(slot * kWSlotBytes + u * 1024)); };
     auto copy_m = [&](int slot) { if (GROUP) dma4(mrow + (size_t)cw * m_g_stride, m_voff, m_dst + (uint32_t)(slot * kMSlotBytes)); };
-    auto adv_a = [&]() { ca = min(ca + 1, ca_last); };
+    auto adv_a = [&]() { ca = min(ca + 1, cw_last); };
     auto adv_w = [&]() { cw = min(cw + 1, cw_last); };
-    // k-th copy a wave issues after the barrier of an even (s == 0) or odd half-stage
-    auto refill = [&](int k, int s, int a_islot, int w_islot) {
-        if (k < kACopies) copy_a(k, a_islot);
-        else if (s == 0 && k < kACopies + kWCopies) copy_w(k - kACopies, w_islot);
-        else if (s == 0 && k == kACopies + kWCopies) copy_m(w_islot);
+    // k-th copy a wave issues after a group's barrier: the next group but two, into the slabs the barrier has freed
+    auto refill = [&](int k, int islot) {
+        if (k < 2 * kACopies) copy_a(k % kACopies, k / kACopies, islot);
+        else if (k < 2 * kACopies + kWCopies) copy_w(k - 2 * kACopies, islot);
+        else if (k == 2 * kACopies + kWCopies) copy_m(islot);
     };
 
     // Epilogue constants of the tile (token scales, channel scales; per-channel mode: token sums, zero points)
@@ -1095,18 +1110,13 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         }
     }
 
-    // prologue: half-stages 0..4, groups 0..1, in the order of the steady state (odd, even, odd, even, odd)
+    // prologue: the first DEPTH groups, each in the order of the steady state
 #pragma unroll
-    for (int hh = 0; hh < 5; ++hh) {
+    for (int gg = 0; gg < DEPTH; ++gg) {
 #pragma unroll
-        for (int t = 0; t < kACopies; ++t) copy_a(t, hh);
+        for (int k = 0; k < kAll; ++k) refill(k, gg);
         adv_a();
-        if (hh & 1) {
-#pragma unroll
-            for (int u = 0; u < kWCopies; ++u) copy_w(u, hh >> 1);
-            copy_m(hh >> 1);
-            adv_w();
-        }
+        adv_w();
     }
 
     // ---- compute role ---------------------------------------------------------------------------
@@ -1122,14 +1132,14 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
     // LDS byte offsets of this lane's operands inside a slab.
-    //   activations, token fragment tf (+ tf * 2048), k32-step jj of the half-stage: token wm*128 + tf*32 + r32
-    //   -> block token/16, row token%16, 16-byte chunk (2jj + kb2) ^ h(row)
-    const int arow = r32 & 15;
-    const int ah = ((arow >> 1) ^ (arow >> 2)) & 3;
-    uint32_t a_rd[2], w_rd[2];
+    //   activations, token fragment tf (+ tf * 4096), half hf of the group, k32-step jj of that half: token
+    //   wm*128 + tf*32 + r32 -> row of 128 bytes, 16-byte chunk (4hf + 2jj + kb2) ^ row_swizzle(token % 16)
+    uint32_t a_rd[2][2], w_rd[2];
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
-        a_rd[jj] = (uint32_t)((wm * 8 + (r32 >> 4)) * 1024 + (4 * arow + (((2 * jj + kb2) & 3) ^ ah)) * 16);
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+            a_rd[hf][jj] = (uint32_t)((wm * 128 + r32) * 128 + (((4 * hf + 2 * jj + kb2) ^ row_swizzle(r32 & 15)) * 16));
         //   weights, channel fragment cf (+ cf * 2048; 32 rows = units 2cf, 2cf+1), both halves in one lane word:
         //   unit 2 * (frag0 + cf * kFragStep) + r32/16, lane word ((2jj + kb2) % 4) * 16 + r32 % 16
         w_rd[jj] = (uint32_t)((2 * frag0 + (r32 >> 4)) * 1024 + ((((2 * jj + kb2) & 3) * 16) + (r32 & 15)) * 16);
@@ -1142,8 +1152,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         m_rd[cf] = (uint32_t)((u / kWCopies) * 256 + ((u % kWCopies) * 16 + (r32 & 15)) * 2);
     }
 
-    auto lds_a = [&](uint32_t slab, int jj, int tf) {
-        return as_v4i(*reinterpret_cast<const uint4*>(aring + slab + a_rd[jj] + tf * 2048));
+    auto lds_a = [&](uint32_t slab, int hf, int jj, int tf) {
+        return as_v4i(*reinterpret_cast<const uint4*>(aring + slab + a_rd[hf][jj] + tf * 4096));
     };
     auto lds_w = [&](uint32_t slab, int blk) {           // lane word (both halves) of block blk = (jj, cf)
         return *reinterpret_cast<const uint4*>(wring + slab + w_rd[blk / CF] + (blk % CF) * (2048 * kFragStep));
@@ -1182,8 +1192,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
         }
     };
 
-    // first barrier: half-stage 0 and group 0 have landed everywhere
-    wait_vmcnt<2 * kOdd + kEven>();
+    // first barrier: group 0 has landed everywhere
+    wait_vmcnt<(DEPTH - 1) * kAll>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     uint32_t S[CF], B[CF], mt[CF];
@@ -1206,27 +1216,29 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
     for (int i = 0; i < NB; ++i) rq[i] = (CF == 2 || i < NB / 2) ? lds_w(0, i) : make_uint4(0, 0, 0, 0);
     v4i a0[4], a1[2][4];
 #pragma unroll
-    for (int tf = 0; tf < 4; ++tf) { a0[tf] = lds_a(0, 0, tf); a1[0][tf] = lds_a(0, 1, tf); a1[1][tf] = (v4i){0, 0, 0, 0}; }
+    for (int tf = 0; tf < 4; ++tf) { a0[tf] = lds_a(0, 0, 0, tf); a1[0][tf] = lds_a(0, 0, 1, tf); a1[1][tf] = (v4i){0, 0, 0, 0}; }
     v4i w_cur = {deq1(rq[0], 0, 0, S[0], B[0]), deq1(rq[0], 0, 1, S[0], B[0]), deq1(rq[0], 0, 2, S[0], B[0]), deq1(rq[0], 0, 3, S[0], B[0])};
     v4i w_nxt = {0, 0, 0, 0};
     uint32_t dq[4] = {0, 0, 0, 0};
     deq_phase(0, rq[1], 0, S[1 % CF], B[1 % CF], dq, w_nxt);   // block 1 is one phase ahead, as in the steady state
 
-    int gs = 0;                                          // g % 3
+    int gs = 0;                                          // g % DEPTH
     for (int g = 0; g < Gs; ++g) {
-        const int gp1 = gs == 2 ? 0 : gs + 1, gm1 = gs == 0 ? 2 : gs - 1;
+        const int gp1 = gs == DEPTH - 1 ? 0 : gs + 1;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {                    // half-stage h = 2g + s
-            const uint32_t a_nxt = (uint32_t)((s == 0 ? 2 * gs + 1 : 2 * gp1) * kASlotBytes);
+            const uint32_t a_nxt = (uint32_t)((s == 0 ? gs : gp1) * kASlotBytes);   // slab of the next half-stage: half 1 - s of this / the next group
             const uint32_t w_this = (uint32_t)(gs * kWSlotBytes), w_next = (uint32_t)(gp1 * kWSlotBytes);
             const uint32_t m_nxt = (uint32_t)(gp1 * kMSlotBytes);
-            const int a_islot = s == 0 ? 2 * gm1 + 1 : 2 * gs;   // slab of half-stage h-1 = (h+5) % 6
-            const int w_islot = gm1;                             // slab of group g-1 = (g+2) % 3
 #pragma unroll
             for (int c = 0; c < NC; ++c) {               // chunk = (block b = (jj, cf), token fragment tf)
                 const int b = c >> 2, tf = c & 3, jj = b / CF, cf = b % CF;
-                if (c == BAR) {
-                    if (s == 0) wait_vmcnt<2 * kOdd + kEven>(); else wait_vmcnt<kOdd + kEven>();
+                if (c == BAR && s == 1) {
+                    // One barrier per group, in its second half-stage.  Before it a wave waits for its own copies of
+                    // group g+1 (those of g+2 may be in flight) and for its outstanding LDS reads; all waves meeting
+                    // publishes group g+1 and proves that nobody reads group g's slabs any more (its second k-half
+                    // went to registers during the first half-stage): they are refilled with group g+DEPTH.
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"((DEPTH - 2) * kAll) : "memory");
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
                 }
@@ -1246,8 +1258,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                     }
                     if (b >= 4 && (tf & 1)) {            // activations of the next half-stage, two fragments per block
                         const int q = (b & 1) * 2 + (tf >> 1);
-                        if (b < 6) a0[q] = lds_a(a_nxt, 0, q);
-                        else a1[1 - s][q] = lds_a(a_nxt, 1, q);
+                        if (b < 6) a0[q] = lds_a(a_nxt, 1 - s, 0, q);
+                        else a1[1 - s][q] = lds_a(a_nxt, 1 - s, 1, q);
                     }
                     if (GROUP && s == 1) {               // level-2 constants of the next group, each after the last use of the old one
                         if (b == 4) mt[tf] = lds_m(m_nxt, tf);
@@ -1267,8 +1279,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                         if (s == 0 && b < 3) rq[b + 3] = lds_w(w_this, b + 3);
                         if (s == 1 && b >= 3) rq[b - 3] = lds_w(w_next, b - 3);
                     }
-                    if (c >= 12 && c <= 15) a0[c - 12] = lds_a(a_nxt, 0, c - 12);
-                    if (c >= 16 && c <= 19) a1[1 - s][c - 16] = lds_a(a_nxt, 1, c - 16);
+                    if (c >= 12 && c <= 15) a0[c - 12] = lds_a(a_nxt, 1 - s, 0, c - 12);
+                    if (c >= 16 && c <= 19) a1[1 - s][c - 16] = lds_a(a_nxt, 1 - s, 1, c - 16);
                     if (GROUP && s == 1) {
                         if (b == 3 && tf < 3) mt[tf] = lds_m(m_nxt, tf);
                         const int pc = c == 16 ? 0 : c == 18 ? 1 : c == 20 ? 2 : -1;
@@ -1282,8 +1294,8 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                         const int e = c == 4 ? 0 : c == 5 ? 1 : c == 8 ? 2 : c == 12 ? 3 : -1;
                         if (e >= 0) rq[e] = lds_w(w_next, e);
                     }
-                    if (c >= 5 && c <= 8) a0[c - 5] = lds_a(a_nxt, 0, c - 5);          // a0[q] is last used in chunk 4 + q
-                    if (c >= 9 && c <= 12) a1[1 - s][c - 9] = lds_a(a_nxt, 1, c - 9);
+                    if (c >= 5 && c <= 8) a0[c - 5] = lds_a(a_nxt, 1 - s, 0, c - 5);          // a0[q] is last used in chunk 4 + q
+                    if (c >= 9 && c <= 12) a1[1 - s][c - 9] = lds_a(a_nxt, 1 - s, 1, c - 9);
                     if (GROUP && s == 1) {
                         if (c == 4) mt[0] = lds_m(m_nxt, 0);
                         if (c == 6) mt[1] = lds_m(m_nxt, 1);
@@ -1294,12 +1306,11 @@ __global__ __launch_bounds__(kMmaThreads) void mma_kernel(GemmDev p)
                         }
                     }
                 }
-                if (c >= BAR) refill(c - BAR, s, a_islot, w_islot);   // refill the slabs the barrier has just freed
+                if (s == 1 && c >= BAR) refill(c - BAR, gs);   // refill the slabs the barrier has just freed
                 __builtin_amdgcn_sched_barrier(0);
             }
             w_cur = w_nxt;
-            adv_a();
-            if (s == 0) adv_w();
+            if (s == 1) { adv_a(); adv_w(); }
         }
         gs = gp1;
     }
@@ -1487,13 +1498,13 @@ void launch_stream(const GemmDev& p, bool fp16, dim3 grid, hipStream_t s)
     }
 }
 
-template <bool GROUP, int CF, int WM>
+template <bool GROUP, int CF, int WM, int DEPTH = 3>
 void launch_mma(const GemmDev& p, bool fp16, hipStream_t s)
 {
     constexpr int TMt = 128 * WM, TNt = 32 * CF * (4 / WM);
     const dim3 grid((unsigned)(((p.N + TNt - 1) / TNt) * ((p.M + TMt - 1) / TMt)), (unsigned)p.S);
-    if (fp16) mma_kernel<GROUP, OUT_FP16, CF, WM><<<grid, kMmaThreads, 0, s>>>(p);
-    else mma_kernel<GROUP, OUT_I32, CF, WM><<<grid, kMmaThreads, 0, s>>>(p);
+    if (fp16) mma_kernel<GROUP, OUT_FP16, CF, WM, DEPTH><<<grid, kMmaThreads, 0, s>>>(p);
+    else mma_kernel<GROUP, OUT_I32, CF, WM, DEPTH><<<grid, kMmaThreads, 0, s>>>(p);
 }
 
 // tile_m selects the kernel and its shape: 16 / 32 / 64 = streaming kernel with that many tokens per tile;
@@ -1531,6 +1542,9 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
         launch_mma<GROUP, 2, 2>(p, fp16, s);
     } else if (tile_m == 131) {
         launch_mma<GROUP, 3, 2>(p, fp16, s);
+    } else if (tile_m == 132) {
+        launch_mma<GROUP, 2, 1, 2>(p, fp16, s);
+
     } else {
         launch_mma<GROUP, 4, 2>(p, fp16, s);
     }
@@ -1544,7 +1558,7 @@ void launch_any(const GemmDev& p, int tile_m, int nwg, bool fp16, hipStream_t s)
 // workgroups the unit stream is dealt to (per token tile); compute-bound kernel = k-slices per tile.
 static void mma_tile_shape(int tile_m, int64_t& tm, int64_t& tn)
 {
-    tm = tile_m == 129 ? 128 : 256;
+    tm = (tile_m == 129 || tile_m == 132) ? 128 : 256;
     tn = tile_m == 130 ? 128 : tile_m == 131 ? 192 : 256;
 }
 static int64_t mma_tiles(int64_t M, int64_t N, int tile_m)
@@ -1574,6 +1588,14 @@ static double mma_cost(int64_t M, int64_t N, int64_t G, int tile_m, int& S)
 {
     S = mma_split(M, N, G, tile_m, 0);
     const int64_t wgs = mma_tiles(M, N, tile_m) * S;
+    if (tile_m == 132) {
+        // two workgroups per compute unit (128 x 256 tiles, shallower rings): worth it only when the compute units
+        // really get two each; a pair then takes about 1.85 times one workgroup's time per group at full load
+        if (S > 1 || wgs < 384) return 1e30;
+        const int64_t rounds2 = (wgs + 511) / 512;
+        const double load2 = (double)wgs / (double)(rounds2 * 512);
+        return (double)rounds2 * (8.0 + 1.14 * (1.0 + 0.45 * load2 * load2) * (double)G);
+    }
     const int64_t rounds = (wgs + 255) / 256;
     const double load = (double)wgs / (double)(rounds * 256);
     const double light = tile_m == 128 ? 1.18 : tile_m == 131 ? 0.92 : tile_m == 130 ? 0.64 : 0.62;
@@ -1738,7 +1760,7 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
         // kernels (they re-read the weights once per token tile but spread K over the whole chip).
         int S;
         double best = mma_cost(M, N, G, 128, S);
-        for (int cand = 129; cand <= 131; ++cand) {
+        for (int cand = 129; cand <= 132; ++cand) {
             const double c = mma_cost(M, N, G, cand, S);
             if (c < 0.98 * best) { best = c; tile_m = cand; }
         }

@@ -94,8 +94,7 @@ __global__ __launch_bounds__(kAsThreads) void astat_kernel(GemmDev p)
     // instruction) and was measured three times slower than reading whole lines, so the slab goes through LDS:
     // chunks of 16 tokens x 32 groups are copied by global->LDS DMA, 1 KiB of one token row per instruction (eight
     // whole 128-byte lines), double buffered, and every wave then reads its operands from LDS.  Inside a row the
-    // 16-byte chunks are stored XORed with (row & 7), so that the eight lanes the LDS serves together (eight rows,
-    // same chunk) hit different banks.
+    // 16-byte chunks are stored XORed with row_swizzle(row), which keeps the operand reads free of bank conflicts.
     v4i a[J][MF][2];
 #pragma unroll
     for (int j = 0; j < J; ++j)
@@ -119,36 +118,39 @@ __global__ __launch_bounds__(kAsThreads) void astat_kernel(GemmDev p)
                 const int r = (2 * wave + (i >> 2) + rot_r) & 15, part = ((i & 3) + rot_p) & 3;
                 const uint32_t row = (uint32_t)min(m0 + mf * 16 + r, p.M - 1);      // rows past M repeat the last one
                 const uint32_t col = min((uint32_t)(g_lo + 32 * kc) * (uint32_t)kGroup + (uint32_t)part * 1024u +
-                                             (uint32_t)((lane ^ (r & 7)) * 16),
+                                             (uint32_t)((lane ^ row_swizzle(r)) * 16),
                                          (uint32_t)p.K - 16u);                        // parts past the row re-read its end
                 dma16(abase, row * (uint32_t)p.K + col, dst + (uint32_t)(r * 4096 + part * 1024));
             }
         };
-        // Order of the requests: two chunks of activations, then the first R fragments of weights, then the other
-        // chunks as the staging buffers come free.  Data returns in request order, so the weights, which take a trip
-        // to memory, must not stand in front of the first chunks; behind them their latency passes while the
-        // chunks are unpacked.  The waits below count what was requested after the chunk being waited for:
-        // kNW weight loads (build.py checks that the compiler emits exactly that many) and 8 copies per chunk.
+        // Order of the requests: two chunks of activations; then, once every wave's copies of the first chunk have
+        // landed, the first R fragments of weights; then the other chunks as the staging buffers come free.  Data
+        // returns to a compute unit in request order, whichever wave asked, so no wave's weights (a trip to memory)
+        // may stand in front of another wave's first chunks; behind them their latency passes while the chunks are
+        // unpacked.  The waits below count what this wave requested after the chunk it waits for: kNW weight
+        // loads (build.py checks that the compiler emits exactly that many) and 8 copies per chunk.
         constexpr int kNW = R * J * (GROUP ? 2 : 1);
         static_assert(kNW + 8 < 64, "vmcnt range");
         issue_chunk(0);
         if (T > 1) issue_chunk(1);
-        asm volatile("; astat weight prologue begin" ::: "memory");
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int j = 0; j < J; ++j) load_unit(r * J + j, j, f0 + min(r, nfr - 1));
-        asm volatile("; astat weight prologue end" ::: "memory");
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf) {
             for (int kc = 0; kc < KC; ++kc) {
                 const int t = mf * KC + kc;
                 // this wave's copies of chunk t have landed
-                if (t == 0) { if (T > 1) wait_vmcnt<kNW + 8>(); else wait_vmcnt<kNW>(); }
+                if (t == 0) { if (T > 1) wait_vmcnt<8>(); else wait_vmcnt<0>(); }
                 else if (t == 1) { if (T > 2) wait_vmcnt<kNW + 8>(); else wait_vmcnt<kNW>(); }
                 else if (t + 1 < T) wait_vmcnt<8>();
                 else wait_vmcnt<0>();
                 __syncthreads();                                         // ... and everyone else's
+                if (mf == 0 && kc == 0) {
+                    asm volatile("; astat weight prologue begin" ::: "memory");
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int j = 0; j < J; ++j) load_unit(r * J + j, j, f0 + min(r, nfr - 1));
+                    asm volatile("; astat weight prologue end" ::: "memory");
+                }
                 const char* src = lds_raw + (t & 1) * kStageBytes + ml * 4096;
 #pragma unroll
                 for (int j = 0; j < J; ++j) {
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(kAsThreads) void astat_kernel(GemmDev p)
                     if (slot_valid(j) && (g >> 5) == kc) {
 #pragma unroll
                         for (int ks = 0; ks < 2; ++ks)
-                            a[j][mf][ks] = *reinterpret_cast<const v4i*>(src + (g & 31) * kGroup + (((ks * 4 + q) ^ (ml & 7)) * 16));
+                            a[j][mf][ks] = *reinterpret_cast<const v4i*>(src + (g & 31) * kGroup + (((ks * 4 + q) ^ row_swizzle(ml)) * 16));
                     }
                 }
                 __syncthreads();                                         // the buffer may be overwritten

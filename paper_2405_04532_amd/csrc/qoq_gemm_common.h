@@ -87,6 +87,13 @@ __device__ __forceinline__ void wait_vmcnt()
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
+// Bank swizzle of activation rows kept in LDS as whole 128-byte lines (eight 16-byte chunks per token row): chunk c
+// of row r is stored at chunk position c ^ row_swizzle(r).  The LDS of gfx950 has 64 banks of 4 bytes and serves
+// a 16-byte fragment read 16 lanes at a time; those lanes take the same chunk of 16 consecutive rows, i.e. 8 even
+// rows (first half of the banks) and 8 odd ones (second half), and (r >> 1) & 7 gives each of the eight a different
+// position.  (Measured: swizzles that only use r & 7 leave two-way conflicts on every such read.)
+__device__ __forceinline__ int row_swizzle(int r) { return (r >> 1) & 7; }   // r = row % 16
+
 // Compiler-visible write-through store / cache-bypassing load (two relaxed device-scope 8-byte atomics each): the
 // compiler tracks their registers and waits itself.  For code with no copy queue to preserve, and wherever
 // control flow lies between a load and its use (the compiler may copy a register it believes already loaded).

@@ -107,7 +107,7 @@ def test_launch_plan_host_logic(api):
         for K in (128, 1152, 4096, 11008, 28672):
             for M in (1, 7, 16, 17, 32, 33, 64, 65, 100, 128, 200, 256, 512, 1024, 4096):
                 tile, split = api.query_gemm_config(M, N, K)
-                assert tile in (16, 32, 64, 65, 66, 67, 68, 69, 70, 71, 128, 129, 130, 131) and split >= 1, (M, N, K, tile, split)
+                assert tile in (16, 32, 64, 65, 66, 67, 68, 69, 70, 71, 128, 129, 130, 131, 132) and split >= 1, (M, N, K, tile, split)
                 units = (N // 64) * (K // 128)
                 if tile in (69, 70, 71):
                     assert split <= min(256, N // 16)

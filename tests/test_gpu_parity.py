@@ -201,7 +201,7 @@ def test_group_ragged_m(api, M):
 
 @pytest.mark.parametrize("tile_m,split_k", [(16, 1), (32, 1), (64, 1), (128, 1), (16, 3), (64, 5), (128, 2), (32, 9),
                                             (64, 2), (128, 9), (129, 1), (130, 1), (129, 3), (130, 2), (129, 9), (130, 4),
-                                            (131, 1), (131, 2), (131, 5)])
+                                            (131, 1), (131, 2), (131, 5), (132, 1), (132, 2), (132, 9)])
 def test_group_forced_variants(api, tile_m, split_k):
     run_group_case(api, 150, 576, 1152, seed=7, tile_m=tile_m, split_k=split_k)
 
@@ -313,7 +313,7 @@ def test_group_several_tiles_all_axes(api):
     run_group_case(api, 300, 1088, 2048, seed=11)
 
 
-@pytest.mark.parametrize("tile_m,split_k", [(128, 1), (129, 1), (130, 1), (129, 2), (130, 3), (131, 1), (131, 2)])
+@pytest.mark.parametrize("tile_m,split_k", [(128, 1), (129, 1), (130, 1), (129, 2), (130, 3), (131, 1), (131, 2), (132, 1), (132, 3)])
 def test_group_compute_kernel_shapes_ragged(api, tile_m, split_k):
     """Every tile shape of the compute-bound kernel on a problem ragged in tokens and channels (M % 128 != 0,
     N % 128 != 0) with several tiles on both axes and, with a split, odd slice lengths (17 groups)."""
