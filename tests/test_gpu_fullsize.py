@@ -9,7 +9,12 @@ token row (cheap) and only the sampled weight rows, and must agree
   * bit for bit on the INT32 accumulators of (all tokens) x (sampled channels),
   * within 1e-3 relative (+2^-24 absolute, the FP16 subnormal step) on the FP16 outputs.
 Sampled channels always include the first and last channel, both sides of a 256-channel tile
-boundary, and seeded picks elsewhere, so every corner of the tiling is touched.
+boundary, seeded picks elsewhere and, derived from the launch configuration the library reports for the shape,
+a channel of every block that two workgroups share, of the first and last block (pair, quad, fragment) of every
+workgroup, and the first and last channel of every tile of the compute-bound kernel.
+
+The decode configurations themselves (every Llama-2-7B layer and every per-channel Llama-3-8B layer at M = 64) are
+also compared as WHOLE tensors: every packed code, scale and zero, every INT32 accumulator, every FP16 output.
 """
 import numpy as np
 import pytest
@@ -33,6 +38,99 @@ def _sample_channels(N, count, seed):
     return np.array(picks, dtype=np.int64)
 
 
+def _partition_channels(M, N, K, mode, rng):
+    """Channels that sit where the launch configuration of this shape cuts the work: see the module docstring."""
+    tile, split = api.query_gemm_config(M, N, K, mode)
+    G = K // 128
+    picks = set()
+
+    def block(b, width=64):                      # two channels of the `width`-channel set b
+        lo = min(b * width, N - width)
+        picks.update(int(v) for v in lo + rng.choice(width, size=2, replace=False))
+
+    if tile in (16, 32, 64):                     # units = (64-channel block, group), dealt in runs of upw
+        units = (N // 64) * G
+        upw = -(-units // split)
+        for k in range(split + 1):
+            for u in (k * upw - 1, k * upw):
+                if 0 <= u < units:
+                    block(u // G)
+    elif tile in (65, 66, 67, 68):               # whole pairs / quads of blocks per workgroup
+        width = 256 if tile == 66 else 128
+        sets = N // width
+        per = -(-sets // split)
+        for k in range(split + 1):
+            for sset in (k * per - 1, k * per):
+                if 0 <= sset < sets:
+                    block(sset, width)
+    elif tile in (69, 70, 71):                   # 16-channel fragments in runs of unequal length
+        frags = N // 16
+        base, rem = divmod(frags, split)
+        f = 0
+        for k in range(split):
+            n = base + (1 if k < rem else 0)
+            for frag in (f, f + n - 1):
+                if 0 <= frag < frags and n > 0:
+                    picks.add((frag >> 2) * 64 + 16 * int(rng.integers(4)) + 4 * (frag & 3) + int(rng.integers(4)))
+            f += n
+    else:                                        # compute-bound kernel: first and last channel of every tile
+        tn = {128: 256, 129: 256, 130: 128, 131: 192, 132: 256}[tile]
+        for n0 in range(0, N, tn):
+            picks.update((n0, min(N, n0 + tn) - 1))
+    return picks
+
+
+def _check_whole_layer(family, layer, M, mode, base_seed, launches=1):
+    """Every element of one layer at M tokens against the oracle; `launches` > 1 repeats the GEMM and demands
+    identical accumulators every time (the partial tiles of shared blocks cross workgroups without fences)."""
+    from oracle import gemm as ogemm
+    from oracle import qoq_quant as qq
+
+    dev = "cuda:0"
+    K, N = FAMILIES[family][layer]
+    print(f"[whole tensor] {family}/{layer} K={K} N={N} M={M} mode={mode} cfg={api.query_gemm_config(M, N, K, mode)}", flush=True)
+    w = wl.layer_weights(family, layer, base_seed, dev)
+    blob = api.pack_weights(w, mode)
+    q, s1, z, s = api.unpack_weights(blob, N, K, mode)
+    q, z, s = q.cpu().numpy(), z.cpu().numpy(), s.cpu().numpy()
+    s1 = s1.cpu().numpy() if s1 is not None else None
+    w_np = w.cpu().numpy()
+    del w
+    operand = np.empty((N, K), dtype=np.int8)
+    scale = np.empty(N, dtype=np.float16)
+    zc = np.empty(N, dtype=np.int64)
+    for r0 in range(0, N, 1024):                 # the oracle's quantizers, 1024 channels at a time
+        r1 = min(N, r0 + 1024)
+        if mode == api.QOQ_GROUP128:
+            wq = qq.progressive_quant(w_np[r0:r1])
+            assert np.array_equal(q[r0:r1], wq["Q"]) and np.array_equal(s1[r0:r1], wq["s1"]) and np.array_equal(z[r0:r1], wq["z"])
+            operand[r0:r1], scale[r0:r1] = wq["w_hat"], wq["s0"]
+        else:
+            code, zz, sw = qq.per_channel_quant(w_np[r0:r1])
+            assert np.array_equal(q[r0:r1], code) and np.array_equal(z[r0:r1], zz)
+            operand[r0:r1], scale[r0:r1], zc[r0:r1] = code, sw, zz
+    assert np.array_equal(s.view(np.uint16), scale.view(np.uint16))
+    del q, s1, z, s, w_np
+
+    x = wl.layer_activations(family, layer, M, base_seed, dev)
+    qx, sx, rowsum, _ = api.quant_act_per_token(x)
+    oqx, osx, orowsum, _ = qq.act_quant(x.cpu().numpy())
+    assert np.array_equal(qx.cpu().numpy(), oqx) and np.array_equal(rowsum.cpu().numpy(), orowsum)
+    ref = ogemm.gemm_i64(oqx, operand)
+    if mode == api.QOQ_PER_CHANNEL:
+        ref = qq.per_channel_acc(ref, zc, orowsum)
+    assert np.abs(ref).max(initial=0) < 2 ** 31
+    ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, mode), dev)
+    for it in range(launches):
+        acc = api.w4a8_gemm_i32(qx, blob, N, mode, rowsum=rowsum if mode else None, workspace=ws)
+        bad = (acc.cpu().numpy().astype(np.int64) != ref)
+        assert not bad.any(), f"launch {it}: {int(bad.sum())} INT32 accumulators differ, first at {np.argwhere(bad)[0]}"
+    out = api.w4a8_gemm(qx, sx, blob, N, mode, rowsum=rowsum if mode else None, workspace=ws)
+    ref64 = qq.output_fp64(ref, osx, scale)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref64)
+    assert np.all(err <= REL_TOL * np.abs(ref64) + ABS_TOL), f"fp16 out, worst {err.max()}"
+
+
 def _check_layer(family, layer, Ms, mode, base_seed, samples=48):
     from oracle import gemm as ogemm
     from oracle import qoq_quant as qq
@@ -42,6 +140,11 @@ def _check_layer(family, layer, Ms, mode, base_seed, samples=48):
     w = wl.layer_weights(family, layer, base_seed, dev)
     blob = api.pack_weights(w, mode)
     idx = _sample_channels(N, samples, base_seed * 1000 + N % 997)
+    rng = np.random.default_rng(base_seed * 7919 + N)
+    cut = set()
+    for M in Ms:                                   # where each of these launches cuts the layer
+        cut |= _partition_channels(M, N, K, mode, rng)
+    idx = np.array(sorted(set(int(v) for v in idx) | cut), dtype=np.int64)
     w_rows = w[torch.from_numpy(idx).to(dev)].cpu().numpy()
     del w
     torch.cuda.empty_cache()
@@ -97,6 +200,22 @@ def _check_layer(family, layer, Ms, mode, base_seed, samples=48):
         torch.cuda.empty_cache()
     del blob
     torch.cuda.empty_cache()
+
+
+# C1 and C4 at M = 64, whole tensors; the layers whose blocks are shared between workgroups (down, and O at one
+# token) are launched 50 times over.
+@pytest.mark.parametrize("layer", list(wl.LLAMA2_7B))
+def test_llama2_7b_decode_whole_tensor(layer):
+    _check_whole_layer("llama2_7b", layer, 64, api.QOQ_GROUP128, 1, launches=50 if layer in ("down", "o") else 2)
+
+
+@pytest.mark.parametrize("layer", list(wl.LLAMA3_8B))
+def test_llama3_8b_per_channel_decode_whole_tensor(layer):
+    _check_whole_layer("llama3_8b", layer, 64, api.QOQ_PER_CHANNEL, 4, launches=50 if layer == "down" else 2)
+
+
+def test_llama2_7b_down_one_token_whole_tensor_repeated():
+    _check_whole_layer("llama2_7b", "down", 1, api.QOQ_GROUP128, 1, launches=50)
 
 
 # C1: the benchmark workload itself, every layer at M = 64 (and the neighbouring tile sizes).
