@@ -1709,15 +1709,20 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
         if (c.cost < 0.99 * plan.cost) { plan = c; stream_tile = t; }
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
-    // Up to 32 tokens the activation-stationary kernels are the fastest wherever one workgroup can hold the whole
-    // of K and there is at least a fragment per compute unit (measured on the Llama-2-7B layers at 1 ... 32 tokens:
-    // 5 - 25% ahead of the register-streaming and lockstep kernels for K = 4096, behind them for K = 11008, where
-    // those spread K over the chip; at 64 tokens loading the [64, K] slab costs more than it saves).
-    if (!forced.tile_m && M <= 32) {
-        const int cand = M <= 16 ? 69 : 70;
+    // The activation-stationary kernels are the fastest wherever one workgroup can hold the whole of K and there
+    // is at least a fragment per compute unit (measured on the Llama-2-7B layers: up to 32 tokens 5 - 30% ahead of
+    // the register-streaming and lockstep kernels for K = 4096, behind them for K = 11008, where those spread K over
+    // the chip).  At 33 - 64 tokens loading the [64, K] slab into every compute unit costs about 3 us more than at
+    // 16 tokens, which only the widest layers win back (gate/up: 17.1 us against 18.3 us; QKV: 13.0 against 12.3);
+    // a narrow layer (256 fragments) is best served as two 32-token tiles, one workgroup per compute unit.
+    if (!forced.tile_m && M <= 64) {
+        const int64_t frags = N / 16;
+        int cand = M <= 16 ? 69 : M <= 32 ? 70 : 71;
+        bool take = M <= 32 ? frags >= 192 : frags >= 1024;
+        if (M > 32 && frags >= 192 && frags <= 256) { cand = 70; take = true; }
         int64_t S, gps;
         astat_slices(G, cand, S, gps);
-        if (S == 1 && G <= 64 && N / 16 >= 192) tile_m = cand;
+        if (take && S == 1 && G <= (cand == 71 ? 32 : 64)) tile_m = cand;
     }
     if (tile_m >= 69 && tile_m <= 71) {
         split_k = (int)astat_nwg(M, N, G, tile_m, forced.split_k);

@@ -49,11 +49,11 @@ __global__ __launch_bounds__(kAsThreads) void astat_kernel(GemmDev p)
     static_assert(J * MF <= 16, "128 registers of activations per lane");
     constexpr int D = R * J;
     constexpr int kEl = MF * 64;                       // int4 elements of a fragment tile: mf * 64 + lane
-    // LDS: first the staging buffers of the activation preload (two chunks of 16 tokens x 4 KiB), afterwards, in
-    // the same bytes, the double-buffered exchange of the waves' fragment sums.
-    constexpr int kStageBytes = 16 * 4096;
-    __shared__ __attribute__((aligned(16))) char lds_raw[2 * kStageBytes];
-    static_assert(2 * kAsWaves * kEl * 16 <= 2 * kStageBytes, "the exchange buffers fit in the staging area");
+    // LDS: first every wave's private staging area of the activation preload, afterwards, in the same bytes, the
+    // double-buffered exchange of the waves' fragment sums.
+    constexpr int kWaveStage = 16 * 1024;
+    __shared__ __attribute__((aligned(16))) char lds_raw[kAsWaves * kWaveStage];
+    static_assert(2 * kAsWaves * kEl * 16 <= kAsWaves * kWaveStage, "the exchange buffers fit in the staging areas");
     int4 (*red)[kAsWaves][kEl] = reinterpret_cast<int4 (*)[kAsWaves][kEl]>(lds_raw);
     __shared__ int s_last[kAsMaxFrags];
 
@@ -91,81 +91,79 @@ __global__ __launch_bounds__(kAsThreads) void astat_kernel(GemmDev p)
     // ---- activations: loaded once, resident for the whole kernel ---------------------------------
     // lane (ml, q) holds, of every (group, m-fragment, k-step) operand, token row ml and the 16-byte k-chunk q.
     // Loading those words directly costs the vector cache one request per 64-byte half line (16 rows x 64 B per
-    // instruction) and was measured three times slower than reading whole lines, so the slab goes through LDS:
-    // chunks of 16 tokens x 32 groups are copied by global->LDS DMA, 1 KiB of one token row per instruction (eight
-    // whole 128-byte lines), double buffered, and every wave then reads its operands from LDS.  Inside a row the
-    // 16-byte chunks are stored XORed with row_swizzle(row), which keeps the operand reads free of bank conflicts.
+    // instruction) and was measured three times slower than reading whole lines, so they go through LDS: every
+    // wave copies the columns of ITS OWN groups (JP * 128 contiguous bytes of each token row, whole 128-byte lines,
+    // 1 KiB per instruction) into a private 16 KiB staging area by global->LDS DMA and reads its operands back --
+    // one or two passes, no barrier: the waves do not wait for one another.  Inside a row the 16-byte chunks are
+    // stored XORed with the row number (64-bank LDS: the 16 lanes served together read the same chunk of 16
+    // consecutive rows), which keeps the operand reads free of bank conflicts.
     v4i a[J][MF][2];
 #pragma unroll
     for (int j = 0; j < J; ++j)
 #pragma unroll
         for (int mf = 0; mf < MF; ++mf) a[j][mf][0] = a[j][mf][1] = (v4i){0, 0, 0, 0};   // slots past the slice stay zero
     {
+        constexpr int JP = J >= 8 ? 8 : 4;                                   // groups per pass
+        constexpr int RP = (128 / JP) < MF * 16 ? (128 / JP) : MF * 16;      // token rows per pass
+        constexpr int kRowPasses = MF * 16 / RP, kJPasses = (J + JP - 1) / JP, kDma = RP * JP / 8;
+        static_assert(kDma * 1024 <= kWaveStage && RP % 16 == 0, "a pass fits the wave's staging area");
         const char* abase = reinterpret_cast<const char*>(p.qx);
-        const uint32_t stage = (uint32_t)(uintptr_t)&lds_raw[0];
-        const int KC = (g_hi - g_lo + 31) >> 5;            // chunks along k
-        const int T = MF * KC;
-        // copy role: wave w copies two token rows of a chunk, four 1 KiB parts each
-        const int rot = (int)blockIdx.x >> 3;              // workgroups 8 apart share an XCD
-        const int rot_r = rot & 15, rot_p = (rot >> 4) & 3;
-        auto issue_chunk = [&](int t) __attribute__((always_inline)) {
-            const int mf = t / KC, kc = t - mf * KC;
-            const uint32_t dst = stage + (uint32_t)(t & 1) * kStageBytes;
+        const uint32_t region = (uint32_t)(uintptr_t)&lds_raw[0] + (uint32_t)wave * kWaveStage;
+        const char* region_ptr = lds_raw + wave * kWaveStage;
+        auto issue_pass = [&](int rp, int jp) __attribute__((always_inline)) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                // (the workgroups of an XCD walk the chunk in different orders: they all want the same lines, and in
-                // step they would all queue at the same L2 channel)
-                const int r = (2 * wave + (i >> 2) + rot_r) & 15, part = ((i & 3) + rot_p) & 3;
-                const uint32_t row = (uint32_t)min(m0 + mf * 16 + r, p.M - 1);      // rows past M repeat the last one
-                const uint32_t col = min((uint32_t)(g_lo + 32 * kc) * (uint32_t)kGroup + (uint32_t)part * 1024u +
-                                             (uint32_t)((lane ^ row_swizzle(r)) * 16),
-                                         (uint32_t)p.K - 16u);                        // parts past the row re-read its end
-                dma16(abase, row * (uint32_t)p.K + col, dst + (uint32_t)(r * 4096 + part * 1024));
+            for (int i = 0; i < kDma; ++i) {
+                const int flat = i * 64 + lane;                              // 16-byte position inside the pass
+                const int row_local = flat / (JP * 8), pos = flat % (JP * 8);
+                const uint32_t row = (uint32_t)min(m0 + rp * RP + row_local, p.M - 1);   // rows past M repeat the last one
+                const uint32_t col = min((uint32_t)(g_lo + wave * jeff + jp * JP) * (uint32_t)kGroup +
+                                             (uint32_t)((pos ^ (row_local & 15)) * 16),
+                                         (uint32_t)p.K - 16u);                // groups past K re-read the end of the row
+                dma16(abase, row * (uint32_t)p.K + col, region + (uint32_t)(i * 1024));
             }
         };
-        // Order of the requests: two chunks of activations; then, once every wave's copies of the first chunk have
-        // landed, the first R fragments of weights; then the other chunks as the staging buffers come free.  Data
-        // returns to a compute unit in request order, whichever wave asked, so no wave's weights (a trip to memory)
-        // may stand in front of another wave's first chunks; behind them their latency passes while the chunks are
-        // unpacked.  The waits below count what this wave requested after the chunk it waits for: kNW weight
-        // loads (build.py checks that the compiler emits exactly that many) and 8 copies per chunk.
-        constexpr int kNW = R * J * (GROUP ? 2 : 1);
-        static_assert(kNW + 8 < 64, "vmcnt range");
-        issue_chunk(0);
-        if (T > 1) issue_chunk(1);
+        auto read_pass = [&](int rp, int jp) __attribute__((always_inline)) {
 #pragma unroll
-        for (int mf = 0; mf < MF; ++mf) {
-            for (int kc = 0; kc < KC; ++kc) {
-                const int t = mf * KC + kc;
-                // this wave's copies of chunk t have landed
-                if (t == 0) { if (T > 1) wait_vmcnt<8>(); else wait_vmcnt<0>(); }
-                else if (t == 1) { if (T > 2) wait_vmcnt<kNW + 8>(); else wait_vmcnt<kNW>(); }
-                else if (t + 1 < T) wait_vmcnt<8>();
-                else wait_vmcnt<0>();
-                __syncthreads();                                         // ... and everyone else's
-                if (mf == 0 && kc == 0) {
-                    asm volatile("; astat weight prologue begin" ::: "memory");
+            for (int mm = 0; mm < RP / 16; ++mm)
 #pragma unroll
-                    for (int r = 0; r < R; ++r)
+                for (int jj = 0; jj < JP; ++jj) {
+                    const int mf = rp * (RP / 16) + mm, j = jp * JP + jj;
+                    if (j < J) {
+                        if (slot_valid(j)) {                                 // wave-uniform
+                            const int row_local = mm * 16 + ml;
 #pragma unroll
-                        for (int j = 0; j < J; ++j) load_unit(r * J + j, j, f0 + min(r, nfr - 1));
-                    asm volatile("; astat weight prologue end" ::: "memory");
-                }
-                const char* src = lds_raw + (t & 1) * kStageBytes + ml * 4096;
-#pragma unroll
-                for (int j = 0; j < J; ++j) {
-                    const int g = wave * jeff + j;                       // relative to g_lo; wave-uniform
-                    if (slot_valid(j) && (g >> 5) == kc) {
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks)
-                            a[j][mf][ks] = *reinterpret_cast<const v4i*>(src + (g & 31) * kGroup + (((ks * 4 + q) ^ row_swizzle(ml)) * 16));
+                            for (int ks = 0; ks < 2; ++ks)
+                                a[j][mf][ks] = *reinterpret_cast<const v4i*>(region_ptr + row_local * (JP * 128) +
+                                                                             (((jj * 8 + ks * 4 + q) ^ (row_local & 15)) * 16));
+                        }
                     }
                 }
-                __syncthreads();                                         // the buffer may be overwritten
-                if (t + 2 < T) issue_chunk(t + 2);
-            }
+        };
+        // Order of the requests: the first pass of activations, then the first R fragments of weights (a trip to
+        // memory: data returns in request order, so they must not stand in front of the first pass; behind it
+        // their latency passes while the pass is unpacked), then the other passes.  The waits count what this wave
+        // requested after the pass it waits for: kNW weight loads (build.py checks that the compiler emits
+        // exactly that many).
+        constexpr int kNW = R * J * (GROUP ? 2 : 1);
+        static_assert(kNW < 64, "vmcnt range");
+        issue_pass(0, 0);
+        asm volatile("; astat weight prologue begin" ::: "memory");
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int j = 0; j < J; ++j) load_unit(r * J + j, j, f0 + min(r, nfr - 1));
+        asm volatile("; astat weight prologue end" ::: "memory");
+        wait_vmcnt<kNW>();
+        read_pass(0, 0);
+#pragma unroll
+        for (int pp = 1; pp < kRowPasses * kJPasses; ++pp) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");               // the reads of the pass before are done
+            issue_pass(pp / kJPasses, pp % kJPasses);
+            wait_vmcnt<0>();
+            read_pass(pp / kJPasses, pp % kJPasses);
         }
     }
+    __syncthreads();    // the staging areas become the exchange buffers of the fragment sums
 
     // ---- epilogue role: thread t owns element t of every fragment tile (one token, four consecutive channels) ----
     const int el = threadIdx.x;

@@ -119,10 +119,12 @@ def test_launch_plan_host_logic(api):
                 else:
                     assert M > 64 and split <= K // 128
                 assert api.gemm_workspace_bytes(M, N, K) % 16 == 0
-    assert api.query_gemm_config(64, 4096, 4096) == (16, 64)        # 64 blocks: four 16-token tiles x 64 workgroups
+    assert api.query_gemm_config(64, 4096, 4096) == (70, 128)       # narrow: two 32-token tiles x 128 workgroups, activations resident
     assert api.query_gemm_config(64, 12288, 4096) == (64, 192)      # one block per workgroup already
-    assert api.query_gemm_config(64, 22016, 4096) == (65, 172)      # one whole pair of blocks per workgroup, in lockstep
-    assert api.query_gemm_config(64, 22016, 4096, api.QOQ_PER_CHANNEL) == (65, 172)   # in either mode
+    assert api.query_gemm_config(64, 22016, 4096) == (71, 256)      # widest layer: activations resident, 16-channel fragments dealt to 256 workgroups
+    assert api.query_gemm_config(64, 22016, 4096, api.QOQ_PER_CHANNEL) == (71, 256)   # in either mode
+    assert api.query_gemm_config(64, 4096, 11008) == (32, 128)      # K too long for one workgroup's registers: K spread over the chip
+    assert api.query_gemm_config(16, 12288, 4096) == (69, 256)
     assert api.query_gemm_config(1024, 12288, 4096)[0] == 131       # 256 tiles of 256 x 192
     api.set_gemm_config(32, 5)
     try:

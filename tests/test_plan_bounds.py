@@ -119,13 +119,24 @@ static void check_astat(int tl) {
         if (f0 >= f1) continue;
         const ll g_lo = sl * gps, g_hi = std::min(G, g_lo + gps);
         if (g_lo >= g_hi) { fail = "astat empty slice"; return; }
-        const ll KC = (g_hi - g_lo + 31) >> 5;
-        for (ll mf = 0; mf < MF; ++mf) for (ll kc = 0; kc < KC; ++kc) for (int r = 0; r < 16; ++r) for (int part = 0; part < 4; ++part)
-            for (int lane = 0; lane < 64; lane += 63) {
-                const ll row = std::min(m0 + mf * 16 + r, M - 1);
-                const ll col = std::min((g_lo + 32 * kc) * kGroup + part * 1024 + (ll)((lane ^ ((r >> 1) & 7)) * 16), K - 16);
-                chk("qx", row * K + col, 16, n_qx);
+        if (wg == 0) {   // the activation preload does not depend on the workgroup's fragments
+            // compiled group capacity per wave: the smallest instantiation that holds jeff groups
+            const ll J = tl == 64 ? std::max<ll>(jeff, 2) : tl == 32 ? (jeff <= 4 ? 4 : 8) : (jeff <= 4 ? 4 : jeff <= 8 ? 8 : 16);
+            const ll JP = J >= 8 ? 8 : 4, RP = std::min<ll>(128 / JP, MF * 16), row_passes = MF * 16 / RP, j_passes = cdiv(J, JP), dma = RP * JP / 8;
+            if (dma * 1024 > 16384) { fail = "astat staging"; return; }
+            for (int w = 0; w < waves; ++w) for (ll rp = 0; rp < row_passes; ++rp) for (ll jp = 0; jp < j_passes; ++jp) {
+                for (ll flat = 0; flat < dma * 64; ++flat) {
+                    const ll row_local = flat / (JP * 8), pos = flat % (JP * 8);
+                    const ll row = std::min(m0 + rp * RP + row_local, M - 1);
+                    const ll col = std::min((g_lo + w * jeff + jp * JP) * kGroup + ((pos ^ (row_local & 15)) * 16), K - 16);
+                    chk("qx", row * K + col, 16, n_qx);
+                }
+                for (ll mm = 0; mm < RP / 16; ++mm) for (ll jj = 0; jj < JP; ++jj) for (int lane = 0; lane < 64; ++lane) for (int ks = 0; ks < 2; ++ks) {
+                    const ll row_local = mm * 16 + (lane & 15), L = jj * 8 + ks * 4 + (lane >> 4);
+                    chk("staging", row_local * JP * 128 + ((L ^ (row_local & 15)) * 16), 16, dma * 1024);
+                }
             }
+        }
         for (ll nf = f0; nf < f1; ++nf) {
             for (int w = 0; w < waves; ++w) for (ll j = 0; j < std::max<ll>(jeff, 1) + 3; ++j) {   // slots past jeff re-read the last group
                 const ll g = std::min(g_lo + w * jeff + std::min(j, jeff - 1), g_hi - 1);
