@@ -53,6 +53,19 @@ def profile_traffic(workload, config_now):
     return None, None
 
 
+def load_read_probe():
+    """The measurement probe built next to the library (a plain streaming read; see csrc/probe_read.hip)."""
+    import ctypes
+
+    from paper_2405_04532_amd import build as qbuild
+    if not os.path.exists(qbuild.PROBE_LIB):
+        raise RuntimeError(qbuild.PROBE_LIB + " is missing: run `python -m paper_2405_04532_amd.build` first")
+    lib = ctypes.CDLL(qbuild.PROBE_LIB)
+    lib.qoq_probe_read.restype = ctypes.c_int
+    lib.qoq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    return lib
+
+
 def graph_schedule(steps, per_graph):
     """How `steps` timed steps are replayed from captured graphs: (replays of the full graph of `per_graph`
     consecutive steps, steps in one shorter graph replayed once after them).  Any steps >= 1 is timed exactly."""
@@ -203,6 +216,24 @@ def main():
     ms_step = timed(full_step, args.steps, args.warmup)
     ms_gemm = timed(gemm_only, args.steps, args.warmup)   # the four GEMM launches alone
 
+    # What a plain read reaches in the same launch regime: the simplest streaming kernel over the same packed
+    # weights (same rotation, same graph replay), best of four grid sizes.  Context for `frac`, which stays
+    # measured against the published peak.
+    probe = load_read_probe()
+    sink = torch.zeros(65536, dtype=torch.int32, device=dev)
+    floor = None
+    for nwg in (256, 512, 1024, 2048):
+        def read_step(step, s=None, nwg=nwg):
+            s = sp if s is None else s
+            for name, _ in layers:
+                blob = blobs[name][step % args.copies]
+                if probe.qoq_probe_read(P(blob), blob.numel() // 16 * 16, P(sink), nwg, s) != 0:
+                    raise RuntimeError("qoq_probe_read refused its arguments")
+        ms = timed(read_step, args.steps, min(args.warmup, 3))
+        if floor is None or ms < floor[0]:
+            floor = (ms, nwg)
+    read_bytes = sum(blobs[name][0].numel() // 16 * 16 for name, _ in layers)
+
     ops = sum(2.0 * M * K * N for _, (K, N) in layers)
     byts = sum(algorithmic_bytes(M, N, K) for _, (K, N) in layers)
     tops = ops / (ms_step * 1e-3) / 1e12
@@ -229,7 +260,15 @@ def main():
                      "algorithmic_ops_per_launch": round(ops / len(layers)),
                      "gemm_only_tops": round(gemm_tops, 3), "gemm_only_gbs": round(gemm_gbs, 1),
                      "int8_mfma_frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
-                     "hbm_frac": round(gemm_gbs / HBM_PEAK_GBS, 4)})
+                     "hbm_frac": round(gemm_gbs / HBM_PEAK_GBS, 4),
+                     "read_floor": {
+                         "kernel": "plain streaming read of the same packed weights, one launch per layer, same "
+                                   "rotation and graph replay (best of 256/512/1024/2048 workgroups)",
+                         "workgroups": floor[1], "avg_launch_us": round(floor[0] * 1e3 / len(layers), 3),
+                         "bytes_per_launch": read_bytes // len(layers),
+                         "gbs": round(read_bytes / (floor[0] * 1e-3) / 1e9, 1),
+                         "frac_of_peak": round(read_bytes / (floor[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                     "gemm_time_over_read_floor": round(ms_gemm / floor[0], 3)})
 
     result = {
         "metric": "W4A8 GEMM effective TOPS (Llama-2-7B-shaped layers, M=%d, g128)" % M,

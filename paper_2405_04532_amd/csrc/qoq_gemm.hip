@@ -1634,8 +1634,11 @@ static StreamPlan stream_plan(int64_t M, int64_t N, int64_t G, int tile, int64_t
         const double miss = std::min(1.0, weight_mb / 32.0);
         const double reads = (n_eff % 8 == 0 && rounds == 1) ? 1.0 + miss * (double)(m_tiles - 1) : (double)m_tiles;
         // every further block of a workgroup's run ends in an exchange of partial sums and an epilogue
-        const double loop = (double)rounds * ((double)((upw + per_it - 1) / per_it) * t_it +
-                                              (double)((upw + G - 1) / G - 1) * (tile == 64 ? 0.3 : 0.8));
+        double loop = (double)rounds * ((double)((upw + per_it - 1) / per_it) * t_it +
+                                        (double)((upw + G - 1) / G - 1) * (tile == 64 ? 0.3 : 0.8));
+        // a long run of the 16-token kernel streams 25 GB/s per workgroup (0.16 us per 4 KiB unit; measured on
+        // K = 28672: 128 workgroups of 224 units 40.6 us, 256 of 112 units 27.7 us)
+        if (tile == 16 && upw >= 64) loop = std::max(loop, (double)rounds * (double)upw * 0.16);
         // the hand-over follows the loop; a later round pays it again and waits 1.5 us for its first copies
         return fixed + std::max(loop, weight_mb * reads / 4.5) + (double)rounds * (upw % G ? handover : 0.0) +
                (double)(rounds - 1) * 1.5;
@@ -1709,12 +1712,14 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
         if (c.cost < 0.99 * plan.cost) { plan = c; stream_tile = t; }
     }
     tile_m = forced.tile_m ? forced.tile_m : (M <= 64 ? stream_tile : 128);
-    // The activation-stationary kernels are the fastest wherever one workgroup can hold the whole of K and there
-    // is at least a fragment per compute unit (measured on the Llama-2-7B layers: up to 32 tokens 5 - 30% ahead of
-    // the register-streaming and lockstep kernels for K = 4096, behind them for K = 11008, where those spread K over
-    // the chip).  At 33 - 64 tokens loading the [64, K] slab into every compute unit costs about 3 us more than at
-    // 16 tokens, which only the widest layers win back (gate/up: 17.1 us against 18.3 us; QKV: 13.0 against 12.3);
-    // a narrow layer (256 fragments) is best served as two 32-token tiles, one workgroup per compute unit.
+    // The activation-stationary kernels are the fastest wherever a workgroup's registers hold the activations of
+    // all of K, or of half of it (two k-slices meeting in the workspace), and there is at least a fragment per
+    // compute unit.  Measured on the Llama-2-7B layers: up to 32 tokens 5 - 30% ahead of the register-streaming and
+    // lockstep kernels for K = 4096 and 5 - 13% for K = 11008 (two slices).  At 33 - 64 tokens loading the [64, K]
+    // slab into every compute unit costs about 3 us more than at 16 tokens (the compute unit's vector cache takes in
+    // about 100 bytes per ns; reading the slab pre-tiled straight into registers was measured no faster), which only
+    // the widest layers win back (gate/up: 17.1 us against 18.3 us; QKV: 13.0 against 12.3); a narrow layer
+    // (256 fragments) is best served as two 32-token tiles, one workgroup per compute unit.
     if (!forced.tile_m && M <= 64) {
         const int64_t frags = N / 16;
         int cand = M <= 16 ? 69 : M <= 32 ? 70 : 71;
@@ -1722,7 +1727,8 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
         if (M > 32 && frags >= 192 && frags <= 256) { cand = 70; take = true; }
         int64_t S, gps;
         astat_slices(G, cand, S, gps);
-        if (take && S == 1 && G <= (cand == 71 ? 32 : 64)) tile_m = cand;
+        const bool fits = M <= 32 ? S <= 2 : (S == 1 && G <= (cand == 71 ? 32 : 64));
+        if (take && fits) tile_m = cand;
     }
     if (tile_m >= 69 && tile_m <= 71) {
         split_k = (int)astat_nwg(M, N, G, tile_m, forced.split_k);

@@ -10,8 +10,10 @@
 // traffic -- the loop should then move weights only).
 //
 //   * Workgroup = eight waves, two per SIMD, 256 registers per lane each.  Wave w keeps the activations of the
-//     quantization groups g_lo + 8j + w (j = 0 .. J-1) of the workgroup's k-slice: J * MF * 2 operands of 16 bytes
-//     per lane (MF = tokens / 16), at most 128 registers -- together the 256 KiB a [64, 4096] INT8 slab takes.
+//     quantization groups g_lo + w * J' + j (j = 0 .. J'-1, J' <= J) of the workgroup's k-slice: J * MF * 2 operands
+//     of 16 bytes per lane (MF = tokens / 16), at most 128 registers -- together the 256 KiB a [64, 4096] INT8 slab
+//     takes; J <= 4 at 64 tokens, <= 8 at 32 and 16 tokens (sixteen groups per wave at 16 tokens, i.e. all of
+//     K = 11008 in one workgroup, lost to two k-slices of eight: every compute unit then loads half the slab).
 //     (Four waves with twice the registers each were tried first: the compiler then parks part of the activations
 //     in accumulation registers and copies them back in front of every matrix instruction.)  Slots past the end
 //     of the slice hold zeros, so the loop needs no bounds logic: whatever weights are loaded for such a slot are
@@ -310,7 +312,6 @@ hipError_t launch_mode(const GemmDev& p, int tile, dim3 grid, bool fp16, hipStre
     } else {
         if (need <= 4) launch_j<1, 4, 2, GROUP>(p, grid, fp16, s);
         else if (need <= 8) launch_j<1, 8, 1, GROUP>(p, grid, fp16, s);
-        else if (need <= 16) launch_j<1, 16, 1, GROUP>(p, grid, fp16, s);
         else return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -318,7 +319,7 @@ hipError_t launch_mode(const GemmDev& p, int tile, dim3 grid, bool fp16, hipStre
 
 }  // namespace
 
-int astat_max_groups(int tile) { return kAsWaves * (tile == 64 ? 4 : tile == 32 ? 8 : 16); }
+int astat_max_groups(int tile) { return kAsWaves * (tile == 64 ? 4 : 8); }
 
 hipError_t launch_astat(const GemmDev& p, int tile_m, int nwg, bool group, bool fp16, hipStream_t s)
 {

@@ -69,11 +69,50 @@ def test_driver_command_line_prints_one_complete_json_line():
     assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
     assert "traffic" in roof
+    # the plain read of the same weights, timed beside the GEMM: between the launch floor and the GEMM's own time
+    floor = roof["read_floor"]
+    assert 2.0 < floor["avg_launch_us"] < roof["avg_launch_us"] * 1.2 and 0 < floor["frac_of_peak"] < 1
+    assert abs(roof["gemm_time_over_read_floor"] - roof["avg_launch_us"] / floor["avg_launch_us"]) < 0.02
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     leg = d["compute_leg"]
     assert leg["workload"] == "llama3_70b_prefill_m2048"
     assert leg["roofline"]["bound"] == "mfma" and leg["roofline"]["peak"] == 5033.0 and 0 < leg["roofline"]["frac"] < 1
+
+
+def test_read_probe_library_exports_its_entry_point():
+    import ctypes
+
+    from paper_2405_04532_amd import build as qbuild
+    assert os.path.exists(qbuild.PROBE_LIB), "run `python -m paper_2405_04532_amd.build` first"
+    lib = ctypes.CDLL(qbuild.PROBE_LIB)
+    assert hasattr(lib, "qoq_probe_read")
+    lib.qoq_probe_read.restype = ctypes.c_int
+    lib.qoq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    # argument checks run before anything touches a device
+    assert lib.qoq_probe_read(None, 1024, None, 256, None) == 1
+    assert lib.qoq_probe_read(ctypes.c_void_p(4096), 1000, ctypes.c_void_p(4096), 256, None) == 1
+    assert lib.qoq_probe_read(ctypes.c_void_p(4096), 1024, ctypes.c_void_p(4096), 0, None) == 1
+
+
+@pytest.mark.gpu
+def test_read_probe_reads_what_it_is_given():
+    """Contract of the probe: the call succeeds for sizes around the slab boundaries and any grid, stays inside the
+    buffer (the sizes below end exactly at the end of the allocation's used part), and leaves the sink untouched
+    for ordinary data."""
+    import ctypes
+
+    import torch
+
+    import bench
+    lib = bench.load_read_probe()
+    src = torch.zeros(1 << 20, dtype=torch.int32, device="cuda:0")
+    sink = torch.full((4096,), -1, dtype=torch.int32, device="cuda:0")
+    for nbytes in (16, 4096 + 16, (1 << 22) - 16, 1 << 22):
+        for nwg in (1, 7, 256, 4096):
+            assert lib.qoq_probe_read(src.data_ptr(), nbytes, sink.data_ptr(), nwg, None) == 0
+    torch.cuda.synchronize()
+    assert bool((sink == -1).all())
 
 
 def test_more_than_one_gpu_is_refused():

@@ -109,7 +109,7 @@ static void check_lockstep(int NB, int MF) {
 
 // ---- activation-stationary kernels ---------------------------------------------------------------------------------
 static void check_astat(int tl) {
-    const int MF = tl / 16, waves = 8, cap = waves * (tl == 64 ? 4 : tl == 32 ? 8 : 16);
+    const int MF = tl / 16, waves = 8, cap = waves * (tl == 64 ? 4 : 8);
     ll S = cdiv(G, cap), gps = cdiv(G, S); S = cdiv(G, gps);
     const ll nf_total = N / 16, nwg = split, base = nf_total / nwg, rem = nf_total - base * nwg, m_tiles = cdiv(M, tl), kEl = MF * 64;
     const ll jeff = cdiv(gps, waves);
@@ -121,7 +121,7 @@ static void check_astat(int tl) {
         if (g_lo >= g_hi) { fail = "astat empty slice"; return; }
         if (wg == 0) {   // the activation preload does not depend on the workgroup's fragments
             // compiled group capacity per wave: the smallest instantiation that holds jeff groups
-            const ll J = tl == 64 ? std::max<ll>(jeff, 2) : tl == 32 ? (jeff <= 4 ? 4 : 8) : (jeff <= 4 ? 4 : jeff <= 8 ? 8 : 16);
+            const ll J = tl == 64 ? std::max<ll>(jeff, 2) : (jeff <= 4 ? 4 : 8);
             const ll JP = J >= 8 ? 8 : 4, RP = std::min<ll>(128 / JP, MF * 16), row_passes = MF * 16 / RP, j_passes = cdiv(J, JP), dma = RP * JP / 8;
             if (dma * 1024 > 16384) { fail = "astat staging"; return; }
             for (int w = 0; w < waves; ++w) for (ll rp = 0; rp < row_passes; ++rp) for (ll jp = 0; jp < j_passes; ++jp) {
