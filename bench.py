@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compute-leg", action="store_true",
                     help="skip the compute-bound leg (Llama-3-70B layers at M = 2048) that the default run appends")
+    ap.add_argument("--compute-leg-only", action="store_true",
+                    help="run only the compute-bound leg and print its object (for profiling that leg alone)")
     ap.add_argument("--sweep", type=str, default=None, help="also write a per-layer/per-M table to this file")
     ap.add_argument("--attention", action="store_true",
                     help="time the KV4 decode attention kernel instead (64 sequences x --seq tokens, Llama-2-7B heads)")
@@ -125,6 +127,9 @@ def main():
         return
     if args.producers:
         print(json.dumps(producers_bench(args, api, wl, dev)))
+        return
+    if args.compute_leg_only:
+        print(json.dumps(compute_leg(args, api, wl, dev)))
         return
     M = args.m
     layers = list(wl.LLAMA2_7B.items())          # name -> (K, N)
