@@ -1776,7 +1776,21 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
             if (c < 0.98 * best) { best = c; tile_m = cand; }
         }
         const double stream_cost = pair_wins ? lock_cost : plan.cost;
-        if (stream_cost < (pair_wins ? 0.95 : 0.9) * best) tile_m = pair_wins ? lock : stream_tile;
+        double chosen = best;
+        if (stream_cost < (pair_wins ? 0.95 : 0.9) * best) { tile_m = pair_wins ? lock : stream_tile; chosen = stream_cost; }
+        // Or 64-token activation-stationary tiles side by side, all token tiles together on the 256 compute units
+        // (K <= 4096: one workgroup holds all of K; measured 6.5 us + 1.15 ... 1.5 us per fragment of a workgroup's
+        // run on the Llama-2-7B and Llama-3-8B layers at 96 ... 512 tokens: QKV at M = 128 15.5 us against 18.4 us,
+        // gate+up 22.5 against 27.8, Llama-3-8B QKV at M = 384 18.7 against 23.0).
+        if (G <= 32 && M <= 512) {
+            const int64_t m_tiles = (M + 63) / 64, n = std::max<int64_t>(1, 256 / m_tiles);
+            const double c = 6.5 + 1.4 * (double)((N / 16 + n - 1) / n);
+            if (c < 0.97 * chosen) {
+                tile_m = 71;
+                split_k = (int)astat_nwg(M, N, G, tile_m, 0);
+                return;
+            }
+        }
         if (tile_m == 65 || tile_m == 66) {
             split_k = (int)pair_plan(M, N, G, 0, tile_m == 65 ? 2 : 4).nwg;
             return;
