@@ -1728,13 +1728,14 @@ void pick_gemm_config(int64_t M, int64_t N, int64_t K, int mode, const GemmTunin
     // lockstep kernels for K = 4096 and 5 - 13% for K = 11008 (two slices).  At 33 - 64 tokens loading the [64, K]
     // slab into every compute unit costs about 3 us more than at 16 tokens (the compute unit's vector cache takes in
     // about 100 bytes per ns; reading the slab pre-tiled straight into registers was measured no faster), which only
-    // the widest layers win back (gate/up: 17.1 us against 18.3 us; QKV: 13.0 against 12.3); a narrow layer
-    // (256 fragments) is best served as two 32-token tiles, one workgroup per compute unit.
+    // the widest layers win back (gate/up: 17.1 us against 18.3 us; QKV: 13.0 against 12.3); layers of 192 - 704
+    // fragments are best served as two 32-token tiles, one workgroup per compute unit (Llama-2-7B O 7.6 us against
+    // 7.9, Llama-3-8B QKV 8.4 against 9.0, Llama-3-70B QKV 18.1 against 19.3).
     if (!forced.tile_m && M <= 64) {
         const int64_t frags = N / 16;
         int cand = M <= 16 ? 69 : M <= 32 ? 70 : 71;
         bool take = M <= 32 ? frags >= 192 : frags >= 1024;
-        if (M > 32 && frags >= 192 && frags <= 256) { cand = 70; take = true; }
+        if (M > 32 && frags >= 192 && frags <= 704) { cand = 70; take = true; }
         int64_t S, gps;
         astat_slices(G, cand, S, gps);
         const bool fits = M <= 32 ? S <= 2 : (S == 1 && G <= (cand == 71 ? 32 : 64));
