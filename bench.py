@@ -63,7 +63,38 @@ def load_read_probe():
     lib = ctypes.CDLL(qbuild.PROBE_LIB)
     lib.qoq_probe_read.restype = ctypes.c_int
     lib.qoq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    lib.qoq_probe_mfma.restype = ctypes.c_int
+    lib.qoq_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     return lib
+
+
+def mfma_ceiling(dev):
+    """What the INT8 matrix cores sustain on this machine, with no memory traffic at all (csrc/probe_mfma.hip): one
+    wave per SIMD issuing nothing but the compute-bound kernel's matrix instruction, about 3 ms per mode so that the
+    clock settles.  Fractions of the published peak."""
+    import torch
+    probe = load_read_probe()
+    sink = torch.zeros(16, dtype=torch.int32, device=dev)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {}
+    names = {0: "constant_operands", 1: "random_operands", 2: "random_operands_with_dequant_valu",
+             3: "gemm_like_operands_with_dequant_valu"}
+    iters = 12000
+    for mode, name in names.items():
+        if probe.qoq_probe_mfma(mode, iters // 10, cus, sink.data_ptr(), stream) != 0:
+            raise RuntimeError("qoq_probe_mfma refused its arguments")
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        probe.qoq_probe_mfma(mode, iters, cus, sink.data_ptr(), stream)
+        e1.record()
+        torch.cuda.synchronize()
+        tops = 2.0 * 32 ** 3 * 16 * iters * 4 * cus / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        out[name] = round(tops / INT8_PEAK_TOPS, 4)
+    out["kernel"] = ("v_mfma_i32_32x32x32_i8 back to back, one wave per SIMD on %d compute units, 16 accumulator tiles, "
+                     "no memory or LDS traffic; fractions of the published peak" % cus)
+    return out
 
 
 def graph_schedule(steps, per_graph):
@@ -380,7 +411,8 @@ def compute_leg(args, api, wl, dev, family="llama3_70b", M=2048):
                          "kernel": "qoq_w4a8_gemm launch (average over the four layers)",
                          "avg_launch_us": round(ms_gemm * 1e3 / len(layers), 3),
                          "algorithmic_ops_per_launch": round(ops / len(layers)),
-                         "algorithmic_bytes_per_launch": round(byts / len(layers))}}
+                         "algorithmic_bytes_per_launch": round(byts / len(layers)),
+                         "mfma_ceiling": mfma_ceiling(dev)}}
 
 
 def attention_bench(args, api, wl, dev):

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqoq_w4a8.so")
-PROBE_LIB = os.path.join(HERE, "libqoq_probe.so")     # measurement probe of the benchmark (plain streaming read)
+PROBE_LIB = os.path.join(HERE, "libqoq_probe.so")     # measurement probes of the benchmark (plain streaming read, matrix-core ceiling)
 SOURCES = ["qoq_api.hip", "qoq_pack.hip", "qoq_act.hip", "qoq_gemm.hip", "qoq_gemm_astat.hip", "qoq_kv4.hip", "qoq_transforms.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions off (they have produced wrong results on these machines)
@@ -76,7 +76,8 @@ def build(extra_flags=(), verbose=False):
     with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
-    subprocess.check_call(["hipcc", "-shared", os.path.join(CSRC, "probe_read.hip"), "-o", PROBE_LIB] + FLAGS + extra)
+    subprocess.check_call(["hipcc", "-shared", os.path.join(CSRC, "probe_read.hip"), os.path.join(CSRC, "probe_mfma.hip"),
+                           "-o", PROBE_LIB] + FLAGS + extra)
     if verbose:
         print("built", LIB)
     return LIB

@@ -78,6 +78,12 @@ def test_driver_command_line_prints_one_complete_json_line():
     leg = d["compute_leg"]
     assert leg["workload"] == "llama3_70b_prefill_m2048"
     assert leg["roofline"]["bound"] == "mfma" and leg["roofline"]["peak"] == 5033.0 and 0 < leg["roofline"]["frac"] < 1
+    # the matrix cores' own sustained rates, measured in the same run: constant operands close to the published peak,
+    # random operands below it, the GEMM below the ceiling with the dequantizer's vector work attached
+    ceil = leg["roofline"]["mfma_ceiling"]
+    assert 0.8 < ceil["constant_operands"] <= 1.02
+    assert ceil["random_operands_with_dequant_valu"] <= ceil["random_operands"] * 1.03 <= ceil["constant_operands"] * 1.06
+    assert leg["roofline"]["frac"] < ceil["gemm_like_operands_with_dequant_valu"] * 1.05
 
 
 def test_read_probe_library_exports_its_entry_point():
@@ -86,7 +92,12 @@ def test_read_probe_library_exports_its_entry_point():
     from paper_2405_04532_amd import build as qbuild
     assert os.path.exists(qbuild.PROBE_LIB), "run `python -m paper_2405_04532_amd.build` first"
     lib = ctypes.CDLL(qbuild.PROBE_LIB)
-    assert hasattr(lib, "qoq_probe_read")
+    assert hasattr(lib, "qoq_probe_read") and hasattr(lib, "qoq_probe_mfma")
+    lib.qoq_probe_mfma.restype = ctypes.c_int
+    lib.qoq_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.qoq_probe_mfma(4, 10, 256, ctypes.c_void_p(4096), None) == 1
+    assert lib.qoq_probe_mfma(0, 0, 256, ctypes.c_void_p(4096), None) == 1
+    assert lib.qoq_probe_mfma(0, 10, 256, None, None) == 1
     lib.qoq_probe_read.restype = ctypes.c_int
     lib.qoq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
     # argument checks run before anything touches a device
