@@ -59,7 +59,7 @@ def test_two_calls_in_a_row_second_one_smaller(api):
 @pytest.mark.parametrize("M,N,K,mode,cfg", [(17, 640, 1152, 0, (16, 3)), (64, 320, 1152, 0, (64, 5)), (40, 256, 4096, 1, (32, 9)),
                                             (300, 512, 3072, 0, (128, 2)), (200, 256, 4096, 1, (130, 3)), (64, 640, 1152, 0, (65, 0)),
                                             (1, 4096, 4096, 0, (0, 0)), (64, 12288, 4096, 0, (0, 0)), (64, 256, 11008, 1, (71, 5)),
-                                            (33, 192, 5120, 0, (71, 0))])
+                                            (33, 192, 5120, 0, (71, 0)), (16, 4096, 11008, 0, (0, 0)), (128, 12288, 4096, 0, (0, 0))])
 def test_every_kernel_family(api, M, N, K, mode, cfg):
     api.set_gemm_config(*cfg)
     try:
