@@ -73,6 +73,8 @@ def test_driver_command_line_prints_one_complete_json_line():
     floor = roof["read_floor"]
     assert 1.0 < floor["avg_launch_us"] < roof["avg_launch_us"] * 1.5 and 0 < floor["frac_of_peak"] < 1
     assert abs(roof["gemm_time_over_read_floor"] - roof["avg_launch_us"] / floor["avg_launch_us"]) < 0.02
+    fused = d["fused_producer_step"]        # the same GEMMs fed by the producers with the quantizer fused in
+    assert fused["unit"] == "TOPS" and fused["value"] > 0 and 0.5 * d["ms_per_step"] < fused["ms_per_step"] < 3 * d["ms_per_step"]
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     leg = d["compute_leg"]
