@@ -10,7 +10,11 @@ set are rotated so the weights of a step come from HBM, not from the 256 MB Infi
 as they do when a whole model's layers stream through.
 
 Prints ONE JSON line: effective TOPS (2*M*K*N summed over the layers / step time), the HBM
-roofline of the GEMM launch, and the CPU oracle timed on the host cores as a baseline.
+roofline of the GEMM launch with a plain streaming read of the same weights timed beside it
+(`roofline.read_floor`), the same GEMMs fed by the producers with the quantizer fused in
+(`fused_producer_step`), the compute-bound leg (`compute_leg`: Llama-3-70B-shaped layers at
+M = 2048 with their own roofline and the matrix cores' measured ceiling), and the CPU oracle
+timed on the host cores as a baseline.
 `--sweep FILE` additionally writes per-layer, per-M timings of every configuration family.
 `--attention` times the KV4 decode attention kernel instead (its own JSON line, same fields).
 `--producers` times RMSNorm and SiLU*up with the quantizer fused in, at --m tokens (its own JSON line, same fields).
