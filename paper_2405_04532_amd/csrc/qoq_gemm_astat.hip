@@ -20,13 +20,15 @@
 //     multiplied by zero.
 //   * Work item = one 16-channel fragment of the packed layout (1 KiB per quantization group, contiguous over the
 //     groups).  The layer's fragments are dealt in contiguous, equal runs to the workgroups, so a workgroup reads
-//     one contiguous stretch of the packed weights, each wave every eighth KiB, each lane exactly the 16 bytes its
+//     one contiguous stretch of the packed weights, each wave its own J' consecutive KiB of every fragment, each lane exactly the 16 bytes its
 //     matrix-instruction operand consists of (Section 5.2.1: stored in consumption order) -- straight into
 //     registers, a ring of D units ahead, no LDS staging, no barrier inside a fragment.
 //   * Per unit: the register dequantizer of Sections 5.2.2-5.2.3 (3-operation unpack, packed multiply-add, sign
 //     flip) and 2 * MF v_mfma_i32_16x16x64_i8.
 //   * End of a fragment: the eight waves' sums over their groups meet in LDS (double buffered: one barrier per
 //     fragment); thread t then owns four consecutive channels of one token and runs the epilogue (Eq. 5-7).
+//   * More tokens than a tile: token tiles on blockIdx.y, run side by side; the tiles of one fragment run share its
+//     weights through L2 (the host keeps token tiles x fragment runs x k-slices at one workgroup per compute unit).
 //   * K longer than 8 * J groups: k-slices on blockIdx.z.  Every slice writes its fragment sums through to the
 //     workspace; after the loop it bumps the fragments' arrival counters, and whoever arrives last at a fragment
 //     adds the slices (integer sums: exact and order independent) and runs the epilogue.  Same fence-free
