@@ -465,7 +465,9 @@ def test_linear_equals_quant_then_gemm(api, M, N, K, mode):
 @pytest.mark.parametrize("M,N,K,cfg", [(16, 256, 256, (0, 0)), (64, 512, 4096, (0, 0)), (70, 192, 640, (32, 3)),
                                        (200, 448, 1152, (128, 1)), (200, 448, 1152, (129, 2)), (300, 320, 2048, (130, 1)),
                                        (300, 320, 2048, (131, 1)), (200, 448, 1152, (131, 2)), (257, 256, 640, (131, 1)),
-                                       (64, 640, 1152, (65, 0)), (100, 384, 384, (65, 2))])
+                                       (64, 640, 1152, (65, 0)), (100, 384, 384, (65, 2)), (64, 512, 1024, (66, 0)),
+                                       (16, 3072, 512, (69, 0)), (40, 320, 1152, (70, 0)), (64, 256, 4096, (71, 0)),
+                                       (64, 256, 11008, (71, 5)), (130, 320, 2048, (71, 0)), (300, 512, 1024, (132, 1))])
 def test_per_channel_token_sum_epilogue(api, M, N, K, cfg):
     """out = acc * sx * sw - t_X * (z * sw) with t_X summed over the unquantized activations (Section 5.2.2),
     against the oracle's FP64 form.  Tolerance: the stated 1e-3 relative on the result plus the FP32 rounding
