@@ -337,8 +337,14 @@ def test_one_hot_operands_pin_fragment_maps(api):
     qx = np.zeros((M, K), dtype=np.int8)
     ks = rng.permutation(K)[:M]
     qx[np.arange(M), ks] = 1
-    acc = api.w4a8_gemm_i32(torch.from_numpy(qx).to(DEV), blob, N)
-    assert (_np(acc).astype(np.int64) == w_hat[:, ks].T).all()
+    # in every kernel family: each has its own staging, swizzle and operand order
+    for cfg in [(0, 0), (16, 0), (32, 2), (64, 0), (65, 0), (67, 0), (69, 0), (70, 0), (71, 0), (71, 1), (128, 1), (129, 1), (131, 1), (132, 1)]:
+        api.set_gemm_config(*cfg)
+        try:
+            acc = api.w4a8_gemm_i32(torch.from_numpy(qx).to(DEV), blob, N)
+        finally:
+            api.set_gemm_config(0, 0)
+        assert (_np(acc).astype(np.int64) == w_hat[:, ks].T).all(), cfg
 
 
 def test_extreme_magnitudes_fit_int32(api):
@@ -351,9 +357,15 @@ def test_extreme_magnitudes_fit_int32(api):
     blob = _pack_logical(api, code, s1, z, np.ones(N, np.float16))
     qx = torch.full((M, K), 127, dtype=torch.int8, device=DEV)
     qx[1::2] = -127
-    acc = _np(api.w4a8_gemm_i32(qx, blob, N)).astype(np.int64)
     ref = ogemm.gemm_i64(_np(qx), qq.level2_dequant(code, s1, z))
-    assert np.abs(ref).max() == 127 * 128 * K and (acc == ref).all()
+    assert np.abs(ref).max() == 127 * 128 * K
+    for cfg in [(0, 0), (64, 0), (69, 0), (71, 0), (129, 1), (132, 1)]:
+        api.set_gemm_config(*cfg)
+        try:
+            acc = _np(api.w4a8_gemm_i32(qx, blob, N)).astype(np.int64)
+        finally:
+            api.set_gemm_config(0, 0)
+        assert (acc == ref).all(), cfg
 
 
 @pytest.mark.parametrize("M,N,K", [(16, 256, 256), (70, 192, 640), (200, 448, 1152), (64, 640, 1152), (50, 384, 384)])
