@@ -773,6 +773,29 @@ def sweep(path, api, wl, dev):
             del w
             copies = max(2, -(-640_000_000 // blob0.numel()))   # rotate at least 640 MB: past L2 and Infinity Cache
             blobs = [blob0] + [blob0.clone() for _ in range(copies - 1)]
+            # what a plain streaming read of the same packed weights takes in the same regime (graph replay, rotated
+            # copies): the practical floor of the memory-bound rows of this layer
+            probe = load_read_probe()
+            sink = torch.zeros(65536, dtype=torch.int32, device=dev)
+            read_us = 1e9
+            for nwg in (256, 512):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    cs = torch.cuda.current_stream().cuda_stream
+                    for i in range(max(copies, 16)):
+                        b = blobs[i % copies]
+                        if probe.qoq_probe_read(b.data_ptr(), b.numel() // 16 * 16, sink.data_ptr(), nwg, cs) != 0:
+                            raise RuntimeError("qoq_probe_read refused its arguments")
+                graph.replay()
+                torch.cuda.synchronize()
+                for _ in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    graph.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    read_us = min(read_us, e0.elapsed_time(e1) * 1e3 / max(copies, 16))
+                del graph
             for M in ms:
                 x = wl.layer_activations(fam, name, M, 2, dev)
                 qx, sx, rowsum, _ = api.quant_act_per_token(x)
@@ -811,7 +834,7 @@ def sweep(path, api, wl, dev):
                              "tops": round(ops / us / 1e6, 2), "mfma_frac": round(ops / us / 1e6 / INT8_PEAK_TOPS, 4),
                              "gbs": round(byts / us / 1e3, 1), "hbm_frac": round(byts / us / 1e3 / HBM_PEAK_GBS, 4),
                              "roof_tops": round(roof, 1), "roof_frac": round(ops / us / 1e6 / roof, 4),
-                             "us_cache_hot": round(us_hot, 2)})
+                             "us_cache_hot": round(us_hot, 2), "weights_read_us": round(read_us, 2)})
                 del x, qx, sx, out, ws
             del blobs, blob0
             torch.cuda.empty_cache()
@@ -820,12 +843,12 @@ def sweep(path, api, wl, dev):
         for r in rows:
             f.write(json.dumps(r) + "\n")
     with open(path + ".txt", "w") as f:               # the same rows as a table
-        f.write("%-10s %-8s %4s %5s %6s %6s %9s %8s %6s %8s %6s %8s %6s %9s\n" % (
-            "family", "layer", "mode", "M", "K", "N", "us", "TOP/s", "mfma", "GB/s", "hbm", "roof", "frac", "us(hot)"))
+        f.write("%-10s %-8s %4s %5s %6s %6s %9s %8s %6s %8s %6s %8s %6s %9s %9s\n" % (
+            "family", "layer", "mode", "M", "K", "N", "us", "TOP/s", "mfma", "GB/s", "hbm", "roof", "frac", "us(hot)", "read(us)"))
         for r in rows:
-            f.write("%-10s %-8s %4d %5d %6d %6d %9.2f %8.1f %6.3f %8.1f %6.3f %8.1f %6.3f %9.2f\n" % (
+            f.write("%-10s %-8s %4d %5d %6d %6d %9.2f %8.1f %6.3f %8.1f %6.3f %8.1f %6.3f %9.2f %9.2f\n" % (
                 r["family"], r["layer"], r["mode"], r["M"], r["K"], r["N"], r["us"], r["tops"], r["mfma_frac"],
-                r["gbs"], r["hbm_frac"], r["roof_tops"], r["roof_frac"], r["us_cache_hot"]))
+                r["gbs"], r["hbm_frac"], r["roof_tops"], r["roof_frac"], r["us_cache_hot"], r["weights_read_us"]))
 
 
 if __name__ == "__main__":
