@@ -1,7 +1,7 @@
 """Writes tests/golden/gemm_acc_digests.txt: digests of the INT32 accumulators of whole layers at large token counts,
 computed by the CPU oracle alone (nothing here imports or runs the HIP path).
 
-Usage, from the repository root:  python tests/golden/make_gemm_digests.py            (about six minutes on 8 cores, 30 GB of memory for the largest layer)
+Usage, from the repository root:  python tests/golden/make_gemm_digests.py            (about a quarter of an hour on 8 cores, 30 GB of memory for the largest layer)
 
 For every (family, layer, M, mode) of CASES the seeded inputs of the workload module are generated on the CPU, the oracle
 runs the whole W4A8 path (Section 4.1 quantizers, integer GEMM, Eq. 5 / Eq. 6), and the accumulators acc[M, N] are
@@ -22,10 +22,13 @@ from oracle import gemm as ogemm                                  # noqa: E402
 from paper_2405_04532_amd import workloads as wl                  # noqa: E402  (seeded inputs only)
 
 # (family, layer, M, mode, base seed): the prefill-size rows of the benchmark configurations -- Llama-2-7B layers at
-# 1024 tokens, per-channel Llama-3-8B layers at 1024 tokens, Llama-3-70B layers at 512 tokens
+# 1024 and 4096 tokens, per-channel Llama-3-8B layers at 1024 tokens, Llama-3-70B layers at 512 and at 2048 tokens (the
+# compute-bound leg of the benchmark)
 CASES = [("llama2_7b", name, 1024, 0, 2) for name in ("qkv", "o", "gate_up", "down")] + \
         [("llama3_8b", name, 1024, 1, 4) for name in ("qkv", "gate_up", "down")] + \
-        [("llama3_70b", name, 512, 0, 3) for name in ("qkv", "o", "gate_up", "down")]
+        [("llama3_70b", name, 512, 0, 3) for name in ("qkv", "o", "gate_up", "down")] + \
+        [("llama2_7b", name, 4096, 0, 2) for name in ("qkv", "o", "gate_up", "down")] + \
+        [("llama3_70b", name, 2048, 0, 3) for name in ("qkv", "o", "gate_up", "down")]
 ROWS = 64
 OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gemm_acc_digests.txt")
 

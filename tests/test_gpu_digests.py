@@ -39,6 +39,9 @@ def test_digest_file_covers_the_prefill_rows():
     keys = set(k[:4] for k in GOLDEN)
     assert ("llama2_7b", "gate_up", 1024, 0) in keys and ("llama3_8b", "down", 1024, 1) in keys
     assert ("llama3_70b", "down", 512, 0) in keys
+    # the compute-bound leg of the benchmark and the largest Llama-2-7B rows
+    assert all(("llama3_70b", n, 2048, 0) in keys for n in ("qkv", "o", "gate_up", "down"))
+    assert all(("llama2_7b", n, 4096, 0) in keys for n in ("qkv", "o", "gate_up", "down"))
     for (family, layer, M, mode, seed), blocks in GOLDEN.items():
         assert sorted(blocks) == list(range(-(-M // ROWS))), (family, layer)
 
